@@ -1,0 +1,222 @@
+"""ctypes front end of the CPU oracle (``a3po_oracle.c``).
+
+Test infrastructure only: the product package never imports this module.  All
+floating-point results are float64.  Logits are float32 arrays or bfloat16 bit
+patterns held in uint16 arrays; per-token float inputs are widened exactly to
+float64 before the call.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "a3po_oracle.c")
+_LIB = os.path.join(_HERE, "liba3po_oracle.so")
+
+F32, BF16 = 0, 1
+
+
+class Stats(ctypes.Structure):
+    _fields_ = [("n_tokens", ctypes.c_int64), ("n_clipped", ctypes.c_int64),
+                ("n_bad_index", ctypes.c_int64), ("n_negative_staleness", ctypes.c_int64),
+                ("iw_min", ctypes.c_double), ("iw_max", ctypes.c_double)]
+
+    def as_dict(self):
+        return {k: getattr(self, k) for k, _ in self._fields_}
+
+
+def build(force: bool = False) -> str:
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        subprocess.check_call(["gcc", "-O2", "-fopenmp", "-Wall", "-shared", "-fPIC",
+                               "-o", _LIB, _SRC, "-lm"])
+    return _LIB
+
+
+_lib = None
+_P = ctypes.c_void_p
+_I64 = ctypes.c_int64
+_I32 = ctypes.c_int32
+_F64 = ctypes.c_double
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        lib = ctypes.CDLL(_LIB)
+        lib.a3po_oracle_threads.restype = ctypes.c_int
+        lib.a3po_oracle_token_logprobs.restype = None
+        lib.a3po_oracle_token_logprobs.argtypes = [_P, ctypes.c_int, _I64, _I64, _I64, _P, _P, _P, _P]
+        lib.a3po_oracle_alpha.restype = None
+        lib.a3po_oracle_alpha.argtypes = [_P, _I32, _I64, _P]
+        lib.a3po_oracle_proximal_interp.restype = None
+        lib.a3po_oracle_proximal_interp.argtypes = [_P, _P, _P, _I32, _I64, _P, _P]
+        lib.a3po_oracle_grpo_advantages.restype = ctypes.c_int
+        lib.a3po_oracle_grpo_advantages.argtypes = [_P, _I64, _I32, _F64, _P, _I64, _P, _P]
+        lib.a3po_oracle_surrogate.restype = None
+        lib.a3po_oracle_surrogate.argtypes = [_P, _P, _P, _I32, _P, _P, _F64, _F64, _I64,
+                                              _P, _P, _P, _P, _P, _P, _P, _P]
+        lib.a3po_oracle_decoupled_clip.restype = None
+        lib.a3po_oracle_decoupled_clip.argtypes = [_P, _P, _P, _P, _P, _F64, _F64, _I64,
+                                                   _P, _P, _P, _P, _P, _P, _P]
+        lib.a3po_oracle_dlogits_rows.restype = None
+        lib.a3po_oracle_dlogits_rows.argtypes = [_P, ctypes.c_int, _I64, _I64, _P, _P, _P, _P, _I64, _P]
+        lib.a3po_oracle_loss_fwd_bwd.restype = None
+        lib.a3po_oracle_loss_fwd_bwd.argtypes = [_P, ctypes.c_int, _I64, _I64, _I64, _P, _P, _P, _I32,
+                                                 _P, _P, _F64, _F64, _P, _P, _P, _P, _P, _P, _P, _P, _P]
+        _lib = lib
+    return _lib
+
+
+def threads() -> int:
+    return int(_load().a3po_oracle_threads())
+
+
+def _logits(z):
+    z = np.ascontiguousarray(z)
+    assert z.ndim == 2
+    if z.dtype == np.float32:
+        return z, F32
+    if z.dtype == np.uint16:
+        return z, BF16
+    raise TypeError("logits must be float32 or uint16 (bfloat16 bits)")
+
+
+def _f64(a):
+    return np.ascontiguousarray(np.asarray(a, dtype=np.float64))
+
+
+def _i32(a):
+    a = np.ascontiguousarray(a)
+    assert a.dtype == np.int32
+    return a
+
+
+def _u8(a):
+    a = np.ascontiguousarray(a)
+    assert a.dtype == np.uint8
+    return a
+
+
+def token_logprobs(z, y, V=None):
+    """-> dict(logp[T], lse[T], chosen_raw[T] stored bits)."""
+    z, dt = _logits(z)
+    T, ld = z.shape
+    V = ld if V is None else V
+    y = _i32(y)
+    logp = np.empty(T)
+    lse = np.empty(T)
+    raw = np.empty(T, dtype=np.uint32 if dt == F32 else np.uint16)
+    _load().a3po_oracle_token_logprobs(z.ctypes.data, dt, T, V, ld, y.ctypes.data,
+                                       logp.ctypes.data, lse.ctypes.data, raw.ctypes.data)
+    return dict(logp=logp, lse=lse, chosen_raw=raw)
+
+
+def alpha(versions, current_version):
+    v = _i32(versions)
+    out = np.empty(v.shape[0])
+    _load().a3po_oracle_alpha(v.ctypes.data, int(current_version), v.shape[0], out.ctypes.data)
+    return out
+
+
+def proximal_interp(lb, lt, versions, current_version):
+    lb, lt, v = _f64(lb), _f64(lt), _i32(versions)
+    T = v.shape[0]
+    lp = np.empty(T)
+    al = np.empty(T)
+    _load().a3po_oracle_proximal_interp(lb.ctypes.data, lt.ctypes.data, v.ctypes.data,
+                                        int(current_version), T, lp.ctypes.data, al.ctypes.data)
+    return lp, al
+
+
+def grpo_advantages(rewards, G, seq_id=None, eps_adv=1e-6):
+    R = _f64(rewards)
+    S = R.shape[0]
+    adv_seq = np.empty(S)
+    if seq_id is None:
+        rc = _load().a3po_oracle_grpo_advantages(R.ctypes.data, S, int(G), float(eps_adv), None, 0,
+                                                 adv_seq.ctypes.data, None)
+        if rc != 0:
+            raise ValueError("bad group structure")
+        return adv_seq
+    sid = _i32(seq_id)
+    adv_tok = np.empty(sid.shape[0])
+    rc = _load().a3po_oracle_grpo_advantages(R.ctypes.data, S, int(G), float(eps_adv), sid.ctypes.data,
+                                             sid.shape[0], adv_seq.ctypes.data, adv_tok.ctypes.data)
+    if rc != 0:
+        raise ValueError("bad group structure")
+    return adv_seq, adv_tok
+
+
+def surrogate(lt, lb, versions, current_version, A, mask, clip_eps, denom=0.0):
+    """Eq. 2 with Eq. 3/4 per token.  -> dict(lp, iw, r, obj, g, clipped, loss, stats)."""
+    lt, lb, A = _f64(lt), _f64(lb), _f64(A)
+    v, m = _i32(versions), _u8(mask)
+    T = v.shape[0]
+    lp, iw, r, obj, g = (np.empty(T) for _ in range(5))
+    cl = np.empty(T, dtype=np.uint8)
+    loss = ctypes.c_double(0.0)
+    st = Stats()
+    _load().a3po_oracle_surrogate(lt.ctypes.data, lb.ctypes.data, v.ctypes.data, int(current_version),
+                                  A.ctypes.data, m.ctypes.data, float(clip_eps), float(denom), T,
+                                  lp.ctypes.data, iw.ctypes.data, r.ctypes.data, obj.ctypes.data,
+                                  g.ctypes.data, cl.ctypes.data, ctypes.addressof(loss),
+                                  ctypes.addressof(st))
+    return dict(lp=lp, iw=iw, r=r, obj=obj, g=g, clipped=cl, loss=loss.value, stats=st.as_dict())
+
+
+def decoupled_clip(lt, lb, lp, A, mask, clip_eps, denom=0.0):
+    """Eq. 2 for a given proximal log-prob.  -> dict(iw, r, obj, g, clipped, loss, stats)."""
+    lt, lb, lp, A = _f64(lt), _f64(lb), _f64(lp), _f64(A)
+    m = _u8(mask)
+    T = m.shape[0]
+    iw, r, obj, g = (np.empty(T) for _ in range(4))
+    cl = np.empty(T, dtype=np.uint8)
+    loss = ctypes.c_double(0.0)
+    st = Stats()
+    _load().a3po_oracle_decoupled_clip(lt.ctypes.data, lb.ctypes.data, lp.ctypes.data, A.ctypes.data,
+                                       m.ctypes.data, float(clip_eps), float(denom), T,
+                                       iw.ctypes.data, r.ctypes.data, obj.ctypes.data, g.ctypes.data,
+                                       cl.ctypes.data, ctypes.addressof(loss), ctypes.addressof(st))
+    return dict(iw=iw, r=r, obj=obj, g=g, clipped=cl, loss=loss.value, stats=st.as_dict())
+
+
+def dlogits_rows(z, y, lse, g, rows, V=None):
+    """Dense float64 gradient rows [len(rows), V] for the listed absolute rows."""
+    z, dt = _logits(z)
+    T, ld = z.shape
+    V = ld if V is None else V
+    y, lse, g = _i32(y), _f64(lse), _f64(g)
+    rows = np.ascontiguousarray(np.asarray(rows, dtype=np.int64))
+    out = np.empty((rows.shape[0], V))
+    _load().a3po_oracle_dlogits_rows(z.ctypes.data, dt, V, ld, y.ctypes.data, lse.ctypes.data,
+                                     g.ctypes.data, rows.ctypes.data, rows.shape[0], out.ctypes.data)
+    return out
+
+
+def loss_fwd_bwd(z, y, lb, versions, current_version, A, mask, clip_eps, denom=0.0, V=None,
+                 want_dz=True):
+    """Whole path.  -> dict(logp, lse, lp, g, eff_mask, clipped, dz (or None), loss, stats)."""
+    z, dt = _logits(z)
+    T, ld = z.shape
+    V = ld if V is None else V
+    y, v, m = _i32(y), _i32(versions), _u8(mask)
+    lb, A = _f64(lb), _f64(A)
+    logp, lse, lp, g = (np.empty(T) for _ in range(4))
+    eff = np.empty(T, dtype=np.uint8)
+    cl = np.empty(T, dtype=np.uint8)
+    dz = np.empty((T, V)) if want_dz else None
+    loss = ctypes.c_double(0.0)
+    st = Stats()
+    _load().a3po_oracle_loss_fwd_bwd(z.ctypes.data, dt, T, V, ld, y.ctypes.data, lb.ctypes.data,
+                                     v.ctypes.data, int(current_version), A.ctypes.data, m.ctypes.data,
+                                     float(clip_eps), float(denom), logp.ctypes.data, lse.ctypes.data,
+                                     lp.ctypes.data, g.ctypes.data, eff.ctypes.data, cl.ctypes.data,
+                                     dz.ctypes.data if want_dz else None, ctypes.addressof(loss),
+                                     ctypes.addressof(st))
+    return dict(logp=logp, lse=lse, lp=lp, g=g, eff_mask=eff, clipped=cl, dz=dz, loss=loss.value,
+                stats=st.as_dict())
