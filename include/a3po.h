@@ -1,0 +1,152 @@
+/*
+ * a3po.h - C ABI of the MI355X (gfx950) library for the per-token policy-probability
+ * path of A-3PO training (arXiv 2512.06547): vocabulary-wide log-softmax + chosen-token
+ * gather, staleness-aware log-linear proximal interpolation, decoupled clipped surrogate
+ * with masked token mean, and the gradient written back to the logits.
+ *
+ * Conventions for every entry point
+ *  - Pointers are DEVICE pointers owned by the caller unless marked "host".  The
+ *    library never allocates, frees or synchronises; all work is enqueued on `stream`
+ *    (a hipStream_t passed as void*, NULL = the default stream) and the call returns
+ *    as soon as the launches are queued.  Outputs are valid once the stream reaches them.
+ *  - Return value: A3PO_OK (0) or a negative A3PO_E_* code for anything the host can
+ *    detect (null pointer, bad size, unknown dtype, misaligned pointer, workspace too
+ *    small, launch failure).  Nothing throws or aborts.  T == 0 is success.
+ *  - Data-dependent problems cannot be returned synchronously; they are counted in
+ *    a3po_stats (chosen id outside [0,V) => the token is treated as masked; negative
+ *    staleness => alpha = 1).
+ *  - No global state: calls are re-entrant and may be issued from several host threads
+ *    on different streams, as long as they do not share output buffers or a workspace.
+ *  - Logits are row-major [T, V] with a row stride of `ld` elements (ld >= V), float32
+ *    or bfloat16.  Row t pairs with chosen[t]; any next-token shift is the caller's.
+ *    Base pointers of logits / dlogits must be 16-byte aligned.  Rows whose byte stride
+ *    is a multiple of 16 and that fit on chip (V <= 163,840 bfloat16 / 81,920 float32)
+ *    take the single-pass kernels; everything else takes a slower multi-pass kernel
+ *    with identical results up to rounding order.
+ */
+#ifndef A3PO_H
+#define A3PO_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { A3PO_F32 = 0, A3PO_BF16 = 1 } a3po_dtype;
+
+enum {
+    A3PO_OK = 0,
+    A3PO_E_NULL = -1,        /* a required pointer is NULL                          */
+    A3PO_E_SIZE = -2,        /* T < 0, V <= 0, ld < V, G <= 0, S % G != 0, ...      */
+    A3PO_E_DTYPE = -3,       /* dtype is not A3PO_F32 / A3PO_BF16                   */
+    A3PO_E_ALIGN = -4,       /* logits / dlogits / workspace base not aligned       */
+    A3PO_E_WORKSPACE = -5,   /* workspace_bytes below a3po_workspace_bytes(...)     */
+    A3PO_E_LAUNCH = -6,      /* the HIP runtime rejected a launch                   */
+    A3PO_E_VALUE = -7        /* clip_eps not in [0,1), NaN scalar, ...              */
+};
+
+/* Run statistics of one loss call (the paper tracks importance-weight extrema and the
+ * number of clipped tokens as stability evidence, Section 4.2.2).  Device resident.
+ * iw_min / iw_max are +inf / -inf when no token enters the mean. */
+typedef struct {
+    int64_t n_tokens;             /* tokens that enter the mean: mask != 0 and id valid */
+    int64_t n_clipped;            /* of those, tokens whose clipped branch is the min   */
+    int64_t n_bad_index;          /* mask != 0 but chosen id outside [0,V)              */
+    int64_t n_negative_staleness; /* counted tokens with current_version < version      */
+    float iw_min, iw_max;         /* extrema of pi_prox/pi_behav over counted tokens    */
+} a3po_stats;
+
+enum { A3PO_WS_LOSS_FWD_BWD = 0 };
+
+/* Bytes of device workspace the given entry point needs (256-byte aligned base). */
+size_t a3po_workspace_bytes(int which, int64_t T, int64_t V, int64_t H);
+
+/* Static description of an error code. */
+const char *a3po_strerror(int code);
+
+/*
+ * log pi_theta(y_t | s_t) from logits: log-softmax over the vocabulary at temperature 1
+ * (the paper samples at temperature 1.0, Section 4.1) and a gather of the chosen token.
+ *   lse_t = log sum_j exp z[t,j],  logp_out[t] = z[t,y_t] - lse_t      (fp32 accumulate)
+ * lse_out (nullable) [T] float.  chosen_logit_out (nullable) [T] elements of dtype `dt`:
+ * the stored z[t,y_t] copied bit for bit.  A chosen id outside [0,V) gives logp 0 and a
+ * zero chosen logit; lse is still written.  Reads T*V elements once.
+ */
+int a3po_token_logprobs(const void *logits, a3po_dtype dt, int64_t T, int64_t V, int64_t ld,
+                        const int32_t *chosen, float *logp_out, float *lse_out,
+                        void *chosen_logit_out, void *stream);
+
+/*
+ * Staleness-aware proximal log-prob, Eq. 3 with the coefficient of Eq. 4 (argument order
+ * of Listing 1: behaviour log-probs, current log-probs, per-token behaviour versions,
+ * current version):
+ *   d = current_version - versions[t];  alpha = 1/d if d >= 1 else 1;
+ *   logp_prox_out[t] = alpha * logp_behav[t] + (1 - alpha) * logp_theta[t]     (fp32)
+ * alpha_out (nullable) [T] float.  All arrays [T].
+ */
+int a3po_proximal_interp(const float *logp_behav, const float *logp_theta,
+                         const int32_t *versions, int32_t current_version, int64_t T,
+                         float *logp_prox_out, float *alpha_out, void *stream);
+
+/*
+ * Group-normalised advantages (GRPO; Section 4.1 "group reward normalization"): groups are
+ * G consecutive sequences, A_s = (R_s - mean_g R) / (std_g R + eps_adv) with the population
+ * standard deviation; adv_out[t] = A_{seq_id[t]}.  rewards [S] float, S % G == 0,
+ * seq_id [T] int32 in [0,S) (an id outside gives advantage 0), adv_out [T] float.
+ */
+int a3po_grpo_advantages(const float *rewards, int64_t S, int32_t G, float eps_adv,
+                         const int32_t *seq_id, int64_t T, float *adv_out, void *stream);
+
+/*
+ * The fused path: token log-probs, Eq. 4 / Eq. 3 proximal log-prob, the decoupled clipped
+ * objective of Eq. 2 with a masked token mean, and the gradient of the loss with respect to
+ * the logits, reading each live row once and writing each gradient row once.
+ *
+ *   lt = log pi_theta (as above), lp = alpha lb + (1-alpha) lt (held fixed: the proximal
+ *   policy is a frozen anchor, Section 2.2), iw = exp(lp - lb), r = exp(lt - lp),
+ *   obj = iw * min(r A, clip(r, 1-eps, 1+eps) A),   loss = -(1/N) sum_t m_t obj_t,
+ *   N = denom if denom > 0 else the number of counted tokens; N == 0 => loss 0, dlogits 0.
+ *   g_t = -(m_t/N) iw A r if the un-clipped branch is the min (ties included) else 0,
+ *   dlogits[t,j] = g_t * ([j == y_t] - exp(z[t,j] - lse_t)).
+ *
+ * logits / dlogits: dtype `dt`, stride ld; dlogits may alias logits exactly (in place),
+ * any other overlap is undefined.  Rows that are masked, have an invalid id, are clipped or
+ * have A == 0 get an all-zero gradient row; masked / invalid rows are not read and get
+ * logp_out = logp_prox_out = 0.  Padding columns V..ld-1 are neither read nor written.
+ * chosen, versions [T] int32; logp_behav, advantages [T] float; loss_mask [T] uint8.
+ * logp_out [T], logp_prox_out [T] (nullable), loss_out [1], stats_out (nullable): device.
+ * workspace: a3po_workspace_bytes(A3PO_WS_LOSS_FWD_BWD, T, V, 0) bytes, 256-byte aligned,
+ * private to the call until the stream has passed it.  The loss is reduced in a fixed order:
+ * identical inputs give bit-identical outputs.
+ */
+int a3po_loss_fwd_bwd(const void *logits, a3po_dtype dt, int64_t T, int64_t V, int64_t ld,
+                      const int32_t *chosen, const float *logp_behav,
+                      const int32_t *versions, int32_t current_version,
+                      const float *advantages, const uint8_t *loss_mask,
+                      float clip_eps, float denom,
+                      void *dlogits, float *logp_out, float *logp_prox_out,
+                      float *loss_out, a3po_stats *stats_out,
+                      void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Same as a3po_loss_fwd_bwd, and additionally records two caller-created hipEvent_t
+ * (passed as void*, either may be NULL) on `stream` immediately before and after the
+ * vocabulary-wide row kernel, so that a caller can time that kernel alone without a
+ * profiler.  The events are only recorded, never waited on.
+ */
+int a3po_loss_fwd_bwd_events(const void *logits, a3po_dtype dt, int64_t T, int64_t V, int64_t ld,
+                             const int32_t *chosen, const float *logp_behav,
+                             const int32_t *versions, int32_t current_version,
+                             const float *advantages, const uint8_t *loss_mask,
+                             float clip_eps, float denom,
+                             void *dlogits, float *logp_out, float *logp_prox_out,
+                             float *loss_out, a3po_stats *stats_out,
+                             void *workspace, size_t workspace_bytes, void *stream,
+                             void *event_before_rows, void *event_after_rows);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* A3PO_H */

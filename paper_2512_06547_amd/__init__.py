@@ -1,0 +1,20 @@
+"""MI355X (gfx950) library for the per-token policy-probability path of A-3PO training.
+
+The compute lives in ``liba3po.so`` (HIP kernels behind the C ABI of ``include/a3po.h``);
+this package only marshals arguments.  PyTorch is used for device memory and streams.
+"""
+from .binding import (  # noqa: F401
+    A3PO_BF16,
+    A3PO_F32,
+    A3poError,
+    STATS_DTYPE,
+    grpo_advantages,
+    lib,
+    lib_path,
+    loss_fwd_bwd,
+    proximal_interp,
+    stats_to_dict,
+    strerror,
+    token_logprobs,
+    workspace_bytes,
+)

@@ -1,0 +1,195 @@
+"""ctypes binding of liba3po.so: same names as the C entry points, argument marshalling only.
+
+Every function takes torch tensors that already live on the GPU, passes their device
+pointers and the current HIP stream to the C ABI, and returns torch tensors.  There is no
+fallback: if the shared library is missing, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import numpy as np
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_PKG, "liba3po.so")
+
+A3PO_F32, A3PO_BF16 = 0, 1
+A3PO_WS_LOSS_FWD_BWD = 0
+
+# layout of a3po_stats (include/a3po.h)
+STATS_DTYPE = np.dtype([("n_tokens", "<i8"), ("n_clipped", "<i8"), ("n_bad_index", "<i8"),
+                        ("n_negative_staleness", "<i8"), ("iw_min", "<f4"), ("iw_max", "<f4")])
+
+_P, _I64, _I32, _F32, _SZ = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.c_float, ctypes.c_size_t
+
+_SIGNATURES = {
+    "a3po_workspace_bytes": (_SZ, [ctypes.c_int, _I64, _I64, _I64]),
+    "a3po_strerror": (ctypes.c_char_p, [ctypes.c_int]),
+    "a3po_token_logprobs": (ctypes.c_int, [_P, ctypes.c_int, _I64, _I64, _I64, _P, _P, _P, _P, _P]),
+    "a3po_proximal_interp": (ctypes.c_int, [_P, _P, _P, _I32, _I64, _P, _P, _P]),
+    "a3po_grpo_advantages": (ctypes.c_int, [_P, _I64, _I32, _F32, _P, _I64, _P, _P]),
+    "a3po_loss_fwd_bwd": (ctypes.c_int, [_P, ctypes.c_int, _I64, _I64, _I64, _P, _P, _P, _I32, _P, _P, _F32, _F32,
+                                         _P, _P, _P, _P, _P, _P, _SZ, _P]),
+    "a3po_loss_fwd_bwd_events": (ctypes.c_int, [_P, ctypes.c_int, _I64, _I64, _I64, _P, _P, _P, _I32, _P, _P, _F32,
+                                                _F32, _P, _P, _P, _P, _P, _P, _SZ, _P, _P, _P]),
+}
+
+_lib = None
+
+
+class A3poError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        super().__init__(f"{where}: {strerror(code)} ({code})")
+
+
+def lib_path() -> str:
+    return _LIB_PATH
+
+
+def lib() -> ctypes.CDLL:
+    """The loaded shared library; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise FileNotFoundError(
+                f"{_LIB_PATH} is missing: build it with `python -m paper_2512_06547_amd.build` "
+                "(there is no fallback path)")
+        handle = ctypes.CDLL(_LIB_PATH)
+        for name, (res, args) in _SIGNATURES.items():
+            fn = getattr(handle, name)
+            fn.restype, fn.argtypes = res, args
+        _lib = handle
+    return _lib
+
+
+def strerror(code: int) -> str:
+    return lib().a3po_strerror(int(code)).decode()
+
+
+def _check(rc: int, where: str) -> None:
+    if rc != 0:
+        raise A3poError(rc, where)
+
+
+def _torch():
+    import torch
+    return torch
+
+
+def _stream() -> int:
+    return _torch().cuda.current_stream().cuda_stream
+
+
+def _ptr(t) -> int | None:
+    return None if t is None else t.data_ptr()
+
+
+def _logits_meta(logits, V):
+    torch = _torch()
+    assert logits.is_cuda and logits.dim() == 2 and logits.stride(1) == 1, "logits must be a row-major CUDA matrix"
+    if logits.dtype == torch.float32:
+        dt = A3PO_F32
+    elif logits.dtype == torch.bfloat16:
+        dt = A3PO_BF16
+    else:
+        raise TypeError("logits must be float32 or bfloat16")
+    T = logits.shape[0]
+    ld = logits.stride(0) if T > 1 else max(logits.stride(0), logits.shape[1])
+    V = logits.shape[1] if V is None else int(V)
+    return dt, T, V, ld
+
+
+def _vec(t, dtype, n, name):
+    assert t.is_cuda and t.dtype == dtype and t.is_contiguous() and t.numel() == n, f"{name}: need contiguous {dtype}[{n}] on GPU"
+    return t
+
+
+def workspace_bytes(T: int, V: int = 0, H: int = 0, which: int = A3PO_WS_LOSS_FWD_BWD) -> int:
+    return int(lib().a3po_workspace_bytes(which, T, V, H))
+
+
+def token_logprobs(logits, chosen, V=None, want_lse=True, want_chosen_logit=True):
+    """a3po_token_logprobs -> (logp[T] f32, lse[T] f32 | None, chosen_logit[T] logits.dtype | None)."""
+    torch = _torch()
+    dt, T, V, ld = _logits_meta(logits, V)
+    _vec(chosen, torch.int32, T, "chosen")
+    dev = logits.device
+    logp = torch.empty(T, dtype=torch.float32, device=dev)
+    lse = torch.empty(T, dtype=torch.float32, device=dev) if want_lse else None
+    zy = torch.empty(T, dtype=logits.dtype, device=dev) if want_chosen_logit else None
+    _check(lib().a3po_token_logprobs(_ptr(logits), dt, T, V, ld, _ptr(chosen), _ptr(logp), _ptr(lse), _ptr(zy),
+                                     _stream()), "a3po_token_logprobs")
+    return logp, lse, zy
+
+
+def proximal_interp(logp_behav, logp_theta, versions, current_version: int, want_alpha=True):
+    """a3po_proximal_interp -> (logp_prox[T] f32, alpha[T] f32 | None)."""
+    torch = _torch()
+    T = versions.numel()
+    _vec(logp_behav, torch.float32, T, "logp_behav")
+    _vec(logp_theta, torch.float32, T, "logp_theta")
+    _vec(versions, torch.int32, T, "versions")
+    lp = torch.empty(T, dtype=torch.float32, device=versions.device)
+    al = torch.empty(T, dtype=torch.float32, device=versions.device) if want_alpha else None
+    _check(lib().a3po_proximal_interp(_ptr(logp_behav), _ptr(logp_theta), _ptr(versions), int(current_version), T,
+                                      _ptr(lp), _ptr(al), _stream()), "a3po_proximal_interp")
+    return lp, al
+
+
+def grpo_advantages(rewards, G: int, seq_id, eps_adv: float = 1e-6, out=None):
+    """a3po_grpo_advantages -> adv[T] f32 (advantage of each token's sequence)."""
+    torch = _torch()
+    S, T = rewards.numel(), seq_id.numel()
+    _vec(rewards, torch.float32, S, "rewards")
+    _vec(seq_id, torch.int32, T, "seq_id")
+    adv = torch.empty(T, dtype=torch.float32, device=seq_id.device) if out is None else out
+    _check(lib().a3po_grpo_advantages(_ptr(rewards), S, int(G), float(eps_adv), _ptr(seq_id), T, _ptr(adv),
+                                      _stream()), "a3po_grpo_advantages")
+    return adv
+
+
+def loss_fwd_bwd(logits, chosen, logp_behav, versions, current_version: int, advantages, loss_mask,
+                 clip_eps: float, denom: float = 0.0, V=None, dlogits=None, workspace=None, out=None,
+                 events=None):
+    """a3po_loss_fwd_bwd (or a3po_loss_fwd_bwd_events when ``events=(start, stop)`` raw hipEvent_t handles).
+
+    dlogits: None -> a new tensor like logits; or a tensor with the same dtype and strides (may be
+    ``logits`` itself for the in-place form).  ``out`` may carry preallocated
+    logp/logp_prox/loss/stats tensors from an earlier call.  Returns a dict with dlogits, logp, logp_prox,
+    loss (1-element tensor), stats (40-byte uint8 tensor, see STATS_DTYPE) and the workspace.
+    """
+    torch = _torch()
+    dt, T, V, ld = _logits_meta(logits, V)
+    dev = logits.device
+    _vec(chosen, torch.int32, T, "chosen")
+    _vec(logp_behav, torch.float32, T, "logp_behav")
+    _vec(versions, torch.int32, T, "versions")
+    _vec(advantages, torch.float32, T, "advantages")
+    _vec(loss_mask, torch.uint8, T, "loss_mask")
+    if dlogits is None:
+        dlogits = torch.empty_strided(logits.shape, logits.stride(), dtype=logits.dtype, device=dev)
+    assert dlogits.dtype == logits.dtype and dlogits.shape == logits.shape and dlogits.stride() == logits.stride()
+    need = workspace_bytes(T, V)
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=dev)
+    out = {} if out is None else out
+    logp = out.get("logp") if out.get("logp") is not None else torch.empty(T, dtype=torch.float32, device=dev)
+    prox = out.get("logp_prox") if out.get("logp_prox") is not None else torch.empty(T, dtype=torch.float32, device=dev)
+    loss = out.get("loss") if out.get("loss") is not None else torch.empty(1, dtype=torch.float32, device=dev)
+    stats = out.get("stats") if out.get("stats") is not None else torch.empty(STATS_DTYPE.itemsize, dtype=torch.uint8, device=dev)
+    args = [_ptr(logits), dt, T, V, ld, _ptr(chosen), _ptr(logp_behav), _ptr(versions), int(current_version),
+            _ptr(advantages), _ptr(loss_mask), float(clip_eps), float(denom), _ptr(dlogits), _ptr(logp), _ptr(prox),
+            _ptr(loss), _ptr(stats), _ptr(workspace), workspace.numel(), _stream()]
+    if events is None:
+        _check(lib().a3po_loss_fwd_bwd(*args), "a3po_loss_fwd_bwd")
+    else:
+        _check(lib().a3po_loss_fwd_bwd_events(*args, events[0], events[1]), "a3po_loss_fwd_bwd_events")
+    return dict(dlogits=dlogits, logp=logp, logp_prox=prox, loss=loss, stats=stats, workspace=workspace)
+
+
+def stats_to_dict(stats_tensor) -> dict:
+    """Copies a device a3po_stats to the host (synchronises) and decodes it."""
+    rec = np.frombuffer(stats_tensor.cpu().numpy().tobytes(), dtype=STATS_DTYPE)[0]
+    return {k: rec[k].item() for k in STATS_DTYPE.names}

@@ -1,0 +1,167 @@
+// extern "C" boundary: argument validation on the host, workspace carve-up, launches.
+#include <cmath>
+
+#include "a3po.h"
+#include "a3po_common.h"
+#include "a3po_launch.h"
+
+using namespace a3po;
+
+namespace {
+
+inline size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+struct WsLayout {
+    size_t records, obj, iw, flags, total;
+};
+
+WsLayout loss_ws_layout(int64_t T)
+{
+    WsLayout l;
+    const size_t t = (size_t)(T > 0 ? T : 0);
+    l.records = kWsHeaderBytes;
+    l.obj = l.records + round_up(t * sizeof(TokenRecord), 256);
+    l.iw = l.obj + round_up(t * sizeof(float), 256);
+    l.flags = l.iw + round_up(t * sizeof(float), 256);
+    l.total = l.flags + round_up(t, 256);
+    return l;
+}
+
+inline bool aligned(const void *p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+
+int check_logits(const void *logits, int dt, int64_t T, int64_t V, int64_t ld)
+{
+    if (dt != A3PO_F32 && dt != A3PO_BF16) return A3PO_E_DTYPE;
+    if (T < 0 || V <= 0 || ld < V || V > (int64_t)0x7FFFFFFF) return A3PO_E_SIZE;
+    if (T > 0 && !logits) return A3PO_E_NULL;
+    if (!aligned(logits, 16)) return A3PO_E_ALIGN;
+    return A3PO_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t a3po_workspace_bytes(int which, int64_t T, int64_t V, int64_t H)
+{
+    (void)V;
+    (void)H;
+    if (which == A3PO_WS_LOSS_FWD_BWD) return loss_ws_layout(T).total;
+    return 0;
+}
+
+const char *a3po_strerror(int code)
+{
+    switch (code) {
+        case A3PO_OK: return "success";
+        case A3PO_E_NULL: return "a required pointer is NULL";
+        case A3PO_E_SIZE: return "invalid size (T < 0, V <= 0, ld < V, or bad group structure)";
+        case A3PO_E_DTYPE: return "unsupported dtype";
+        case A3PO_E_ALIGN: return "pointer is not sufficiently aligned";
+        case A3PO_E_WORKSPACE: return "workspace is missing or too small";
+        case A3PO_E_LAUNCH: return "HIP rejected a kernel launch";
+        case A3PO_E_VALUE: return "scalar argument out of range";
+        default: return "unknown a3po error code";
+    }
+}
+
+int a3po_token_logprobs(const void *logits, a3po_dtype dt, int64_t T, int64_t V, int64_t ld, const int32_t *chosen,
+                        float *logp_out, float *lse_out, void *chosen_logit_out, void *stream)
+{
+    if (int rc = check_logits(logits, (int)dt, T, V, ld)) return rc;
+    if (T == 0) return A3PO_OK;
+    if (!chosen || !logp_out) return A3PO_E_NULL;
+    const hipError_t e = launch_token_logprobs(logits, (int)dt, T, V, ld, chosen, logp_out, lse_out, chosen_logit_out,
+                                               static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? A3PO_OK : A3PO_E_LAUNCH;
+}
+
+int a3po_proximal_interp(const float *logp_behav, const float *logp_theta, const int32_t *versions,
+                         int32_t current_version, int64_t T, float *logp_prox_out, float *alpha_out, void *stream)
+{
+    if (T < 0) return A3PO_E_SIZE;
+    if (T == 0) return A3PO_OK;
+    if (!logp_behav || !logp_theta || !versions || !logp_prox_out) return A3PO_E_NULL;
+    const hipError_t e = launch_proximal_interp(logp_behav, logp_theta, versions, current_version, T, logp_prox_out,
+                                                alpha_out, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? A3PO_OK : A3PO_E_LAUNCH;
+}
+
+int a3po_grpo_advantages(const float *rewards, int64_t S, int32_t G, float eps_adv, const int32_t *seq_id, int64_t T,
+                         float *adv_out, void *stream)
+{
+    if (T < 0 || S < 0 || G <= 0 || S % G != 0) return A3PO_E_SIZE;
+    if (!(eps_adv >= 0.0f)) return A3PO_E_VALUE;
+    if (T == 0) return A3PO_OK;
+    if (!rewards || !seq_id || !adv_out) return A3PO_E_NULL;
+    const hipError_t e =
+        launch_grpo_advantages(rewards, S, G, eps_adv, seq_id, T, adv_out, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? A3PO_OK : A3PO_E_LAUNCH;
+}
+
+int a3po_loss_fwd_bwd_events(const void *logits, a3po_dtype dt, int64_t T, int64_t V, int64_t ld,
+                             const int32_t *chosen, const float *logp_behav, const int32_t *versions,
+                             int32_t current_version, const float *advantages, const uint8_t *loss_mask,
+                             float clip_eps, float denom, void *dlogits, float *logp_out, float *logp_prox_out,
+                             float *loss_out, a3po_stats *stats_out, void *workspace, size_t workspace_bytes,
+                             void *stream, void *event_before_rows, void *event_after_rows)
+{
+    if (int rc = check_logits(logits, (int)dt, T, V, ld)) return rc;
+    if (!(clip_eps >= 0.0f && clip_eps < 1.0f) || std::isnan(denom)) return A3PO_E_VALUE;
+    if (!loss_out) return A3PO_E_NULL;
+    if (T > 0 && (!dlogits || !chosen || !logp_behav || !versions || !advantages || !loss_mask || !logp_out))
+        return A3PO_E_NULL;
+    if (!aligned(dlogits, 16)) return A3PO_E_ALIGN;
+    const WsLayout lay = loss_ws_layout(T);
+    if (!workspace || workspace_bytes < lay.total) return A3PO_E_WORKSPACE;
+    if (!aligned(workspace, 256)) return A3PO_E_ALIGN;
+
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    char *ws = static_cast<char *>(workspace);
+    LossArgs a;
+    a.z = logits;
+    a.dz = dlogits;
+    a.dt = (int)dt;
+    a.T = T;
+    a.V = V;
+    a.ld = ld;
+    a.chosen = chosen;
+    a.lb = logp_behav;
+    a.versions = versions;
+    a.current_version = current_version;
+    a.adv = advantages;
+    a.mask = loss_mask;
+    a.clip_eps = clip_eps;
+    a.denom = denom;
+    a.logp_out = logp_out;
+    a.prox_out = logp_prox_out;
+    a.loss_out = loss_out;
+    a.stats_out = stats_out;
+    a.ws_header = ws;
+    a.ws_records = reinterpret_cast<TokenRecord *>(ws + lay.records);
+    a.ws_obj = reinterpret_cast<float *>(ws + lay.obj);
+    a.ws_iw = reinterpret_cast<float *>(ws + lay.iw);
+    a.ws_flags = reinterpret_cast<uint8_t *>(ws + lay.flags);
+
+    if (launch_loss_prep(a, s) != hipSuccess) return A3PO_E_LAUNCH;
+    if (event_before_rows && hipEventRecord(static_cast<hipEvent_t>(event_before_rows), s) != hipSuccess)
+        return A3PO_E_LAUNCH;
+    if (launch_loss_rows(a, s) != hipSuccess) return A3PO_E_LAUNCH;
+    if (event_after_rows && hipEventRecord(static_cast<hipEvent_t>(event_after_rows), s) != hipSuccess)
+        return A3PO_E_LAUNCH;
+    if (launch_loss_finish(a, s) != hipSuccess) return A3PO_E_LAUNCH;
+    return A3PO_OK;
+}
+
+int a3po_loss_fwd_bwd(const void *logits, a3po_dtype dt, int64_t T, int64_t V, int64_t ld, const int32_t *chosen,
+                      const float *logp_behav, const int32_t *versions, int32_t current_version,
+                      const float *advantages, const uint8_t *loss_mask, float clip_eps, float denom, void *dlogits,
+                      float *logp_out, float *logp_prox_out, float *loss_out, a3po_stats *stats_out, void *workspace,
+                      size_t workspace_bytes, void *stream)
+{
+    return a3po_loss_fwd_bwd_events(logits, dt, T, V, ld, chosen, logp_behav, versions, current_version, advantages,
+                                    loss_mask, clip_eps, denom, dlogits, logp_out, logp_prox_out, loss_out, stats_out,
+                                    workspace, workspace_bytes, stream, nullptr, nullptr);
+}
+
+}  // extern "C"

@@ -1,0 +1,200 @@
+// Device-side helpers shared by the gfx950 kernels: element packing, wave/block
+// reductions for 64-wide wavefronts, and the per-token A-3PO arithmetic.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "a3po.h"
+
+namespace a3po {
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+constexpr float kNegFloor = -1.0e30f;  // running-max seed; logits are assumed above this
+constexpr int kWave = 64;
+
+struct F32 {
+    using scalar = float;
+    static constexpr int kBytes = 4;
+    static constexpr int kPerVec = 4;  // elements per 16-byte vector
+};
+struct Bf16 {
+    using scalar = uint16_t;
+    static constexpr int kBytes = 2;
+    static constexpr int kPerVec = 8;
+};
+
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ float exp2_hw(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// two floats -> packed bfloat16 pair, round to nearest even (lo in bits 0..15)
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
+{
+    f32x2_t f = {lo, hi};
+    bf16x2_t b = __builtin_convertvector(f, bf16x2_t);
+    return __builtin_bit_cast(uint32_t, b);
+}
+
+__device__ __forceinline__ float bf16_bits_to_float(uint32_t bits16) { return __uint_as_float(bits16 << 16); }
+
+template <typename DT>
+__device__ __forceinline__ uint4 neg_inf_vec()
+{
+    if constexpr (DT::kBytes == 4) return make_uint4(0xFF800000u, 0xFF800000u, 0xFF800000u, 0xFF800000u);
+    else return make_uint4(0xFF80FF80u, 0xFF80FF80u, 0xFF80FF80u, 0xFF80FF80u);
+}
+
+// widen one 16-byte vector to DT::kPerVec floats (exact)
+template <typename DT>
+__device__ __forceinline__ void unpack(const uint4 &v, float *f)
+{
+    if constexpr (DT::kBytes == 4) {
+        f[0] = __uint_as_float(v.x); f[1] = __uint_as_float(v.y);
+        f[2] = __uint_as_float(v.z); f[3] = __uint_as_float(v.w);
+    } else {
+        f[0] = __uint_as_float(v.x << 16); f[1] = __uint_as_float(v.x & 0xFFFF0000u);
+        f[2] = __uint_as_float(v.y << 16); f[3] = __uint_as_float(v.y & 0xFFFF0000u);
+        f[4] = __uint_as_float(v.z << 16); f[5] = __uint_as_float(v.z & 0xFFFF0000u);
+        f[6] = __uint_as_float(v.w << 16); f[7] = __uint_as_float(v.w & 0xFFFF0000u);
+    }
+}
+
+template <typename DT>
+__device__ __forceinline__ uint4 pack(const float *f)
+{
+    if constexpr (DT::kBytes == 4) {
+        return make_uint4(__float_as_uint(f[0]), __float_as_uint(f[1]), __float_as_uint(f[2]), __float_as_uint(f[3]));
+    } else {
+        return make_uint4(pack_bf16x2(f[0], f[1]), pack_bf16x2(f[2], f[3]),
+                          pack_bf16x2(f[4], f[5]), pack_bf16x2(f[6], f[7]));
+    }
+}
+
+// one element (index e) of a row, widened exactly
+template <typename DT>
+__device__ __forceinline__ float load_elem(const void *row, int64_t e)
+{
+    if constexpr (DT::kBytes == 4) return reinterpret_cast<const float *>(row)[e];
+    else return bf16_bits_to_float(reinterpret_cast<const uint16_t *>(row)[e]);
+}
+
+// stored bits of one element, zero-extended; raw_to_float widens them exactly
+template <typename DT>
+__device__ __forceinline__ uint32_t load_raw(const void *row, int64_t e)
+{
+    if constexpr (DT::kBytes == 4) return reinterpret_cast<const uint32_t *>(row)[e];
+    else return reinterpret_cast<const uint16_t *>(row)[e];
+}
+
+template <typename DT>
+__device__ __forceinline__ float raw_to_float(uint32_t bits)
+{
+    if constexpr (DT::kBytes == 4) return __uint_as_float(bits);
+    else return __uint_as_float(bits << 16);
+}
+
+template <typename DT>
+__device__ __forceinline__ void store_elem(void *row, int64_t e, float v)
+{
+    if constexpr (DT::kBytes == 4) reinterpret_cast<float *>(row)[e] = v;
+    else reinterpret_cast<uint16_t *>(row)[e] = (uint16_t)(pack_bf16x2(v, 0.0f) & 0xFFFFu);
+}
+
+// ---- (max, sum) pairs of an online log-sum-exp:  sum_j exp(z_j) = s * exp(m) ----------------
+struct MaxSum {
+    float m, s;
+};
+
+__device__ __forceinline__ MaxSum combine(MaxSum a, MaxSum b)
+{
+    const float m = fmaxf(a.m, b.m);
+    MaxSum o;
+    o.m = m;
+    o.s = a.s * exp2_hw((a.m - m) * kLog2e) + b.s * exp2_hw((b.m - m) * kLog2e);
+    return o;
+}
+
+__device__ __forceinline__ MaxSum wave_reduce(MaxSum v)
+{
+#pragma unroll
+    for (int off = kWave / 2; off > 0; off >>= 1) {
+        MaxSum o;
+        o.m = __shfl_xor(v.m, off, kWave);
+        o.s = __shfl_xor(v.s, off, kWave);
+        v = combine(v, o);
+    }
+    return v;
+}
+
+// Folds DT::kPerVec elements into a thread's running (m, s).
+template <int N>
+__device__ __forceinline__ void fold(MaxSum &acc, const float *f)
+{
+    float vmax = f[0];
+#pragma unroll
+    for (int e = 1; e < N; ++e) vmax = fmaxf(vmax, f[e]);
+    const float m_new = fmaxf(acc.m, vmax);
+    const float nm = -m_new * kLog2e;
+    // (acc.m - m_new) first: exactly 0 when the maximum did not move, whatever its magnitude
+    float s = acc.s * exp2_hw((acc.m - m_new) * kLog2e);
+#pragma unroll
+    for (int e = 0; e < N; ++e) s += exp2_hw(fmaf(f[e], kLog2e, nm));
+    acc.m = m_new;
+    acc.s = s;
+}
+
+// ---- per-token A-3PO terms (Eq. 2 - Eq. 4 of the paper) -----------------------------------
+struct TokenTerms {
+    float alpha, lp, iw, r, obj, g;
+    bool clipped, negative_staleness;
+};
+
+// lt = log pi_theta, lb = log pi_behav.  inv_n = 1/N (0 when N == 0).
+// The ratios use the closed form of Section 3.1 (r = w^alpha, iw = w^(1-alpha), w = exp(lt-lb)),
+// which is algebraically the same as exp(lt - lp), exp(lp - lb) without the cancellation.
+__device__ __forceinline__ TokenTerms token_terms(float lt, float lb, int32_t version, int32_t current_version,
+                                                  float A, float clip_eps, float inv_n)
+{
+    TokenTerms o;
+    const int64_t d = (int64_t)current_version - (int64_t)version;
+    o.negative_staleness = d < 0;
+    o.alpha = d >= 1 ? 1.0f / (float)d : 1.0f;
+    const float one_minus = 1.0f - o.alpha;
+    o.lp = o.alpha * lb + one_minus * lt;
+    const float delta = lt - lb;
+    o.r = expf(o.alpha * delta);
+    o.iw = expf(one_minus * delta);
+    const float s1 = o.r * A;
+    const float rc = fminf(fmaxf(o.r, 1.0f - clip_eps), 1.0f + clip_eps);
+    const float s2 = rc * A;
+    o.clipped = s2 < s1;
+    o.obj = o.iw * (o.clipped ? s2 : s1);
+    o.g = o.clipped ? 0.0f : -inv_n * o.iw * A * o.r;
+    return o;
+}
+
+// flag bits stored per token in the workspace
+enum : uint8_t { kFlagCounted = 1, kFlagClipped = 2, kFlagNegStale = 4 };
+
+// Per-token inputs packed by the prep kernel so that the row kernel fetches them with one
+// 16-byte scalar load.  y = -1 marks a token that does not enter the loss (masked, or a
+// chosen id outside the vocabulary).
+struct alignas(16) TokenRecord {
+    int32_t y, ver;
+    float lb, A;
+};
+
+// Workspace header written by the prep kernel, read by the row kernel and the finish kernel.
+struct WsHeader {
+    float inv_n;        // 1/N, or 0 when N == 0
+    float n_as_float;   // N
+    int64_t n_counted;  // tokens with mask != 0 and a valid id
+    int64_t n_bad;      // tokens with mask != 0 and an invalid id
+};
+
+constexpr size_t kWsHeaderBytes = 256;
+
+}  // namespace a3po

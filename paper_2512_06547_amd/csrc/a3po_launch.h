@@ -1,0 +1,52 @@
+// Host-side launch interface between the C ABI (a3po_api.hip) and the kernel files.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "a3po.h"
+
+namespace a3po {
+
+struct TokenRecord;
+
+struct LossArgs {
+    const void *z;
+    void *dz;
+    int dt;  // a3po_dtype
+    int64_t T, V, ld;
+    const int32_t *chosen;
+    const float *lb;
+    const int32_t *versions;
+    int32_t current_version;
+    const float *adv;
+    const uint8_t *mask;
+    float clip_eps;
+    float denom;
+    float *logp_out;
+    float *prox_out;  // nullable
+    float *loss_out;
+    a3po_stats *stats_out;  // nullable
+    // workspace carve-up
+    void *ws_header;
+    TokenRecord *ws_records;  // [T], written by the prep kernel
+    float *ws_obj;
+    float *ws_iw;
+    uint8_t *ws_flags;
+};
+
+// true when the single-pass register-resident kernel can take these rows
+bool rows_fit_on_chip(int dt, int64_t V, int64_t ld, const void *z, const void *dz);
+
+hipError_t launch_loss_prep(const LossArgs &a, hipStream_t s);
+hipError_t launch_loss_rows(const LossArgs &a, hipStream_t s);
+hipError_t launch_loss_finish(const LossArgs &a, hipStream_t s);
+
+hipError_t launch_token_logprobs(const void *z, int dt, int64_t T, int64_t V, int64_t ld, const int32_t *chosen,
+                                 float *logp, float *lse, void *chosen_logit, hipStream_t s);
+hipError_t launch_proximal_interp(const float *lb, const float *lt, const int32_t *versions, int32_t current_version,
+                                  int64_t T, float *lp, float *alpha, hipStream_t s);
+hipError_t launch_grpo_advantages(const float *rewards, int64_t S, int32_t G, float eps_adv, const int32_t *seq_id,
+                                  int64_t T, float *adv, hipStream_t s);
+
+}  // namespace a3po

@@ -1,0 +1,191 @@
+// Per-token kernels (O(T) work): mask count before the row kernel, fixed-order loss and
+// statistics reduction after it, the stand-alone proximal interpolation, GRPO advantages.
+#include "a3po_common.h"
+#include "a3po_launch.h"
+
+namespace a3po {
+
+constexpr int kTokThreads = 1024;
+constexpr int kTokWaves = kTokThreads / kWave;
+
+// N = number of tokens with mask != 0 and a valid chosen id; header gets 1/N (or 1/denom).
+// Also packs each token's inputs into one 16-byte record for the row kernel (y = -1 when the
+// token does not enter the loss).
+__global__ __launch_bounds__(kTokThreads) void loss_prep_kernel(const int32_t *chosen, const uint8_t *mask,
+                                                                const float *lb, const int32_t *versions,
+                                                                const float *adv, int64_t T, int64_t V, float denom,
+                                                                WsHeader *hdr, TokenRecord *records)
+{
+    __shared__ long long s_cnt[kTokWaves], s_bad[kTokWaves];
+    long long cnt = 0, bad = 0;
+    for (int64_t t = threadIdx.x; t < T; t += kTokThreads) {
+        const bool m = mask[t] != 0;
+        const int32_t y = chosen[t];
+        const bool ok = y >= 0 && (int64_t)y < V;
+        cnt += (m && ok) ? 1 : 0;
+        bad += (m && !ok) ? 1 : 0;
+        TokenRecord r;
+        r.y = (m && ok) ? y : -1;
+        r.ver = versions[t];
+        r.lb = lb[t];
+        r.A = adv[t];
+        records[t] = r;
+    }
+#pragma unroll
+    for (int off = kWave / 2; off > 0; off >>= 1) {
+        cnt += __shfl_xor(cnt, off, kWave);
+        bad += __shfl_xor(bad, off, kWave);
+    }
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+    if (lane == 0) {
+        s_cnt[wave] = cnt;
+        s_bad[wave] = bad;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        long long c = 0, b = 0;
+        for (int w = 0; w < kTokWaves; ++w) {
+            c += s_cnt[w];
+            b += s_bad[w];
+        }
+        const float n = denom > 0.0f ? denom : (float)c;
+        hdr->inv_n = n > 0.0f ? 1.0f / n : 0.0f;
+        hdr->n_as_float = n;
+        hdr->n_counted = c;
+        hdr->n_bad = b;
+    }
+}
+
+// loss = -(1/N) sum over counted tokens of obj, accumulated in double in a fixed order
+// (thread-strided partials, then a fixed tree), so repeated runs agree bit for bit.
+__global__ __launch_bounds__(kTokThreads) void loss_finish_kernel(const float *obj, const float *iw, const uint8_t *flags,
+                                                                  int64_t T, const WsHeader *hdr, float *loss_out,
+                                                                  a3po_stats *stats)
+{
+    __shared__ double s_sum[kTokWaves];
+    __shared__ long long s_clip[kTokWaves], s_neg[kTokWaves];
+    __shared__ float s_min[kTokWaves], s_max[kTokWaves];
+    double sum = 0.0;
+    long long clip = 0, neg = 0;
+    float lo = INFINITY, hi = -INFINITY;
+    for (int64_t t = threadIdx.x; t < T; t += kTokThreads) {
+        const uint8_t f = flags[t];
+        if (f & kFlagCounted) {
+            sum += (double)obj[t];
+            clip += (f & kFlagClipped) ? 1 : 0;
+            neg += (f & kFlagNegStale) ? 1 : 0;
+            const float w = iw[t];
+            lo = fminf(lo, w);
+            hi = fmaxf(hi, w);
+        }
+    }
+#pragma unroll
+    for (int off = kWave / 2; off > 0; off >>= 1) {
+        sum += __shfl_xor(sum, off, kWave);
+        clip += __shfl_xor(clip, off, kWave);
+        neg += __shfl_xor(neg, off, kWave);
+        lo = fminf(lo, __shfl_xor(lo, off, kWave));
+        hi = fmaxf(hi, __shfl_xor(hi, off, kWave));
+    }
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+    if (lane == 0) {
+        s_sum[wave] = sum;
+        s_clip[wave] = clip;
+        s_neg[wave] = neg;
+        s_min[wave] = lo;
+        s_max[wave] = hi;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        double S = 0.0;
+        long long c = 0, n = 0;
+        float mn = INFINITY, mx = -INFINITY;
+        for (int w = 0; w < kTokWaves; ++w) {
+            S += s_sum[w];
+            c += s_clip[w];
+            n += s_neg[w];
+            mn = fminf(mn, s_min[w]);
+            mx = fmaxf(mx, s_max[w]);
+        }
+        *loss_out = (float)(-(S * (double)hdr->inv_n));
+        if (stats) {
+            stats->n_tokens = hdr->n_counted;
+            stats->n_clipped = c;
+            stats->n_bad_index = hdr->n_bad;
+            stats->n_negative_staleness = n;
+            stats->iw_min = mn;
+            stats->iw_max = mx;
+        }
+    }
+}
+
+// Eq. 3 with the coefficient of Eq. 4, element-wise.
+__global__ void proximal_interp_kernel(const float *lb, const float *lt, const int32_t *versions,
+                                       int32_t current_version, int64_t T, float *lp, float *alpha_out)
+{
+    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= T) return;
+    const int64_t d = (int64_t)current_version - (int64_t)versions[t];
+    const float alpha = d >= 1 ? 1.0f / (float)d : 1.0f;
+    lp[t] = alpha * lb[t] + (1.0f - alpha) * lt[t];
+    if (alpha_out) alpha_out[t] = alpha;
+}
+
+// GRPO group-normalised advantage of the sequence each token belongs to.
+__global__ void grpo_advantages_kernel(const float *rewards, int64_t S, int32_t G, float eps_adv, const int32_t *seq_id,
+                                       int64_t T, float *adv)
+{
+    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= T) return;
+    const int32_t s = seq_id[t];
+    if (s < 0 || (int64_t)s >= S) {
+        adv[t] = 0.0f;
+        return;
+    }
+    const int64_t g0 = ((int64_t)s / G) * G;
+    double mu = 0.0;
+    for (int32_t k = 0; k < G; ++k) mu += (double)rewards[g0 + k];
+    mu /= (double)G;
+    double var = 0.0;
+    for (int32_t k = 0; k < G; ++k) {
+        const double c = (double)rewards[g0 + k] - mu;
+        var += c * c;
+    }
+    var /= (double)G;
+    adv[t] = (float)(((double)rewards[s] - mu) / (sqrt(var) + (double)eps_adv));
+}
+
+hipError_t launch_loss_prep(const LossArgs &a, hipStream_t s)
+{
+    hipLaunchKernelGGL(loss_prep_kernel, dim3(1), dim3(kTokThreads), 0, s, a.chosen, a.mask, a.lb, a.versions, a.adv,
+                       a.T, a.V, a.denom, reinterpret_cast<WsHeader *>(a.ws_header), a.ws_records);
+    return hipGetLastError();
+}
+
+hipError_t launch_loss_finish(const LossArgs &a, hipStream_t s)
+{
+    hipLaunchKernelGGL(loss_finish_kernel, dim3(1), dim3(kTokThreads), 0, s, a.ws_obj, a.ws_iw, a.ws_flags, a.T,
+                       reinterpret_cast<const WsHeader *>(a.ws_header), a.loss_out, a.stats_out);
+    return hipGetLastError();
+}
+
+hipError_t launch_proximal_interp(const float *lb, const float *lt, const int32_t *versions, int32_t current_version,
+                                  int64_t T, float *lp, float *alpha, hipStream_t s)
+{
+    if (T == 0) return hipSuccess;
+    const unsigned grid = (unsigned)((T + 255) / 256);
+    hipLaunchKernelGGL(proximal_interp_kernel, dim3(grid), dim3(256), 0, s, lb, lt, versions, current_version, T, lp,
+                       alpha);
+    return hipGetLastError();
+}
+
+hipError_t launch_grpo_advantages(const float *rewards, int64_t S, int32_t G, float eps_adv, const int32_t *seq_id,
+                                  int64_t T, float *adv, hipStream_t s)
+{
+    if (T == 0) return hipSuccess;
+    const unsigned grid = (unsigned)((T + 255) / 256);
+    hipLaunchKernelGGL(grpo_advantages_kernel, dim3(grid), dim3(256), 0, s, rewards, S, G, eps_adv, seq_id, T, adv);
+    return hipGetLastError();
+}
+
+}  // namespace a3po

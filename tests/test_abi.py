@@ -1,0 +1,93 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every symbol the
+header declares, sizes its workspace, names its error codes, and rejects bad arguments before
+any launch."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "a3po.h")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    import paper_2512_06547_amd as a3po
+    if not os.path.exists(a3po.lib_path()):
+        from paper_2512_06547_amd import build
+        build.build(force=True)
+    return a3po.lib()
+
+
+def declared_symbols():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(a3po_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_header_declares_the_expected_entry_points():
+    names = declared_symbols()
+    for must in ("a3po_token_logprobs", "a3po_proximal_interp", "a3po_loss_fwd_bwd", "a3po_grpo_advantages",
+                 "a3po_workspace_bytes", "a3po_strerror"):
+        assert must in names
+
+
+def test_library_exports_every_declared_symbol(lib):
+    for name in declared_symbols():
+        assert hasattr(lib, name), name
+
+
+def test_binding_covers_every_declared_symbol():
+    from paper_2512_06547_amd import binding
+    assert sorted(binding._SIGNATURES) == declared_symbols()
+
+
+def test_workspace_size_and_error_strings(lib):
+    import paper_2512_06547_amd as a3po
+    assert a3po.workspace_bytes(0) >= 256
+    small, big = a3po.workspace_bytes(1000, 32000), a3po.workspace_bytes(131072, 151936)
+    assert small % 256 == 0 and big % 256 == 0 and big > small
+    assert big >= 131072 * (16 + 4 + 4 + 1)
+    for code in range(-7, 1):
+        assert "unknown" not in a3po.strerror(code)
+    assert "unknown" in a3po.strerror(-99)
+
+
+def test_host_validation_rejects_bad_arguments_before_launch(lib):
+    # every call below must return at validation: no device pointer is ever dereferenced
+    fake = ctypes.c_void_p(0x1000)
+    tl = lib.a3po_token_logprobs
+    assert tl(fake, 7, 1, 8, 8, fake, fake, None, None, None) == -3          # dtype
+    assert tl(fake, 0, -1, 8, 8, fake, fake, None, None, None) == -2         # T < 0
+    assert tl(fake, 0, 1, 0, 8, fake, fake, None, None, None) == -2          # V <= 0
+    assert tl(fake, 0, 1, 9, 8, fake, fake, None, None, None) == -2          # ld < V
+    assert tl(None, 0, 1, 8, 8, fake, fake, None, None, None) == -1          # null logits
+    assert tl(ctypes.c_void_p(0x1004), 0, 1, 8, 8, fake, fake, None, None, None) == -4   # alignment
+    assert tl(fake, 0, 1, 8, 8, None, fake, None, None, None) == -1          # null chosen
+    assert tl(fake, 0, 0, 8, 8, None, None, None, None, None) == 0           # T == 0 is success
+    pi = lib.a3po_proximal_interp
+    assert pi(None, fake, fake, 1, 4, fake, None, None) == -1
+    assert pi(fake, fake, fake, 1, -4, fake, None, None) == -2
+    assert pi(None, None, None, 1, 0, None, None, None) == 0
+    ga = lib.a3po_grpo_advantages
+    assert ga(fake, 7, 4, 1e-6, fake, 10, fake, None) == -2                  # S % G != 0
+    assert ga(fake, 8, 0, 1e-6, fake, 10, fake, None) == -2
+    assert ga(fake, 8, 4, -1.0, fake, 10, fake, None) == -7
+    assert ga(None, 8, 4, 1e-6, fake, 10, fake, None) == -1
+    lf = lib.a3po_loss_fwd_bwd
+    base = [fake, 1, 4, 64, 64, fake, fake, fake, 3, fake, fake, 0.2, 0.0, fake, fake, None, fake, None,
+            ctypes.c_void_p(0x10000), 1 << 20, None]
+
+    def call(**kw):
+        a = list(base)
+        for k, v in kw.items():
+            a[int(k[1:])] = v
+        return lf(*a)
+
+    assert call(a11=1.5) == -7 and call(a11=-0.1) == -7 and call(a12=float("nan")) == -7
+    assert call(a16=None) == -1 and call(a13=None) == -1 and call(a9=None) == -1
+    assert call(a19=16) == -5 and call(a18=None) == -5
+    assert call(a18=ctypes.c_void_p(0x10010)) == -4
+    assert call(a13=ctypes.c_void_p(0x1008)) == -4
+    assert call(a1=2) == -3 and call(a4=32) == -2

@@ -1,0 +1,328 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same
+seeded inputs.  Tolerances (stated once, used everywhere):
+
+  log-probs / lse      |gpu - ref| <= 1e-5 * |ref| + 1e-5          (fp32 accumulate; both dtypes)
+  gradients, fp32      |gpu - ref| <= 1e-5 * |ref| + 1e-5 * |g_t|
+  gradients, bf16      |gpu - ref| <= 2e-2 * |ref| + 2e-2 * |g_t|   (the stated bar), and
+                       the sharper bound the arithmetic gives: one bf16 rounding of an fp32
+                       value, |gpu - ref| <= 2^-8 * |ref| + 1e-5 * |g_t|
+                       (row t of the gradient is g_t * (onehot - softmax), so |g_t| = d loss / d logp_t
+                       is the row's natural scale: every entry is at most |g_t| in magnitude)
+  loss                 |gpu - ref| <= 1e-5 * |ref| + 1e-5 * sum_t m_t |obj_t| / N
+  integers, gathers    bit exact (chosen logit, counted tokens, bad indices, negative staleness);
+                       the clip count is exact up to tokens whose ratio lies within 1e-4 (fp32
+                       logits) / 1e-3 (bf16 logits) of a clip boundary, where either branch is accepted.
+"""
+import numpy as np
+import pytest
+
+import oracle
+import synth
+
+torch = pytest.importorskip("torch")
+
+pytestmark = pytest.mark.gpu
+
+TOL_LOGP = 1e-5
+CUR = synth.CURRENT_VERSION
+
+
+@pytest.fixture(scope="module")
+def a3po():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2512_06547_amd as lib
+    lib.lib()  # raises if the HIP library is missing: no fallback
+    return lib
+
+
+def dev_logits(z_np, ld=None):
+    """numpy float32 / uint16(bf16 bits) [T, ld] -> cuda tensor view [T, V] with row stride ld."""
+    t = torch.from_numpy(z_np)
+    if z_np.dtype == np.uint16:
+        t = t.view(torch.bfloat16)
+    return t.cuda()
+
+
+def host_rows(t):
+    """cuda logits-like tensor -> float64 numpy"""
+    return t.float().cpu().numpy().astype(np.float64)
+
+
+def dz_tolerances(dtype):
+    return (1e-5, 1e-5, None) if dtype == "f32" else (2e-2, 2e-2, 2.0 ** -8)
+
+
+def assert_close_logp(gpu, ref, what):
+    gpu = np.asarray(gpu, dtype=np.float64)
+    err = np.abs(gpu - ref)
+    bound = TOL_LOGP * np.abs(ref) + TOL_LOGP
+    assert (err <= bound).all(), f"{what}: max err {err.max():.3e} at {err.argmax()}"
+
+
+def assert_close_dz(gpu_rows, ref_rows, g_rows, dtype, what):
+    rel, scale_tol, sharp = dz_tolerances(dtype)
+    scale = np.abs(np.asarray(g_rows, dtype=np.float64)).reshape(-1, 1)
+    err = np.abs(gpu_rows - ref_rows)
+    assert (err <= rel * np.abs(ref_rows) + scale_tol * scale).all(), f"{what}: max err {err.max():.3e}"
+    if sharp is not None:
+        assert (err <= sharp * np.abs(ref_rows) + 1e-5 * scale + 1e-37).all(), f"{what}: beyond one bf16 rounding"
+
+
+def make_case(w, T=None, ld=None, seed_shift=0):
+    """Inputs of workload `w` (first T tokens), oracle results included."""
+    tk = synth.token_arrays(w)
+    T = w.T if T is None else T
+    ld = w.V if ld is None else ld
+    z = synth.logit_rows(w, 0, T, tk["chosen"], ld=ld)
+    chosen = tk["chosen"][:T].copy()
+    fwd = oracle.token_logprobs(z, chosen, V=w.V)
+    lb = synth.behav_from_target(fwd["logp"], tk["noise"][:T])
+    adv_seq = oracle.grpo_advantages(tk["rewards"], w.G)
+    adv = adv_seq[tk["seq_id"][:T]].astype(np.float32)
+    return dict(w=w, T=T, ld=ld, z=z, chosen=chosen, lb=lb, versions=tk["versions"][:T].copy(),
+                adv=adv, mask=tk["mask"][:T].copy(), fwd=fwd, tk=tk)
+
+
+def run_gpu(a3po, c, denom=0.0, inplace=False, dz_fill=None):
+    z_d = dev_logits(c["z"])
+    V = c["w"].V
+    dl = z_d if inplace else None
+    if dz_fill is not None and not inplace:
+        dl = torch.full_like(z_d, dz_fill)
+    out = a3po.loss_fwd_bwd(z_d, torch.from_numpy(c["chosen"]).cuda(), torch.from_numpy(c["lb"]).cuda(),
+                            torch.from_numpy(c["versions"]).cuda(), CUR, torch.from_numpy(c["adv"]).cuda(),
+                            torch.from_numpy(c["mask"]).cuda(), c["w"].clip_eps, denom=denom, V=V, dlogits=dl)
+    torch.cuda.synchronize()
+    return out
+
+
+def check_against_oracle(a3po, c, out, denom=0.0, rows=None):
+    w, T, V = c["w"], c["T"], c["w"].V
+    ref = oracle.loss_fwd_bwd(c["z"], c["chosen"], c["lb"], c["versions"], CUR, c["adv"], c["mask"], w.clip_eps,
+                              denom=denom, V=V, want_dz=False)
+    st = a3po.stats_to_dict(out["stats"])
+    # integers and masks: exact
+    assert st["n_tokens"] == ref["stats"]["n_tokens"]
+    assert st["n_bad_index"] == ref["stats"]["n_bad_index"]
+    assert st["n_negative_staleness"] == ref["stats"]["n_negative_staleness"]
+    logp = out["logp"].cpu().numpy()
+    assert_close_logp(logp, ref["logp"], "logp")
+    assert (logp[ref["eff_mask"] == 0] == 0).all()
+    prox = out["logp_prox"].cpu().numpy()
+    assert_close_logp(prox[ref["eff_mask"] == 1], ref["lp"][ref["eff_mask"] == 1], "logp_prox")
+    # clip decisions: exact away from the boundary band
+    sur = oracle.surrogate(ref["logp"], c["lb"], c["versions"], CUR, c["adv"], ref["eff_mask"], w.clip_eps, denom)
+    tau = 1e-4 if w.dtype == "f32" else 1e-3
+    near = ((np.abs(sur["r"] - (1 + w.clip_eps)) < tau) | (np.abs(sur["r"] - (1 - w.clip_eps)) < tau)) & \
+           (ref["eff_mask"] == 1)
+    assert abs(st["n_clipped"] - ref["stats"]["n_clipped"]) <= int(near.sum())
+    if st["n_tokens"] > 0:
+        assert abs(st["iw_min"] - ref["stats"]["iw_min"]) <= 1e-5 * ref["stats"]["iw_min"] + 1e-6
+        assert abs(st["iw_max"] - ref["stats"]["iw_max"]) <= 1e-5 * ref["stats"]["iw_max"] + 1e-6
+    else:
+        assert st["iw_min"] == np.inf and st["iw_max"] == -np.inf
+    # loss
+    N = denom if denom > 0 else max(ref["stats"]["n_tokens"], 1)
+    scale = (np.abs(sur["obj"]) * ref["eff_mask"]).sum() / N
+    # tokens in the boundary band may legitimately take the other branch: widen by their obj spread
+    slack = (np.abs(sur["obj"][near]).sum() * 2 * tau / N) if near.any() else 0.0
+    loss = float(out["loss"].cpu()[0])
+    assert abs(loss - ref["loss"]) <= 1e-5 * abs(ref["loss"]) + 1e-5 * scale + slack + 1e-12, (loss, ref["loss"])
+    # gradient rows
+    rows = np.arange(T) if rows is None else np.asarray(rows)
+    dz_gpu = host_rows(out["dlogits"][torch.from_numpy(rows).cuda()])[:, :V]
+    dz_ref = oracle.dlogits_rows(c["z"], c["chosen"], ref["lse"], ref["g"], rows, V=V)
+    ok_rows = ~near[rows]
+    assert_close_dz(dz_gpu[ok_rows], dz_ref[ok_rows], ref["g"][rows][ok_rows], w.dtype, "dlogits")
+    for i in np.nonzero(~ok_rows)[0]:   # boundary band: either branch
+        g_other = 0.0 if ref["g"][rows[i]] != 0 else -(1.0 / N) * sur["iw"][rows[i]] * c["adv"][rows[i]] * sur["r"][rows[i]]
+        alt = ref["g"].copy()
+        alt[rows[i]] = g_other
+        dz_alt = oracle.dlogits_rows(c["z"], c["chosen"], ref["lse"], alt, rows[i:i + 1], V=V)
+        try:
+            assert_close_dz(dz_gpu[i:i + 1], dz_ref[i:i + 1], ref["g"][rows[i:i + 1]], w.dtype, "dlogits(band)")
+        except AssertionError:
+            assert_close_dz(dz_gpu[i:i + 1], dz_alt, alt[rows[i:i + 1]], w.dtype, "dlogits(band, other branch)")
+    # dead rows are exactly zero
+    dead = (ref["g"][rows] == 0) & ok_rows
+    assert not dz_gpu[dead].any()
+    return ref, st, int(near.sum())
+
+
+# ------------------------------------------------------------------------------------------ whole path
+
+def test_tiny_workload_fp32_every_element(a3po):
+    c = make_case(synth.WORKLOADS["tiny"])
+    out = run_gpu(a3po, c)
+    ref, st, excused = check_against_oracle(a3po, c, out)
+    assert st["n_tokens"] == int(c["mask"].sum())
+    print(f"tiny: N={st['n_tokens']} clipped={st['n_clipped']} excused={excused} loss={float(out['loss'].cpu()[0]):.6f}")
+
+
+def test_heavy_clipping_fp32(a3po):
+    # behaviour noise 0.3 with small staleness (alpha near 1 keeps the ratio wide): many tokens on
+    # each side of the clip, so both gradient branches and the clip count are exercised
+    w = synth.WORKLOADS["tiny"].scaled(noise_std=0.3, stale_max=4, S=8, L=64, G=8, len_lo=16, len_hi=64, V=8000)
+    c = make_case(w)
+    out = run_gpu(a3po, c)
+    ref, st, excused = check_against_oracle(a3po, c, out)
+    assert st["n_clipped"] > 10 and st["n_tokens"] - st["n_clipped"] > 10
+    print(f"clipping: N={st['n_tokens']} clipped={st['n_clipped']} excused={excused}")
+
+
+def test_bf16_full_vocabulary_rows_every_element(a3po):
+    # 151,936 columns: 18 full sweeps of the 1024-thread row kernel plus a 560-lane ragged sweep
+    w = synth.WORKLOADS["1p5b"].scaled(S=8, L=12, G=8, len_lo=6, len_hi=12)
+    c = make_case(w)
+    out = run_gpu(a3po, c)
+    ref, st, excused = check_against_oracle(a3po, c, out)
+    assert 0 < st["n_tokens"] < c["T"]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("V,pad", [(1, 0), (7, 1), (8, 0), (1000, 0), (1001, 7), (4099, 5), (8192, 0), (8200, 8),
+                                   (32000, 0), (32768, 64), (50257, 0), (50257, 7), (65537, 15)])
+def test_ragged_vocabularies_and_strides(a3po, dtype, V, pad):
+    # covers: single partial sweep, exact sweep multiples, ragged tail vectors, padded strides
+    # (padding columns hold a 1e30 sentinel and must be neither read nor written), and strides
+    # whose byte size is not a multiple of 16 (multi-pass kernel).
+    w = synth.WORKLOADS["tiny"].scaled(V=V, dtype=dtype, S=4, L=6, len_lo=3, len_hi=6, sigma=3.0,
+                                       boost=6.0, boost_prob=0.5, noise_std=0.15, stale_max=6)
+    c = make_case(w, ld=V + pad)
+    out = run_gpu(a3po, c, dz_fill=7.0)
+    check_against_oracle(a3po, c, out)
+    if pad:
+        assert (out["dlogits"][:, V:].float() == 7.0).all(), "padding columns were written"
+
+
+@pytest.mark.parametrize("dtype,V", [("f32", 32000), ("bf16", 151936), ("bf16", 4099), ("f32", 1001)])
+def test_in_place_gradient(a3po, dtype, V):
+    w = synth.WORKLOADS["tiny"].scaled(V=V, dtype=dtype, S=4, L=8, len_lo=4, len_hi=8, noise_std=0.1)
+    c = make_case(w)
+    sep = run_gpu(a3po, c)
+    inp = run_gpu(a3po, c, inplace=True)
+    assert torch.equal(sep["dlogits"].view(torch.uint8), inp["dlogits"].view(torch.uint8))
+    assert torch.equal(sep["logp"], inp["logp"]) and torch.equal(sep["loss"], inp["loss"])
+
+
+def test_runs_are_bit_reproducible(a3po):
+    c = make_case(synth.WORKLOADS["tiny"], T=512)
+    a, b = run_gpu(a3po, c), run_gpu(a3po, c)
+    for k in ("dlogits", "logp", "logp_prox", "loss", "stats"):
+        assert torch.equal(a[k].view(torch.uint8), b[k].view(torch.uint8)), k
+
+
+def test_caller_denominator(a3po):
+    c = make_case(synth.WORKLOADS["tiny"], T=300)
+    out = run_gpu(a3po, c, denom=1234.0)
+    check_against_oracle(a3po, c, out, denom=1234.0)
+
+
+def test_all_masked_and_empty_batch(a3po):
+    c = make_case(synth.WORKLOADS["tiny"], T=64)
+    c["mask"][:] = 0
+    out = run_gpu(a3po, c, dz_fill=3.0)
+    st = a3po.stats_to_dict(out["stats"])
+    assert st["n_tokens"] == 0 and float(out["loss"].cpu()[0]) == 0.0
+    assert not out["dlogits"].any() and not out["logp"].any()
+    assert st["iw_min"] == np.inf and st["iw_max"] == -np.inf
+    # T == 0
+    z = torch.empty((0, 128), dtype=torch.float32, device="cuda")
+    e32 = torch.empty(0, dtype=torch.int32, device="cuda")
+    ef = torch.empty(0, dtype=torch.float32, device="cuda")
+    out = a3po.loss_fwd_bwd(z, e32, ef, e32, CUR, ef, torch.empty(0, dtype=torch.uint8, device="cuda"), 0.2)
+    torch.cuda.synchronize()
+    assert float(out["loss"].cpu()[0]) == 0.0 and a3po.stats_to_dict(out["stats"])["n_tokens"] == 0
+
+
+def test_bad_indices_negative_staleness_zero_advantage(a3po):
+    c = make_case(synth.WORKLOADS["tiny"], T=96)
+    c["mask"][:] = 1
+    c["chosen"][[3, 17]] = [-1, c["w"].V]       # invalid ids: masked and counted
+    c["versions"][[5, 6, 40]] = CUR + 3           # negative staleness: alpha = 1, counted
+    c["adv"][[8, 9]] = 0.0                        # zero advantage: zero gradient row
+    out = run_gpu(a3po, c)
+    ref, st, _ = check_against_oracle(a3po, c, out)
+    assert st["n_bad_index"] == 2 and st["n_negative_staleness"] == 3 and st["n_tokens"] == 94
+    assert not out["dlogits"][[3, 17, 8, 9]].any()
+
+
+def test_zero_and_unit_staleness_give_identical_results(a3po):
+    # Eq. 4: alpha(0) = alpha(1) = 1 -> the proximal policy is the behaviour policy (standard PPO)
+    c = make_case(synth.WORKLOADS["tiny"], T=128)
+    c["versions"][:] = CUR
+    a = run_gpu(a3po, c)
+    c["versions"][:] = CUR - 1
+    b = run_gpu(a3po, c)
+    for k in ("dlogits", "logp", "logp_prox", "loss"):
+        assert torch.equal(a[k].view(torch.uint8), b[k].view(torch.uint8)), k
+    live = torch.from_numpy(c["mask"]).cuda().bool()
+    assert torch.equal(a["logp_prox"][live], torch.from_numpy(c["lb"]).cuda()[live])
+
+
+def test_huge_staleness_never_clips(a3po):
+    c = make_case(synth.WORKLOADS["tiny"], T=128)
+    c["versions"][:] = CUR - (1 << 24)
+    out = run_gpu(a3po, c)
+    assert a3po.stats_to_dict(out["stats"])["n_clipped"] == 0
+    check_against_oracle(a3po, c, out)
+
+
+# ------------------------------------------------------------------------------------------ stand-alone entry points
+
+@pytest.mark.parametrize("dtype,V,pad", [("f32", 32000, 0), ("bf16", 151936, 0), ("bf16", 5001, 3), ("f32", 77, 0),
+                                         ("bf16", 1, 0), ("f32", 262144, 0)])
+def test_token_logprobs(a3po, dtype, V, pad):
+    w = synth.WORKLOADS["tiny"].scaled(V=V, dtype=dtype, S=4, L=10, len_lo=5, len_hi=10, sigma=3.0)
+    tk = synth.token_arrays(w)
+    z = synth.logit_rows(w, 0, w.T, tk["chosen"], ld=V + pad)
+    y = tk["chosen"].copy()
+    y[1], y[2] = -3, V            # invalid ids
+    ref = oracle.token_logprobs(z, y, V=V)
+    logp, lse, zy = a3po.token_logprobs(dev_logits(z), torch.from_numpy(y).cuda(), V=V)
+    torch.cuda.synchronize()
+    assert_close_logp(lse.cpu().numpy(), ref["lse"], "lse")
+    assert_close_logp(logp.cpu().numpy(), ref["logp"], "logp")
+    raw = zy.view(torch.int32 if dtype == "f32" else torch.int16).cpu().numpy()
+    assert np.array_equal(raw.view(ref["chosen_raw"].dtype), ref["chosen_raw"]), "gather is not a bit copy"
+    assert logp[1] == 0 and logp[2] == 0
+
+
+def test_fused_logp_equals_standalone_logp_closely(a3po):
+    c = make_case(synth.WORKLOADS["tiny"], T=256)
+    out = run_gpu(a3po, c)
+    logp, _, _ = a3po.token_logprobs(dev_logits(c["z"]), torch.from_numpy(c["chosen"]).cuda())
+    live = torch.from_numpy(c["mask"]).cuda().bool()
+    assert (out["logp"][live] - logp[live]).abs().max().item() < 2e-5
+
+
+def test_proximal_interp(a3po):
+    n = 10000
+    r = np.random.default_rng(5)
+    lt = (-np.abs(r.standard_normal(n) * 4)).astype(np.float32)
+    lb = np.minimum(0, lt + r.standard_normal(n).astype(np.float32) * 0.3).astype(np.float32)
+    ver = (CUR - r.integers(-2, 20, n)).astype(np.int32)
+    lp, al = a3po.proximal_interp(torch.from_numpy(lb).cuda(), torch.from_numpy(lt).cuda(),
+                                  torch.from_numpy(ver).cuda(), CUR)
+    lp, al = lp.cpu().numpy(), al.cpu().numpy()
+    ref_lp, ref_al = oracle.proximal_interp(lb, lt, ver, CUR)
+    assert np.array_equal(al, ref_al.astype(np.float32))          # one correctly rounded reciprocal
+    assert (np.abs(lp - ref_lp) <= 1e-5 * np.abs(ref_lp) + 1e-6).all()
+    one = ref_al == 1.0
+    assert np.array_equal(lp[one], lb[one])                        # Eq. 4: d in {0,1} -> exactly log pi_behav
+    lo, hi = np.minimum(lb, lt), np.maximum(lb, lt)                # sandwich property on device outputs
+    slack = 4 * np.spacing(np.maximum(np.abs(lb), np.abs(lt)))
+    assert (lp >= lo - slack).all() and (lp <= hi + slack).all()
+
+
+def test_grpo_advantages(a3po):
+    for G, S in ((4, 4), (8, 32), (8, 16)):
+        r = np.random.default_rng(G + S)
+        R = (r.random(S) < 0.4).astype(np.float32)
+        R[:G] = 1.0                                                # a constant group -> exactly zero
+        sid = np.repeat(np.arange(S, dtype=np.int32), 7)
+        adv = a3po.grpo_advantages(torch.from_numpy(R).cuda(), G, torch.from_numpy(sid).cuda()).cpu().numpy()
+        _, ref = oracle.grpo_advantages(R, G, seq_id=sid)
+        assert np.array_equal(adv, ref.astype(np.float32))
+        assert not adv[:G * 7].any()
