@@ -1,0 +1,237 @@
+#!/usr/bin/env python3
+"""Benchmark of the A-3PO loss forward+backward hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 1p5b|8b|long|tiny]
+
+One step = one pass of the whole path over one synthetic batch already resident in HBM:
+GRPO advantages -> mask count / token records -> fused row kernel (log-softmax + gather,
+proximal interpolation, clipped surrogate, gradient rows) -> loss and statistics reduction.
+Prints ONE JSON line (see the keys below).  The CPU oracle is timed beside it on a bounded
+row sample as a reported baseline.
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E peak
+METRIC = "tokens/sec and HBM GB/s (% peak) for A-3PO loss fwd+bwd, vocab 151,936, 1 GPU"
+
+
+class HipEvents:
+    """hipEvent pairs created through the HIP runtime directly (timing of one kernel on its stream)."""
+
+    def __init__(self, n: int):
+        self.hip = ctypes.CDLL("libamdhip64.so")
+        self.hip.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
+        self.hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
+        self.hip.hipEventDestroy.argtypes = [ctypes.c_void_p]
+        self.hip.hipEventSynchronize.argtypes = [ctypes.c_void_p]
+        self.pairs = []
+        for _ in range(n):
+            a, b = ctypes.c_void_p(), ctypes.c_void_p()
+            assert self.hip.hipEventCreate(ctypes.byref(a)) == 0 and self.hip.hipEventCreate(ctypes.byref(b)) == 0
+            self.pairs.append((a, b))
+
+    def elapsed_ms(self):
+        out = []
+        for a, b in self.pairs:
+            ms = ctypes.c_float()
+            assert self.hip.hipEventSynchronize(b) == 0
+            assert self.hip.hipEventElapsedTime(ctypes.byref(ms), a, b) == 0
+            out.append(ms.value)
+        return out
+
+    def close(self):
+        for a, b in self.pairs:
+            self.hip.hipEventDestroy(a)
+            self.hip.hipEventDestroy(b)
+
+
+def build_inputs(w, torch, a3po, synth, log):
+    """Synthetic batch of workload `w`, resident on the GPU.  Behaviour log-probs follow the recipe
+    (target log-prob + noise, clamped); the target log-probs used for that come from
+    a3po_token_logprobs here (parity of that entry point is the test suite's business)."""
+    import numpy as np
+    tk = synth.token_arrays(w)
+    T, V = w.T, w.V
+    tdt = torch.float32 if w.dtype == "f32" else torch.bfloat16
+    z = torch.empty((T, V), dtype=tdt, device="cuda")
+    chunk = max(1, min(T, (1 << 30) // (V * w.elem_bytes)))
+    t0 = time.time()
+    for r0 in range(0, T, chunk):
+        n = min(chunk, T - r0)
+        rows = synth.logit_rows(w, r0, n, tk["chosen"])
+        ten = torch.from_numpy(rows)
+        z[r0:r0 + n].copy_(ten if w.dtype == "f32" else ten.view(torch.bfloat16))
+    log(f"generated {T}x{V} {w.dtype} logits in {time.time() - t0:.1f}s")
+    dev = lambda a: torch.from_numpy(a).cuda()
+    chosen = dev(tk["chosen"])
+    logp, _, _ = a3po.token_logprobs(z, chosen, want_lse=False, want_chosen_logit=False)
+    lb = torch.clamp(logp + dev(tk["noise"]), max=0.0).contiguous()
+    return dict(z=z, chosen=chosen, lb=lb, versions=dev(tk["versions"]), mask=dev(tk["mask"]),
+                rewards=dev(tk["rewards"]), seq_id=dev(tk["seq_id"]), cur=tk["current_version"], tk=tk)
+
+
+def time_steps(a3po, torch, w, b, mask, steps, warmup, dz, ws, out, adv):
+    """W untimed + K timed steps; returns (seconds for K steps, [ms of the row kernel per step])."""
+    ev = HipEvents(steps)
+
+    def step(events=None):
+        a3po.grpo_advantages(b["rewards"], w.G, b["seq_id"], out=adv)
+        a3po.loss_fwd_bwd(b["z"], b["chosen"], b["lb"], b["versions"], b["cur"], adv, mask, w.clip_eps,
+                          dlogits=dz, workspace=ws, out=out, events=events)
+
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        step(ev.pairs[i])
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    kernel_ms = ev.elapsed_ms()
+    ev.close()
+    return dt, kernel_ms
+
+
+def algorithmic_bytes(w, n_counted):
+    """Bytes the method itself must move per step: every counted row read once and its gradient row
+    written once, every other row zero-filled once, plus the per-token side arrays."""
+    row = w.V * w.elem_bytes
+    return row * (2 * n_counted + (w.T - n_counted)) + 30 * w.T
+
+
+def cpu_baseline(w, synth, oracle, rows):
+    """The oracle's whole path on the first `rows` tokens of the same workload, on the host cores."""
+    import numpy as np
+    tk = synth.token_arrays(w)
+    z = synth.logit_rows(w, 0, rows, tk["chosen"])
+    y = tk["chosen"][:rows].copy()
+    fwd = oracle.token_logprobs(z, y)                       # recipe input (not timed)
+    lb = synth.behav_from_target(fwd["logp"], tk["noise"][:rows])
+    t0 = time.perf_counter()
+    _, adv = oracle.grpo_advantages(tk["rewards"], w.G, seq_id=tk["seq_id"][:rows].copy())
+    oracle.loss_fwd_bwd(z, y, lb, tk["versions"][:rows].copy(), tk["current_version"], adv.astype(np.float32),
+                        tk["mask"][:rows].copy(), w.clip_eps, want_dz=True)
+    dt = time.perf_counter() - t0
+    return rows / dt, dt
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="1p5b")
+    ap.add_argument("--cpu-rows", type=int, default=2048, help="rows of the oracle baseline sample (0 = skip)")
+    ap.add_argument("--quiet", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    import paper_2512_06547_amd as a3po
+    import synth
+
+    log = (lambda *a: None) if args.quiet else (lambda *a: print("[bench]", *a, file=sys.stderr, flush=True))
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    a3po.lib()
+    torch.cuda.set_device(0)
+    w = synth.WORKLOADS[args.workload]
+    b = build_inputs(w, torch, a3po, synth, log)
+
+    dz = torch.empty_like(b["z"])
+    ws = torch.empty(a3po.workspace_bytes(w.T, w.V), dtype=torch.uint8, device="cuda")
+    adv = torch.empty(w.T, dtype=torch.float32, device="cuda")
+    out = {}
+    out.update(a3po.loss_fwd_bwd(b["z"], b["chosen"], b["lb"], b["versions"], b["cur"],
+                                 a3po.grpo_advantages(b["rewards"], w.G, b["seq_id"], out=adv), b["mask"],
+                                 w.clip_eps, dlogits=dz, workspace=ws))
+    torch.cuda.synchronize()
+    st = a3po.stats_to_dict(out["stats"])
+    log(f"stats: {st} loss={float(out['loss'].cpu()[0]):.6f}")
+
+    # the workload's own ragged mask: the headline
+    dt, kms = time_steps(a3po, torch, w, b, b["mask"], args.steps, args.warmup, dz, ws, out, adv)
+    kavg = sum(kms) / len(kms)
+    bytes_cfg = algorithmic_bytes(w, st["n_tokens"])
+    ach = bytes_cfg / (kavg * 1e-3) / 1e9
+    log(f"ragged mask: {dt / args.steps * 1e3:.3f} ms/step, row kernel {kavg:.3f} ms, {ach:.0f} GB/s")
+
+    # all rows counted: the 2-passes-per-row case that cannot skip anything
+    ones = torch.ones_like(b["mask"])
+    dt1, kms1 = time_steps(a3po, torch, w, b, ones, args.steps, args.warmup, dz, ws, out, adv)
+    torch.cuda.synchronize()
+    st1 = a3po.stats_to_dict(out["stats"])
+    kavg1 = sum(kms1) / len(kms1)
+    bytes_all = algorithmic_bytes(w, st1["n_tokens"])
+    ach1 = bytes_all / (kavg1 * 1e-3) / 1e9
+    log(f"all-ones mask: {dt1 / args.steps * 1e3:.3f} ms/step, row kernel {kavg1:.3f} ms, {ach1:.0f} GB/s")
+
+    # context only: a plain device copy of the same matrix (read + write), the practical ceiling
+    # of a mixed read/write stream on this machine
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    for _ in range(3):
+        dz.copy_(b["z"])
+    e0.record()
+    for _ in range(10):
+        dz.copy_(b["z"])
+    e1.record()
+    torch.cuda.synchronize()
+    copy_gbs = 2 * b["z"].numel() * w.elem_bytes * 10 / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    log(f"plain copy of the logits matrix: {copy_gbs:.0f} GB/s (read+write)")
+
+    cpu = None
+    if args.cpu_rows > 0:
+        import oracle
+        rows = min(args.cpu_rows, w.T)
+        tps, secs = cpu_baseline(w, synth, oracle, rows)
+        cpu = {"value": tps, "unit": "tokens/s", "cores": oracle.threads(), "kind": "oracle",
+               "sample": f"whole path (fwd + all gradient rows, fp64) on the first {rows} rows of the same workload, "
+                         f"{secs:.2f} s wall"}
+        log(f"oracle: {tps:.1f} tokens/s on {oracle.threads()} threads ({secs:.2f}s for {rows} rows)")
+
+    line = {
+        "metric": METRIC,
+        "value": w.T * args.steps / dt,
+        "unit": "tokens/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": dt / args.steps * 1e3,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": w.dtype,
+        "data": "synthetic",
+        "config": {"workload": f"{w.name}: {w.S} seq x {w.L} tok = {w.T} tokens, vocab {w.V}, {w.dtype} logits, "
+                               f"GRPO group {w.G}, staleness 0..{w.stale_max}, ragged mask "
+                               f"({st['n_tokens']} counted tokens), separate gradient buffer",
+                   "tokens": w.T, "vocab": w.V, "counted_tokens": st["n_tokens"], "clipped_tokens": st["n_clipped"]},
+        "roofline": {"bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": ach / HBM_PEAK_GBS, "traffic": None, "kernel": "loss_rows_kernel",
+                     "kernel_ms": kavg, "algorithmic_bytes": bytes_cfg},
+        "all_rows_counted": {"value": w.T * args.steps / dt1, "unit": "tokens/s", "ms_per_step": dt1 / args.steps * 1e3,
+                             "roofline": {"bound": "hbm", "achieved": ach1, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                                          "frac": ach1 / HBM_PEAK_GBS, "traffic": None, "kernel_ms": kavg1,
+                                          "algorithmic_bytes": bytes_all}},
+        "cpu_baseline": cpu,
+        "plain_copy_gbs": copy_gbs,
+    }
+    print(json.dumps(line), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -25,6 +25,7 @@
 #include <math.h>
 #include <stddef.h>
 #include <stdint.h>
+#include <stdlib.h>
 #include <string.h>
 
 #ifdef _OPENMP
@@ -301,9 +302,9 @@ void a3po_oracle_loss_fwd_bwd(const void *z, int dt, int64_t T, int64_t V, int64
                           denom, T, lp_out, NULL, NULL, NULL, g_out, clipped_out, loss_out, stats);
     if (stats) stats->n_bad_index = bad;
     if (dz_out) {
-        for (int64_t t = 0; t < T; ++t) {
-            const int64_t one = t;
-            a3po_oracle_dlogits_rows(z, dt, V, ld, y, lse_out, g_out, &one, 1, dz_out + t * V);
-        }
+        int64_t *all = (int64_t *)malloc((size_t)(T > 0 ? T : 1) * sizeof(int64_t));
+        for (int64_t t = 0; t < T; ++t) all[t] = t;
+        a3po_oracle_dlogits_rows(z, dt, V, ld, y, lse_out, g_out, all, T, dz_out);
+        free(all);
     }
 }

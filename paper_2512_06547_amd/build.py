@@ -13,8 +13,11 @@ LIB = os.path.join(PKG, "liba3po.so")
 SOURCES = ["a3po_api.hip", "a3po_rows.hip", "a3po_tokens.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 # packed fp32 VALU forms are switched off for every device translation unit
+# (the atomic optimizer would turn the row queue's one-lane atomic into a wave-wide scan that
+# needs its result at once; the plain atomic lets the claim stay in flight behind the row's loads)
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         "-mllvm", "-amdgpu-atomic-optimizer-strategy=None",
          "-I", os.path.join(ROOT, "include"), "-I", CSRC]
 
 

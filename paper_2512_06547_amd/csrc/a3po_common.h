@@ -196,5 +196,11 @@ struct WsHeader {
 };
 
 constexpr size_t kWsHeaderBytes = 256;
+// The row kernel's work-queue counter lives in the header block, away from the read-only fields.
+constexpr size_t kWsRowQueueOffset = 128;
+__host__ __device__ inline unsigned int *row_queue_of(void *ws_header)
+{
+    return reinterpret_cast<unsigned int *>(static_cast<char *>(ws_header) + kWsRowQueueOffset);
+}
 
 }  // namespace a3po

@@ -46,8 +46,25 @@ __device__ __forceinline__ MaxSum block_allreduce(MaxSum v, float *sm, float *ss
 // full and carry no predicate at all; only the last sweep is predicated (and holds the
 // ragged tail when V is not a multiple of the vector width).
 // Requires: 16-byte aligned bases, (ld * element size) % 16 == 0, blockDim.x == 1024.
-// Rows are dealt round-robin: row = blockIdx.x + i * gridDim.x.
+// Rows are claimed from a device-wide queue (one atomic add per row): workgroup b starts with
+// row b and then takes whatever row is next, so masked rows (cheap) and slower compute units
+// balance out by themselves.  The queue counter is zeroed by the prep kernel.
+// Loads and stores of logit rows are non-temporal: every byte is touched exactly once.
 constexpr uint32_t kSweepBytes = kRowThreads * 16;
+
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ uint4 stream_load(const char *p)
+{
+    const u32x4_t t = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t *>(p));
+    return make_uint4(t.x, t.y, t.z, t.w);
+}
+
+__device__ __forceinline__ void stream_store(char *p, const uint4 &v)
+{
+    const u32x4_t t = {v.x, v.y, v.z, v.w};
+    __builtin_nontemporal_store(t, reinterpret_cast<u32x4_t *>(p));
+}
 
 struct RowOutputs {
     float *logp, *prox, *obj, *iw;
@@ -57,12 +74,14 @@ struct RowOutputs {
 template <typename DT, int NSWEEP>
 __global__ __launch_bounds__(kRowThreads) void loss_rows_kernel(
     const void *z, void *dz, int64_t T, int64_t V, int64_t ld, const TokenRecord *__restrict__ records,
-    int32_t current_version, float clip_eps, const WsHeader *__restrict__ hdr, RowOutputs out)
+    int32_t current_version, float clip_eps, const WsHeader *__restrict__ hdr, unsigned int *row_queue,
+    RowOutputs out)
 {
     constexpr int EPV = DT::kPerVec;
     constexpr int LAST = NSWEEP - 1;
     __shared__ float red_m[2][kRowWaves];
     __shared__ float red_s[2][kRowWaves];
+    __shared__ unsigned int next_row[2];
 
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1), wave = tid / kWave;
@@ -79,21 +98,26 @@ __global__ __launch_bounds__(kRowThreads) void loss_rows_kernel(
     int parity = 0;
 
     // Per-token inputs are uniform over the workgroup and come from the packed records the
-    // prep kernel wrote (one 16-byte scalar load per row, fetched one row ahead).
+    // prep kernel wrote (one 16-byte scalar load per row, fetched as soon as the row is known).
     int64_t row = blockIdx.x;
     TokenRecord nxt = {-1, 0, 0.0f, 0.0f};
     if (row < T) nxt = records[row];
 
-    for (; row < T; row += gridDim.x) {
+    while (row < T) {
         const TokenRecord cur = nxt;
         const int32_t y = cur.y;
         const bool live = y >= 0;  // the prep kernel stores y = -1 for masked or invalid tokens
+        // thread 0 claims this workgroup's next row; the answer is shared at the row's barrier
+        unsigned int claimed = 0;
+        if (tid == 0) claimed = atomicAdd(row_queue, 1u);
+        __builtin_amdgcn_sched_barrier(0);
         char *out_row = reinterpret_cast<char *>(dz) + (size_t)row * row_bytes;
         const char *in_row = reinterpret_cast<const char *>(z) + (size_t)row * row_bytes;
 
         uint4 v[NSWEEP];
         float g = 0.0f, lse = 0.0f, zy = 0.0f;
         uint32_t zy_bits = 0;
+        int64_t next = T;
         if (live) {  // uniform over the workgroup
             // ---- issue every load of the row: the chosen logit, the partial sweep, the full sweeps ----
             // (scheduling barriers pin the issue order so that the forward pass below can
@@ -101,15 +125,13 @@ __global__ __launch_bounds__(kRowThreads) void loss_rows_kernel(
             zy_bits = load_raw<DT>(in_row, y);
             __builtin_amdgcn_sched_barrier(0);
             v[LAST] = neg_inf_vec<DT>();
-            if (last_any) v[LAST] = *reinterpret_cast<const uint4 *>(in_row + (size_t)LAST * kSweepBytes + voff);
+            if (last_any) v[LAST] = stream_load(in_row + (size_t)LAST * kSweepBytes + voff);
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int k = 0; k < LAST; ++k) {
-                v[k] = *reinterpret_cast<const uint4 *>(in_row + (size_t)k * kSweepBytes + voff);
+                v[k] = stream_load(in_row + (size_t)k * kSweepBytes + voff);
                 __builtin_amdgcn_sched_barrier(0);
             }
-            // per-token inputs of this workgroup's next row (scalar load, lands during the forward)
-            if (row + gridDim.x < T) nxt = records[row + gridDim.x];
 
             // ---- forward: online (max, sum) per thread, in the order the loads were issued ----
             MaxSum acc = {kNegFloor, 0.0f};
@@ -123,6 +145,7 @@ __global__ __launch_bounds__(kRowThreads) void loss_rows_kernel(
                 }
                 fold<EPV>(acc, f);
             }
+            if (tid == 0) next_row[parity] = claimed;  // the claim was issued before the row's loads
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int k = 0; k < LAST; ++k) {
@@ -141,7 +164,9 @@ __global__ __launch_bounds__(kRowThreads) void loss_rows_kernel(
             MaxSum tot = {red_m[parity][0], red_s[parity][0]};
 #pragma unroll
             for (int w = 1; w < kRowWaves; ++w) tot = combine(tot, MaxSum{red_m[parity][w], red_s[parity][w]});
+            const int64_t upcoming = (int64_t)gridDim.x + (int64_t)__builtin_amdgcn_readfirstlane(next_row[parity]);
             parity ^= 1;
+            if (upcoming < T) nxt = records[upcoming];  // scalar load, lands during the backward pass
 
             lse = tot.m + logf(tot.s);
             const float lt = zy - lse;
@@ -155,27 +180,33 @@ __global__ __launch_bounds__(kRowThreads) void loss_rows_kernel(
                 out.flags[row] = (uint8_t)(kFlagCounted | (tt.clipped ? kFlagClipped : 0) |
                                            (tt.negative_staleness ? kFlagNegStale : 0));
             }
+            next = upcoming;
         } else {
-            if (row + gridDim.x < T) nxt = records[row + gridDim.x];
             if (tid == 0) {
+                next_row[parity] = claimed;
                 out.logp[row] = 0.0f;
                 if (out.prox) out.prox[row] = 0.0f;
                 out.obj[row] = 0.0f;
                 out.iw[row] = 0.0f;
                 out.flags[row] = 0;
             }
+            __syncthreads();
+            next = (int64_t)gridDim.x + (int64_t)__builtin_amdgcn_readfirstlane(next_row[parity]);
+            parity ^= 1;
+            if (next < T) nxt = records[next];
         }
 
         if (g == 0.0f) {
             // masked, invalid id, clipped, zero advantage or empty batch: the gradient row is zero
             const uint4 zero = make_uint4(0u, 0u, 0u, 0u);
 #pragma unroll
-            for (int k = 0; k < LAST; ++k) *reinterpret_cast<uint4 *>(out_row + (size_t)k * kSweepBytes + voff) = zero;
+            for (int k = 0; k < LAST; ++k) stream_store(out_row + (size_t)k * kSweepBytes + voff, zero);
             if (last_full) {
-                *reinterpret_cast<uint4 *>(out_row + (size_t)LAST * kSweepBytes + voff) = zero;
+                stream_store(out_row + (size_t)LAST * kSweepBytes + voff, zero);
             } else if (last_tail) {
                 for (int e = 0; e < rem; ++e) store_elem<DT>(out_row, (int64_t)nfull * EPV + e, 0.0f);
             }
+            row = next;
             continue;
         }
 
@@ -188,7 +219,7 @@ __global__ __launch_bounds__(kRowThreads) void loss_rows_kernel(
             unpack<DT>(v[k], f);
 #pragma unroll
             for (int e = 0; e < EPV; ++e) f[e] = neg_g * exp2_hw(fmaf(f[e], kLog2e, nlse));
-            *reinterpret_cast<uint4 *>(out_row + (size_t)k * kSweepBytes + voff) = pack<DT>(f);
+            stream_store(out_row + (size_t)k * kSweepBytes + voff, pack<DT>(f));
         }
         if (last_any) {
             float f[EPV];
@@ -196,7 +227,7 @@ __global__ __launch_bounds__(kRowThreads) void loss_rows_kernel(
 #pragma unroll
             for (int e = 0; e < EPV; ++e) f[e] = neg_g * exp2_hw(fmaf(f[e], kLog2e, nlse));
             if (last_full) {
-                *reinterpret_cast<uint4 *>(out_row + (size_t)LAST * kSweepBytes + voff) = pack<DT>(f);
+                stream_store(out_row + (size_t)LAST * kSweepBytes + voff, pack<DT>(f));
             } else {
 #pragma unroll
                 for (int e = 0; e < EPV; ++e)
@@ -207,6 +238,7 @@ __global__ __launch_bounds__(kRowThreads) void loss_rows_kernel(
         // rewrites that one element afterwards (same thread, same address: program order).
         if (tid == ((y / EPV) & (kRowThreads - 1)))
             store_elem<DT>(out_row, y, neg_g * exp2_hw(fmaf(zy, kLog2e, nlse)) + g);
+        row = next;
     }
 }
 
@@ -381,7 +413,7 @@ static hipError_t launch_loss_rows_t(const LossArgs &a, hipStream_t s)
     case N: \
         hipLaunchKernelGGL((loss_rows_kernel<DT, N>), dim3(grid), dim3(kRowThreads), 0, s, a.z, a.dz, a.T, a.V, a.ld, \
                            a.ws_records, a.current_version, a.clip_eps, \
-                           reinterpret_cast<const WsHeader *>(a.ws_header), out); \
+                           reinterpret_cast<const WsHeader *>(a.ws_header), row_queue_of(a.ws_header), out); \
         break;
         A3PO_SWEEP_CASE(1) A3PO_SWEEP_CASE(2) A3PO_SWEEP_CASE(3) A3PO_SWEEP_CASE(4) A3PO_SWEEP_CASE(5)
         A3PO_SWEEP_CASE(6) A3PO_SWEEP_CASE(7) A3PO_SWEEP_CASE(8) A3PO_SWEEP_CASE(9) A3PO_SWEEP_CASE(10)

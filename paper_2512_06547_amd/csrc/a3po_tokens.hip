@@ -53,6 +53,7 @@ __global__ __launch_bounds__(kTokThreads) void loss_prep_kernel(const int32_t *c
         hdr->n_as_float = n;
         hdr->n_counted = c;
         hdr->n_bad = b;
+        *row_queue_of(hdr) = 0u;  // the row kernel's work queue starts empty
     }
 }
 
