@@ -103,6 +103,30 @@ def time_steps(a3po, torch, w, b, mask, steps, warmup, dz, ws, out, adv):
     return dt, kernel_ms
 
 
+def measured_traffic(workload: str, phase: str):
+    """HBM bytes per launch of the row kernel taken from rocprofv3 counters (profiles/), or None when
+    there is no record for this workload or the kernel sources changed since the counters were taken."""
+    import glob
+    import hashlib
+    rec = os.path.join(ROOT, "profiles", "hbm_traffic_loss_rows_kernel.txt")
+    if not os.path.exists(rec):
+        return None
+    h = hashlib.sha256()
+    for f in sorted(glob.glob(os.path.join(ROOT, "paper_2512_06547_amd", "csrc", "*"))):
+        h.update(os.path.basename(f).encode())
+        h.update(open(f, "rb").read())
+    table, sha = {}, None
+    for line in open(rec):
+        parts = line.split("#")[0].split()
+        if len(parts) == 2 and parts[0] == "sources_sha256":
+            sha = parts[1]
+        elif len(parts) == 3:
+            table[(parts[0], parts[1])] = float(parts[2])
+    if sha != h.hexdigest():
+        return None
+    return table.get((workload, phase))
+
+
 def algorithmic_bytes(w, n_counted):
     """Bytes the method itself must move per step: every counted row read once and its gradient row
     written once, every other row zero-filled once, plus the per-token side arrays."""
@@ -110,20 +134,27 @@ def algorithmic_bytes(w, n_counted):
     return row * (2 * n_counted + (w.T - n_counted)) + 30 * w.T
 
 
-def cpu_baseline(w, synth, oracle, rows):
-    """The oracle's whole path on the first `rows` tokens of the same workload, on the host cores."""
+def cpu_baseline(w, synth, oracle, rows, block=2048):
+    """The oracle's whole path (advantages, forward, every gradient row, fp64) on the first `rows`
+    tokens of the same workload, on the host cores, in blocks of `block` rows to bound memory.
+    Only the oracle calls are timed; generating the rows is not."""
     import numpy as np
     tk = synth.token_arrays(w)
-    z = synth.logit_rows(w, 0, rows, tk["chosen"])
-    y = tk["chosen"][:rows].copy()
-    fwd = oracle.token_logprobs(z, y)                       # recipe input (not timed)
-    lb = synth.behav_from_target(fwd["logp"], tk["noise"][:rows])
-    t0 = time.perf_counter()
-    _, adv = oracle.grpo_advantages(tk["rewards"], w.G, seq_id=tk["seq_id"][:rows].copy())
-    oracle.loss_fwd_bwd(z, y, lb, tk["versions"][:rows].copy(), tk["current_version"], adv.astype(np.float32),
-                        tk["mask"][:rows].copy(), w.clip_eps, want_dz=True)
-    dt = time.perf_counter() - t0
-    return rows / dt, dt
+    total = 0.0
+    for r0 in range(0, rows, block):
+        n = min(block, rows - r0)
+        sl = slice(r0, r0 + n)
+        z = synth.logit_rows(w, r0, n, tk["chosen"])
+        y = tk["chosen"][sl].copy()
+        fwd = oracle.token_logprobs(z, y)                   # recipe input (not timed)
+        lb = synth.behav_from_target(fwd["logp"], tk["noise"][sl])
+        t0 = time.perf_counter()
+        _, adv = oracle.grpo_advantages(tk["rewards"], w.G, seq_id=tk["seq_id"][sl].copy())
+        oracle.loss_fwd_bwd(z, y, lb, tk["versions"][sl].copy(), tk["current_version"], adv.astype(np.float32),
+                            tk["mask"][sl].copy(), w.clip_eps, denom=float(max(1, tk["mask"][:rows].sum())),
+                            want_dz=True)
+        total += time.perf_counter() - t0
+    return rows / total, total
 
 
 def main():
@@ -132,7 +163,9 @@ def main():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="1p5b")
-    ap.add_argument("--cpu-rows", type=int, default=2048, help="rows of the oracle baseline sample (0 = skip)")
+    ap.add_argument("--cpu-rows", type=int, default=16384, help="rows of the oracle baseline sample (0 = skip)")
+    ap.add_argument("--phase", default="both", choices=["both", "ragged", "ones"],
+                    help="time the workload's own mask, an all-ones mask, or both (default)")
     ap.add_argument("--quiet", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -156,29 +189,30 @@ def main():
     ws = torch.empty(a3po.workspace_bytes(w.T, w.V), dtype=torch.uint8, device="cuda")
     adv = torch.empty(w.T, dtype=torch.float32, device="cuda")
     out = {}
+    first_mask = b["mask"] if args.phase in ("both", "ragged") else torch.ones_like(b["mask"])
     out.update(a3po.loss_fwd_bwd(b["z"], b["chosen"], b["lb"], b["versions"], b["cur"],
-                                 a3po.grpo_advantages(b["rewards"], w.G, b["seq_id"], out=adv), b["mask"],
+                                 a3po.grpo_advantages(b["rewards"], w.G, b["seq_id"], out=adv), first_mask,
                                  w.clip_eps, dlogits=dz, workspace=ws))
     torch.cuda.synchronize()
-    st = a3po.stats_to_dict(out["stats"])
-    log(f"stats: {st} loss={float(out['loss'].cpu()[0]):.6f}")
+    log(f"stats: {a3po.stats_to_dict(out['stats'])} loss={float(out['loss'].cpu()[0]):.6f}")
 
-    # the workload's own ragged mask: the headline
-    dt, kms = time_steps(a3po, torch, w, b, b["mask"], args.steps, args.warmup, dz, ws, out, adv)
-    kavg = sum(kms) / len(kms)
-    bytes_cfg = algorithmic_bytes(w, st["n_tokens"])
-    ach = bytes_cfg / (kavg * 1e-3) / 1e9
-    log(f"ragged mask: {dt / args.steps * 1e3:.3f} ms/step, row kernel {kavg:.3f} ms, {ach:.0f} GB/s")
+    def phase(mask, label):
+        dt_, kms_ = time_steps(a3po, torch, w, b, mask, args.steps, args.warmup, dz, ws, out, adv)
+        torch.cuda.synchronize()
+        st_ = a3po.stats_to_dict(out["stats"])
+        kavg_ = sum(kms_) / len(kms_)
+        nbytes = algorithmic_bytes(w, st_["n_tokens"])
+        gbs = nbytes / (kavg_ * 1e-3) / 1e9
+        log(f"{label}: {dt_ / args.steps * 1e3:.3f} ms/step, row kernel {kavg_:.3f} ms, {gbs:.0f} GB/s "
+            f"({st_['n_tokens']} counted tokens)")
+        return dict(dt=dt_, kavg=kavg_, bytes=nbytes, gbs=gbs, st=st_)
 
-    # all rows counted: the 2-passes-per-row case that cannot skip anything
-    ones = torch.ones_like(b["mask"])
-    dt1, kms1 = time_steps(a3po, torch, w, b, ones, args.steps, args.warmup, dz, ws, out, adv)
-    torch.cuda.synchronize()
-    st1 = a3po.stats_to_dict(out["stats"])
-    kavg1 = sum(kms1) / len(kms1)
-    bytes_all = algorithmic_bytes(w, st1["n_tokens"])
-    ach1 = bytes_all / (kavg1 * 1e-3) / 1e9
-    log(f"all-ones mask: {dt1 / args.steps * 1e3:.3f} ms/step, row kernel {kavg1:.3f} ms, {ach1:.0f} GB/s")
+    # the workload's own ragged mask is the headline; the all-ones mask is the case that cannot
+    # skip anything (every row read once and written once)
+    rag = phase(b["mask"], "ragged mask") if args.phase in ("both", "ragged") else None
+    one = phase(torch.ones_like(b["mask"]), "all-ones mask") if args.phase in ("both", "ones") else None
+    head = rag if rag is not None else one
+    dt, kavg, bytes_cfg, ach, st = head["dt"], head["kavg"], head["bytes"], head["gbs"], head["st"]
 
     # context only: a plain device copy of the same matrix (read + write), the practical ceiling
     # of a mixed read/write stream on this machine
@@ -217,16 +251,21 @@ def main():
         "dtype": w.dtype,
         "data": "synthetic",
         "config": {"workload": f"{w.name}: {w.S} seq x {w.L} tok = {w.T} tokens, vocab {w.V}, {w.dtype} logits, "
-                               f"GRPO group {w.G}, staleness 0..{w.stale_max}, ragged mask "
+                               f"GRPO group {w.G}, staleness 0..{w.stale_max}, "
+                               f"{'ragged mask' if rag is not None else 'all-ones mask'} "
                                f"({st['n_tokens']} counted tokens), separate gradient buffer",
                    "tokens": w.T, "vocab": w.V, "counted_tokens": st["n_tokens"], "clipped_tokens": st["n_clipped"]},
         "roofline": {"bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": ach / HBM_PEAK_GBS, "traffic": None, "kernel": "loss_rows_kernel",
+                     "frac": ach / HBM_PEAK_GBS,
+                     "traffic": measured_traffic(w.name, "ragged" if rag is not None else "ones"),
+                     "kernel": "loss_rows_kernel",
                      "kernel_ms": kavg, "algorithmic_bytes": bytes_cfg},
-        "all_rows_counted": {"value": w.T * args.steps / dt1, "unit": "tokens/s", "ms_per_step": dt1 / args.steps * 1e3,
-                             "roofline": {"bound": "hbm", "achieved": ach1, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                                          "frac": ach1 / HBM_PEAK_GBS, "traffic": None, "kernel_ms": kavg1,
-                                          "algorithmic_bytes": bytes_all}},
+        "all_rows_counted": None if one is None or rag is None else {
+            "value": w.T * args.steps / one["dt"], "unit": "tokens/s", "ms_per_step": one["dt"] / args.steps * 1e3,
+            "roofline": {"bound": "hbm", "achieved": one["gbs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                         "frac": one["gbs"] / HBM_PEAK_GBS, "traffic": measured_traffic(w.name, "ones"),
+                         "kernel_ms": one["kavg"],
+                         "algorithmic_bytes": one["bytes"]}},
         "cpu_baseline": cpu,
         "plain_copy_gbs": copy_gbs,
     }

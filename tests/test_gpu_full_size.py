@@ -1,0 +1,108 @@
+"""GPU parity at the full sizes of the named workloads (32,768 and 131,072 rows of 151,936 bf16
+logits), in the launch configuration the benchmark times: every token's log-prob, the loss, the
+statistics, and a sample of gradient rows are compared with the CPU oracle; rows are generated
+chunk by chunk (counter-based generator), so the host never holds the whole matrix.
+
+Tolerances are those of test_gpu_parity.py.
+"""
+import numpy as np
+import pytest
+
+import oracle
+import synth
+
+torch = pytest.importorskip("torch")
+
+pytestmark = pytest.mark.gpu
+CUR = synth.CURRENT_VERSION
+
+
+@pytest.fixture(scope="module")
+def a3po():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2512_06547_amd as lib
+    lib.lib()
+    return lib
+
+
+def _run_full(a3po, name, n_sample, inplace):
+    w = synth.WORKLOADS[name]
+    tk = synth.token_arrays(w)
+    T, V = w.T, w.V
+    z_d = torch.empty((T, V), dtype=torch.bfloat16, device="cuda")
+    logp_ref = np.empty(T)
+    lse_ref = np.empty(T)
+    chunk = 4096
+    for r0 in range(0, T, chunk):
+        n = min(chunk, T - r0)
+        rows = synth.logit_rows(w, r0, n, tk["chosen"])
+        f = oracle.token_logprobs(rows, tk["chosen"][r0:r0 + n].copy())
+        logp_ref[r0:r0 + n], lse_ref[r0:r0 + n] = f["logp"], f["lse"]
+        z_d[r0:r0 + n].copy_(torch.from_numpy(rows).view(torch.bfloat16))
+    lb = synth.behav_from_target(logp_ref, tk["noise"])
+    adv_seq = oracle.grpo_advantages(tk["rewards"], w.G)
+    adv = adv_seq[tk["seq_id"]].astype(np.float32)
+    dev = lambda a: torch.from_numpy(a).cuda()
+
+    adv_d = a3po.grpo_advantages(dev(tk["rewards"]), w.G, dev(tk["seq_id"]))
+    assert np.array_equal(adv_d.cpu().numpy(), adv)
+    out = a3po.loss_fwd_bwd(z_d, dev(tk["chosen"]), dev(lb), dev(tk["versions"]), CUR, adv_d, dev(tk["mask"]),
+                            w.clip_eps, dlogits=z_d if inplace else None)
+    torch.cuda.synchronize()
+
+    mask = tk["mask"]
+    sur = oracle.surrogate(np.where(mask == 1, logp_ref, 0.0), lb, tk["versions"], CUR, adv, mask, w.clip_eps)
+    st = a3po.stats_to_dict(out["stats"])
+    assert st["n_tokens"] == int(mask.sum()) == sur["stats"]["n_tokens"]
+    assert st["n_bad_index"] == 0 and st["n_negative_staleness"] == 0
+    logp = out["logp"].cpu().numpy().astype(np.float64)
+    live = mask == 1
+    err = np.abs(logp[live] - logp_ref[live])
+    assert (err <= 1e-5 * np.abs(logp_ref[live]) + 1e-5).all(), err.max()
+    assert not logp[~live].any()
+    prox = out["logp_prox"].cpu().numpy().astype(np.float64)
+    assert (np.abs(prox[live] - sur["lp"][live]) <= 1e-5 * np.abs(sur["lp"][live]) + 1e-5).all()
+    tau = 1e-3
+    near = ((np.abs(sur["r"] - (1 + w.clip_eps)) < tau) | (np.abs(sur["r"] - (1 - w.clip_eps)) < tau)) & live
+    assert abs(st["n_clipped"] - sur["stats"]["n_clipped"]) <= int(near.sum())
+    assert abs(st["iw_min"] - sur["stats"]["iw_min"]) <= 1e-5 * sur["stats"]["iw_min"] + 1e-6
+    assert abs(st["iw_max"] - sur["stats"]["iw_max"]) <= 1e-5 * sur["stats"]["iw_max"] + 1e-6
+    N = sur["stats"]["n_tokens"]
+    scale = (np.abs(sur["obj"]) * mask).sum() / N
+    slack = np.abs(sur["obj"][near]).sum() * 2 * tau / N
+    loss = float(out["loss"].cpu()[0])
+    assert abs(loss - sur["loss"]) <= 1e-5 * abs(sur["loss"]) + 1e-5 * scale + slack, (loss, sur["loss"])
+
+    # gradient rows: first, last, and a seeded sample that includes masked, clipped and live rows
+    r = np.random.default_rng(99)
+    cand = [0, T - 1] + list(r.choice(T, n_sample, replace=False))
+    clipped_rows = np.nonzero((sur["clipped"] == 1) & live & ~near)[0]
+    cand += list(clipped_rows[:4]) + list(np.nonzero(~live)[0][:4])
+    rows = np.array(sorted(set(int(c) for c in cand if not near[c])))
+    zs = np.concatenate([synth.logit_rows(w, int(t), 1, tk["chosen"]) for t in rows])
+    ref = oracle.dlogits_rows(zs, tk["chosen"][rows].copy(), lse_ref[rows], sur["g"][rows], np.arange(len(rows)))
+    got = out["dlogits"][torch.from_numpy(rows).cuda()].float().cpu().numpy().astype(np.float64)
+    gs = np.abs(sur["g"][rows]).reshape(-1, 1)
+    e = np.abs(got - ref)
+    assert (e <= 2e-2 * np.abs(ref) + 2e-2 * gs).all()
+    assert (e <= 2.0 ** -8 * np.abs(ref) + 1e-5 * gs + 1e-37).all(), "beyond one bf16 rounding"
+    dead = sur["g"][rows] == 0
+    assert not got[dead].any()
+    assert dead.any() and (~dead).any()
+    print(f"{name}: T={T} counted={N} clipped={st['n_clipped']} (oracle {sur['stats']['n_clipped']}, "
+          f"{int(near.sum())} in the boundary band) loss={loss:.6f} oracle={sur['loss']:.6f} rows checked={len(rows)}")
+    del out, z_d
+    torch.cuda.empty_cache()
+
+
+def test_1p5b_shape_full_size(a3po):
+    _run_full(a3po, "1p5b", 48, inplace=False)
+
+
+def test_8b_shape_full_size_in_place(a3po):
+    _run_full(a3po, "8b", 32, inplace=True)
+
+
+def test_long_response_high_staleness_full_size(a3po):
+    _run_full(a3po, "long", 32, inplace=False)
