@@ -17,7 +17,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "a3po_oracle.c")
 _LIB = os.path.join(_HERE, "liba3po_oracle.so")
 
-F32, BF16 = 0, 1
+F32, BF16, F64 = 0, 1, 2
 
 
 class Stats(ctypes.Structure):
@@ -68,6 +68,10 @@ def _load():
         lib.a3po_oracle_loss_fwd_bwd.restype = None
         lib.a3po_oracle_loss_fwd_bwd.argtypes = [_P, ctypes.c_int, _I64, _I64, _I64, _P, _P, _P, _I32,
                                                  _P, _P, _F64, _F64, _P, _P, _P, _P, _P, _P, _P, _P, _P]
+        lib.a3po_oracle_lmhead_logits.restype = None
+        lib.a3po_oracle_lmhead_logits.argtypes = [_P, _P, _I64, _I64, _P, _I64, _P]
+        lib.a3po_oracle_lmhead_backward.restype = None
+        lib.a3po_oracle_lmhead_backward.argtypes = [_P, _P, _P, _I64, _I64, _I64, _P, _P]
         _lib = lib
     return _lib
 
@@ -83,7 +87,9 @@ def _logits(z):
         return z, F32
     if z.dtype == np.uint16:
         return z, BF16
-    raise TypeError("logits must be float32 or uint16 (bfloat16 bits)")
+    if z.dtype == np.float64:
+        return z, F64
+    raise TypeError("logits must be float32, float64 or uint16 (bfloat16 bits)")
 
 
 def _f64(a):
@@ -110,7 +116,7 @@ def token_logprobs(z, y, V=None):
     y = _i32(y)
     logp = np.empty(T)
     lse = np.empty(T)
-    raw = np.empty(T, dtype=np.uint32 if dt == F32 else np.uint16)
+    raw = np.empty(T, dtype={F32: np.uint32, BF16: np.uint16, F64: np.float64}[dt])
     _load().a3po_oracle_token_logprobs(z.ctypes.data, dt, T, V, ld, y.ctypes.data,
                                        logp.ctypes.data, lse.ctypes.data, raw.ctypes.data)
     return dict(logp=logp, lse=lse, chosen_raw=raw)
@@ -220,3 +226,36 @@ def loss_fwd_bwd(z, y, lb, versions, current_version, A, mask, clip_eps, denom=0
                                      ctypes.addressof(st))
     return dict(logp=logp, lse=lse, lp=lp, g=g, eff_mask=eff, clipped=cl, dz=dz, loss=loss.value,
                 stats=st.as_dict())
+
+
+def _bf16(a):
+    a = np.ascontiguousarray(a)
+    assert a.dtype == np.uint16 and a.ndim == 2
+    return a
+
+
+def lmhead_logits(h, W, rows=None):
+    """z[rows, :] = h[rows] @ W.T in float64 from bfloat16 bit patterns (h [T,H], W [V,H], uint16)."""
+    h, W = _bf16(h), _bf16(W)
+    T, H = h.shape
+    V = W.shape[0]
+    assert W.shape[1] == H
+    rows = np.arange(T, dtype=np.int64) if rows is None else np.ascontiguousarray(np.asarray(rows, dtype=np.int64))
+    z = np.empty((rows.shape[0], V))
+    _load().a3po_oracle_lmhead_logits(h.ctypes.data, W.ctypes.data, H, V, rows.ctypes.data, rows.shape[0],
+                                      z.ctypes.data)
+    return z
+
+
+def lmhead_backward(dz, h, W, want_dh=True, want_dw=True):
+    """dh = dz @ W, dW = dz.T @ h in float64 (dz [T,V] float64; h, W bfloat16 bit patterns)."""
+    h, W = _bf16(h), _bf16(W)
+    dz = _f64(dz)
+    T, H = h.shape
+    V = W.shape[0]
+    assert dz.shape == (T, V)
+    dh = np.empty((T, H)) if want_dh else None
+    dW = np.empty((V, H)) if want_dw else None
+    _load().a3po_oracle_lmhead_backward(dz.ctypes.data, h.ctypes.data, W.ctypes.data, T, H, V,
+                                        dh.ctypes.data if want_dh else None, dW.ctypes.data if want_dw else None)
+    return dh, dW

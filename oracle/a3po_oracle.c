@@ -32,7 +32,7 @@
 #include <omp.h>
 #endif
 
-enum { ORACLE_F32 = 0, ORACLE_BF16 = 1 };
+enum { ORACLE_F32 = 0, ORACLE_BF16 = 1, ORACLE_F64 = 2 /* oracle-internal: logits already double */ };
 
 typedef struct {
     int64_t n_tokens;             /* number of tokens that enter the mean            */
@@ -47,6 +47,8 @@ static inline double load_z(const void *base, int dt, int64_t idx)
 {
     if (dt == ORACLE_F32) {
         return (double)((const float *)base)[idx];
+    } else if (dt == ORACLE_F64) {
+        return ((const double *)base)[idx];
     } else {
         uint32_t u = (uint32_t)((const uint16_t *)base)[idx] << 16;
         float f;
@@ -95,6 +97,8 @@ void a3po_oracle_token_logprobs(const void *z, int dt, int64_t T, int64_t V, int
                 uint32_t bits = 0;
                 if (ok) memcpy(&bits, (const float *)z + off + y[t], 4);
                 memcpy((uint32_t *)chosen_raw + t, &bits, 4);
+            } else if (dt == ORACLE_F64) {
+                ((double *)chosen_raw)[t] = ok ? ((const double *)z)[off + y[t]] : 0.0;
             } else {
                 ((uint16_t *)chosen_raw)[t] = ok ? ((const uint16_t *)z)[off + y[t]] : 0;
             }
@@ -306,5 +310,62 @@ void a3po_oracle_loss_fwd_bwd(const void *z, int dt, int64_t T, int64_t V, int64
         for (int64_t t = 0; t < T; ++t) all[t] = t;
         a3po_oracle_dlogits_rows(z, dt, V, ld, y, lse_out, g_out, all, T, dz_out);
         free(all);
+    }
+}
+
+/* ------------------------------------------------------------------------------------------
+ * LM-head projection in front of the path (not in the paper; the 8B-shape workload feeds hidden
+ * states and the LM-head weight instead of logits):  z[t, v] = sum_k h[t, k] * W[v, k],
+ * h [T, H] and W [V, H] bfloat16 bit patterns, products and sum in double, ascending k.
+ * Only the tokens listed in `rows` are evaluated; z_out is dense [nrows, V] double.
+ */
+static inline double bf16_to_double(uint16_t b)
+{
+    uint32_t u = (uint32_t)b << 16;
+    float f;
+    memcpy(&f, &u, 4);
+    return (double)f;
+}
+
+void a3po_oracle_lmhead_logits(const uint16_t *h, const uint16_t *W, int64_t H, int64_t V,
+                               const int64_t *rows, int64_t nrows, double *z_out)
+{
+#pragma omp parallel for collapse(2) schedule(static)
+    for (int64_t i = 0; i < nrows; ++i) {
+        for (int64_t v = 0; v < V; ++v) {
+            const uint16_t *hr = h + rows[i] * H;
+            const uint16_t *wr = W + v * H;
+            double acc = 0.0;
+            for (int64_t k = 0; k < H; ++k) acc += bf16_to_double(hr[k]) * bf16_to_double(wr[k]);
+            z_out[i * V + v] = acc;
+        }
+    }
+}
+
+/*
+ * Backward of the projection for a dense gradient dz [T, V] (double):
+ *   dh[t, k] = sum_v dz[t, v] * W[v, k]      dW[v, k] = sum_t dz[t, v] * h[t, k]
+ * Either output may be NULL.
+ */
+void a3po_oracle_lmhead_backward(const double *dz, const uint16_t *h, const uint16_t *W, int64_t T,
+                                 int64_t H, int64_t V, double *dh, double *dW)
+{
+    if (dh) {
+#pragma omp parallel for schedule(static)
+        for (int64_t t = 0; t < T; ++t)
+            for (int64_t k = 0; k < H; ++k) {
+                double acc = 0.0;
+                for (int64_t v = 0; v < V; ++v) acc += dz[t * V + v] * bf16_to_double(W[v * H + k]);
+                dh[t * H + k] = acc;
+            }
+    }
+    if (dW) {
+#pragma omp parallel for schedule(static)
+        for (int64_t v = 0; v < V; ++v)
+            for (int64_t k = 0; k < H; ++k) {
+                double acc = 0.0;
+                for (int64_t t = 0; t < T; ++t) acc += dz[t * V + v] * bf16_to_double(h[t * H + k]);
+                dW[v * H + k] = acc;
+            }
     }
 }

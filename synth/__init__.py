@@ -160,3 +160,30 @@ def behav_from_target(logp_theta: np.ndarray, noise: np.ndarray) -> np.ndarray:
 def bf16_bits_to_f64(u16: np.ndarray) -> np.ndarray:
     """Exact widening of bfloat16 bit patterns to float64 (format conversion only)."""
     return (u16.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+
+
+@dataclass(frozen=True)
+class LmHeadWorkload:
+    """Hidden states and LM-head weight in front of the loss path (the 8B-shape fused workload)."""
+    name: str
+    tokens: Workload          # per-token recipe (V of this workload is the vocabulary)
+    H: int                    # hidden size
+    h_sigma: float = 1.0      # hidden ~ N(0, h_sigma^2), bf16
+    w_sigma: float = 0.02     # weight ~ N(0, w_sigma^2), bf16
+
+
+LMHEAD_WORKLOADS = {
+    "lmhead8b": LmHeadWorkload("lmhead8b", WORKLOADS["8b"].scaled(name="lmhead8b", S=16, L=4096, stream=5), 4096),
+}
+
+
+def hidden_rows(lw: LmHeadWorkload, t0: int, nrows: int) -> np.ndarray:
+    """Rows t0.. of the [T, H] hidden states, bfloat16 bit patterns (uint16)."""
+    w = lw.tokens.scaled(V=lw.H, dtype="bf16", sigma=lw.h_sigma, stream=lw.tokens.stream + 64, boost_prob=0.0)
+    return logit_rows(w, t0, nrows, None)
+
+
+def weight_rows(lw: LmHeadWorkload, v0: int, nrows: int) -> np.ndarray:
+    """Rows v0.. of the [V, H] LM-head weight, bfloat16 bit patterns (uint16)."""
+    w = lw.tokens.scaled(V=lw.H, dtype="bf16", sigma=lw.w_sigma, stream=lw.tokens.stream + 128, boost_prob=0.0)
+    return logit_rows(w, v0, nrows, None)

@@ -446,3 +446,72 @@ def test_grpo_broadcast_to_tokens():
     sid = np.repeat(np.arange(8, dtype=np.int32), 5)
     adv_seq, adv_tok = oracle.grpo_advantages(R, 4, seq_id=sid)
     assert np.array_equal(adv_tok, adv_seq[sid])
+
+
+# ----------------------------------------------------------------------------- LM-head projection
+
+def test_lmhead_logits_against_numpy_matmul_and_hand_values():
+    H, V, T = 24, 37, 9
+    h = bf16_bits(rng.standard_normal((T, H)))
+    W = bf16_bits(rng.standard_normal((V, H)) * 0.5)
+    hf, Wf = synth.bf16_bits_to_f64(h), synth.bf16_bits_to_f64(W)
+    z = oracle.lmhead_logits(h, W)
+    assert np.allclose(z, hf @ Wf.T, rtol=1e-13, atol=1e-13)
+    sub = oracle.lmhead_logits(h, W, rows=[7, 2])
+    assert np.array_equal(sub, z[[7, 2]])
+    # hand values: h = [1, 2, -1], W rows [1, 0, 0], [0.5, 0.5, 0.5], [-2, 1, 4]  ->  z = [1, 1, -4]
+    h1 = bf16_bits(np.array([[1.0, 2.0, -1.0]]))
+    W1 = bf16_bits(np.array([[1.0, 0, 0], [0.5, 0.5, 0.5], [-2.0, 1.0, 4.0]]))
+    assert np.array_equal(oracle.lmhead_logits(h1, W1), np.array([[1.0, 1.0, -4.0]]))
+    # an identity weight returns the hidden state as logits (operands not transposed by mistake)
+    eye = bf16_bits(np.eye(H))
+    assert np.array_equal(oracle.lmhead_logits(h, eye), hf)
+
+
+def test_float64_logits_go_through_the_same_logsoftmax():
+    z = rng.standard_normal((5, 33)) * 3
+    y = rng.integers(0, 33, 5).astype(np.int32)
+    o = oracle.token_logprobs(z, y)
+    assert np.allclose(o["lse"], scipy.special.logsumexp(z, axis=1), rtol=0, atol=1e-13)
+    assert np.allclose(o["logp"], z[np.arange(5), y] - o["lse"], rtol=0, atol=1e-13)
+    assert np.array_equal(o["chosen_raw"], z[np.arange(5), y])
+
+
+def test_lmhead_backward_against_numpy_and_finite_differences():
+    H, V, T = 6, 11, 4
+    h = bf16_bits(np.round(rng.standard_normal((T, H)) * 8) / 8)
+    W = bf16_bits(np.round(rng.standard_normal((V, H)) * 8) / 8)
+    hf, Wf = synth.bf16_bits_to_f64(h), synth.bf16_bits_to_f64(W)
+    y = rng.integers(0, V, T).astype(np.int32)
+    ver = (10 - rng.integers(0, 4, T)).astype(np.int32)
+    A = rng.standard_normal(T)
+    m = np.ones(T, np.uint8)
+    z0 = oracle.lmhead_logits(h, W)
+    lt0 = oracle.token_logprobs(z0, y)["logp"]
+    lb = lt0 + rng.uniform(-0.1, 0.1, T)          # inside the clip range: every token carries gradient
+    full = oracle.loss_fwd_bwd(z0, y, lb, ver, 10, A, m, 0.2)
+    dh, dW = oracle.lmhead_backward(full["dz"], h, W)
+    assert np.allclose(dh, full["dz"] @ Wf, rtol=1e-12, atol=1e-15)
+    assert np.allclose(dW, full["dz"].T @ hf, rtol=1e-12, atol=1e-15)
+
+    def frozen_loss(hm, Wm):
+        lt = oracle.token_logprobs(hm @ Wm.T, y)["logp"]
+        return oracle.decoupled_clip(lt, lb, full["lp"], A, m, 0.2)["loss"]
+
+    eps = 2.0 ** -12
+    num_dh = np.zeros_like(hf)
+    for t in range(T):
+        for k in range(H):
+            hp, hm_ = hf.copy(), hf.copy()
+            hp[t, k] += eps
+            hm_[t, k] -= eps
+            num_dh[t, k] = (frozen_loss(hp, Wf) - frozen_loss(hm_, Wf)) / (2 * eps)
+    assert np.abs(num_dh - dh).max() < 1e-6 * np.abs(dh).max() + 1e-10
+    num_dW = np.zeros_like(Wf)
+    for v in range(V):
+        for k in range(H):
+            Wp, Wm_ = Wf.copy(), Wf.copy()
+            Wp[v, k] += eps
+            Wm_[v, k] -= eps
+            num_dW[v, k] = (frozen_loss(hf, Wp) - frozen_loss(hf, Wm_)) / (2 * eps)
+    assert np.abs(num_dW - dW).max() < 1e-6 * np.abs(dW).max() + 1e-10
