@@ -58,7 +58,7 @@ typedef struct {
     float iw_min, iw_max;         /* extrema of pi_prox/pi_behav over counted tokens    */
 } a3po_stats;
 
-enum { A3PO_WS_LOSS_FWD_BWD = 0 };
+enum { A3PO_WS_LOSS_FWD_BWD = 0, A3PO_WS_FUSED_LMHEAD = 1 };
 
 /* Bytes of device workspace the given entry point needs (256-byte aligned base). */
 size_t a3po_workspace_bytes(int which, int64_t T, int64_t V, int64_t H);
@@ -145,6 +145,23 @@ int a3po_loss_fwd_bwd_events(const void *logits, a3po_dtype dt, int64_t T, int64
                              float *loss_out, a3po_stats *stats_out,
                              void *workspace, size_t workspace_bytes, void *stream,
                              void *event_before_rows, void *event_after_rows);
+
+/*
+ * Token log-probs straight from hidden states and the LM-head weight (the 8B-shape fused
+ * workload; the paper itself starts from log pi_theta and never mentions the projection):
+ *   z[t, v] = sum_k hidden[t, k] * weight[v, k]   (bfloat16 inputs, fp32 accumulate on the matrix
+ *   cores),  lse_t = log sum_v exp z[t, v],  logp_out[t] = z[t, chosen[t]] - lse_t.
+ * The [T, V] logits are never written to memory: each 256 x 256 tile is folded into a running
+ * (max, sum) per token as it leaves the matrix cores.
+ * hidden [T, H] and weight [V, H]: row-major, contiguous, bfloat16, 16-byte aligned; H must be a
+ * positive multiple of 64.  chosen [T] int32; an id outside [0,V) gives logp 0 (lse still written).
+ * logp_out [T] float, lse_out [T] float (nullable).
+ * workspace: a3po_workspace_bytes(A3PO_WS_FUSED_LMHEAD, T, V, H) bytes, 256-byte aligned.
+ * The first call on a process raises the kernel's dynamic LDS limit (one hipFuncSetAttribute).
+ */
+int a3po_fused_lmhead_logprob(const void *hidden, const void *weight, int64_t T, int64_t H, int64_t V,
+                              const int32_t *chosen, float *logp_out, float *lse_out,
+                              void *workspace, size_t workspace_bytes, void *stream);
 
 #ifdef __cplusplus
 }

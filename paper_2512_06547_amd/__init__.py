@@ -7,6 +7,7 @@ from .binding import (  # noqa: F401
     A3PO_BF16,
     A3PO_F32,
     A3poError,
+    fused_lmhead_logprob,
     STATS_DTYPE,
     grpo_advantages,
     lib,

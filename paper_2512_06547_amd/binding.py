@@ -16,6 +16,7 @@ _LIB_PATH = os.path.join(_PKG, "liba3po.so")
 
 A3PO_F32, A3PO_BF16 = 0, 1
 A3PO_WS_LOSS_FWD_BWD = 0
+A3PO_WS_FUSED_LMHEAD = 1
 
 # layout of a3po_stats (include/a3po.h)
 STATS_DTYPE = np.dtype([("n_tokens", "<i8"), ("n_clipped", "<i8"), ("n_bad_index", "<i8"),
@@ -29,6 +30,7 @@ _SIGNATURES = {
     "a3po_token_logprobs": (ctypes.c_int, [_P, ctypes.c_int, _I64, _I64, _I64, _P, _P, _P, _P, _P]),
     "a3po_proximal_interp": (ctypes.c_int, [_P, _P, _P, _I32, _I64, _P, _P, _P]),
     "a3po_grpo_advantages": (ctypes.c_int, [_P, _I64, _I32, _F32, _P, _I64, _P, _P]),
+    "a3po_fused_lmhead_logprob": (ctypes.c_int, [_P, _P, _I64, _I64, _I64, _P, _P, _P, _P, _SZ, _P]),
     "a3po_loss_fwd_bwd": (ctypes.c_int, [_P, ctypes.c_int, _I64, _I64, _I64, _P, _P, _P, _I32, _P, _P, _F32, _F32,
                                          _P, _P, _P, _P, _P, _P, _SZ, _P]),
     "a3po_loss_fwd_bwd_events": (ctypes.c_int, [_P, ctypes.c_int, _I64, _I64, _I64, _P, _P, _P, _I32, _P, _P, _F32,
@@ -187,6 +189,25 @@ def loss_fwd_bwd(logits, chosen, logp_behav, versions, current_version: int, adv
     else:
         _check(lib().a3po_loss_fwd_bwd_events(*args, events[0], events[1]), "a3po_loss_fwd_bwd_events")
     return dict(dlogits=dlogits, logp=logp, logp_prox=prox, loss=loss, stats=stats, workspace=workspace)
+
+
+def fused_lmhead_logprob(hidden, weight, chosen, want_lse=True, workspace=None):
+    """a3po_fused_lmhead_logprob -> (logp[T] f32, lse[T] f32 | None); hidden [T,H], weight [V,H] bfloat16."""
+    torch = _torch()
+    assert hidden.is_cuda and weight.is_cuda and hidden.dtype == torch.bfloat16 and weight.dtype == torch.bfloat16
+    assert hidden.is_contiguous() and weight.is_contiguous() and hidden.dim() == 2 and weight.dim() == 2
+    T, H = hidden.shape
+    V = weight.shape[0]
+    assert weight.shape[1] == H
+    _vec(chosen, torch.int32, T, "chosen")
+    need = workspace_bytes(T, V, H, which=A3PO_WS_FUSED_LMHEAD)
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=hidden.device)
+    logp = torch.empty(T, dtype=torch.float32, device=hidden.device)
+    lse = torch.empty(T, dtype=torch.float32, device=hidden.device) if want_lse else None
+    _check(lib().a3po_fused_lmhead_logprob(_ptr(hidden), _ptr(weight), T, H, V, _ptr(chosen), _ptr(logp), _ptr(lse),
+                                           _ptr(workspace), workspace.numel(), _stream()), "a3po_fused_lmhead_logprob")
+    return logp, lse
 
 
 def stats_to_dict(stats_tensor) -> dict:

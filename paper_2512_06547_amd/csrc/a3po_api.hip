@@ -47,6 +47,7 @@ size_t a3po_workspace_bytes(int which, int64_t T, int64_t V, int64_t H)
     (void)V;
     (void)H;
     if (which == A3PO_WS_LOSS_FWD_BWD) return loss_ws_layout(T).total;
+    if (which == A3PO_WS_FUSED_LMHEAD) return lmhead_workspace_bytes(T);
     return 0;
 }
 
@@ -96,6 +97,21 @@ int a3po_grpo_advantages(const float *rewards, int64_t S, int32_t G, float eps_a
     if (!rewards || !seq_id || !adv_out) return A3PO_E_NULL;
     const hipError_t e =
         launch_grpo_advantages(rewards, S, G, eps_adv, seq_id, T, adv_out, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? A3PO_OK : A3PO_E_LAUNCH;
+}
+
+int a3po_fused_lmhead_logprob(const void *hidden, const void *weight, int64_t T, int64_t H, int64_t V,
+                              const int32_t *chosen, float *logp_out, float *lse_out, void *workspace,
+                              size_t workspace_bytes, void *stream)
+{
+    if (T < 0 || V <= 0 || H <= 0 || H % 64 != 0 || V > (int64_t)0x7FFFFFFF) return A3PO_E_SIZE;
+    if (T == 0) return A3PO_OK;
+    if (!hidden || !weight || !chosen || !logp_out) return A3PO_E_NULL;
+    if (!aligned(hidden, 16) || !aligned(weight, 16)) return A3PO_E_ALIGN;
+    if (!workspace || workspace_bytes < lmhead_workspace_bytes(T)) return A3PO_E_WORKSPACE;
+    if (!aligned(workspace, 256)) return A3PO_E_ALIGN;
+    const hipError_t e = launch_fused_lmhead_logprob(hidden, weight, T, H, V, chosen, logp_out, lse_out, workspace,
+                                                     static_cast<hipStream_t>(stream));
     return e == hipSuccess ? A3PO_OK : A3PO_E_LAUNCH;
 }
 

@@ -49,4 +49,8 @@ hipError_t launch_proximal_interp(const float *lb, const float *lt, const int32_
 hipError_t launch_grpo_advantages(const float *rewards, int64_t S, int32_t G, float eps_adv, const int32_t *seq_id,
                                   int64_t T, float *adv, hipStream_t s);
 
+size_t lmhead_workspace_bytes(int64_t T);
+hipError_t launch_fused_lmhead_logprob(const void *hidden, const void *weight, int64_t T, int64_t H, int64_t V,
+                                       const int32_t *chosen, float *logp, float *lse, void *workspace, hipStream_t s);
+
 }  // namespace a3po
