@@ -129,52 +129,81 @@ __global__ __launch_bounds__(kLmThreads) void lmhead_lse_kernel(const uint16_t *
 #pragma unroll
                     for (int e = 0; e < 16; ++e) acc[a][b][e] = 0.0f;
 
-            // K loop, one barrier per chunk: the chunk staged in registers is written to LDS buffer
-            // c & 1, the next chunk's global loads are issued (the last iteration re-reads the last
-            // chunk rather than branching), then the MFMAs run from buffer c & 1.  A wavefront can
-            // only overwrite buffer (c+1) & 1 after the barrier of iteration c+1, which every
-            // wavefront reaches after finishing its MFMAs on that buffer in iteration c-1.
+            // K loop, one barrier per chunk.  While the MFMAs of chunk c run from LDS buffer c & 1,
+            // the chunk staged in registers (c+1) is written to the other buffer and the global
+            // loads of chunk c+2 are issued into the registers just freed; LDS writes, global loads
+            // and the fragment reads of the next k-step are interleaved with the MFMAs.  The barrier
+            // at the end of iteration c publishes buffer (c+1) & 1 and guarantees that nobody still
+            // reads buffer c & 1 when iteration c+1 overwrites it.  Past the last chunk the loads are
+            // clamped to it (re-read) instead of branching.
             lm_u32x4_t ga[8], gb[8];
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
                 ga[j] = *reinterpret_cast<const lm_u32x4_t *>(w_tile + aoff[j]);
                 gb[j] = *reinterpret_cast<const lm_u32x4_t *>(h_tile + boff[j]);
             }
-#pragma unroll 1
-            for (int c = 0; c < nchunks; ++c) {
-                char *sa = lds + (c & 1) * 2 * kLmOperandBytes;
-                char *sb = sa + kLmOperandBytes;
 #pragma unroll
-                for (int j = 0; j < 8; ++j) {
-                    *reinterpret_cast<lm_u32x4_t *>(sa + st_off + j * 32 * kLmRowBytes) = ga[j];
-                    *reinterpret_cast<lm_u32x4_t *>(sb + st_off + j * 32 * kLmRowBytes) = gb[j];
-                }
-                __syncthreads();
-                const uint32_t koff = (uint32_t)min(c + 1, nchunks - 1) * (kLmChunk * 2);
+            for (int j = 0; j < 8; ++j) {
+                *reinterpret_cast<lm_u32x4_t *>(lds + st_off + j * 32 * kLmRowBytes) = ga[j];
+                *reinterpret_cast<lm_u32x4_t *>(lds + kLmOperandBytes + st_off + j * 32 * kLmRowBytes) = gb[j];
+            }
+            {
+                const uint32_t koff = (uint32_t)min(1, nchunks - 1) * (kLmChunk * 2);
 #pragma unroll
                 for (int j = 0; j < 8; ++j) {
                     ga[j] = *reinterpret_cast<const lm_u32x4_t *>(w_tile + (size_t)(aoff[j] + koff));
                     gb[j] = *reinterpret_cast<const lm_u32x4_t *>(h_tile + (size_t)(boff[j] + koff));
                 }
-                __builtin_amdgcn_sched_barrier(0);
+            }
+            __syncthreads();
+#pragma unroll 1
+            for (int c = 0; c < nchunks; ++c) {
+                const char *sa = lds + (c & 1) * 2 * kLmOperandBytes;
+                const char *sb = sa + kLmOperandBytes;
+                char *da = lds + ((c + 1) & 1) * 2 * kLmOperandBytes;
+                char *db = da + kLmOperandBytes;
+                const uint32_t koff = (uint32_t)min(c + 2, nchunks - 1) * (kLmChunk * 2);
+                bf16x8_t fa[2][4], fb[2][4];
+#pragma unroll
+                for (int a = 0; a < 4; ++a)
+                    fa[0][a] = *reinterpret_cast<const bf16x8_t *>(sa + fa_off + a * 32 * kLmRowBytes);
+#pragma unroll
+                for (int b = 0; b < 4; ++b)
+                    fb[0][b] = *reinterpret_cast<const bf16x8_t *>(sb + fb_off + b * 32 * kLmRowBytes);
 #pragma unroll
                 for (int ks = 0; ks < 4; ++ks) {
-                    bf16x8_t fa[4], fb[4];
+                    if (ks < 3) {
 #pragma unroll
-                    for (int a = 0; a < 4; ++a)
-                        fa[a] = *reinterpret_cast<const bf16x8_t *>(sa + fa_off + a * 32 * kLmRowBytes + ks * 32);
+                        for (int a = 0; a < 4; ++a)
+                            fa[(ks + 1) & 1][a] = *reinterpret_cast<const bf16x8_t *>(sa + fa_off + a * 32 * kLmRowBytes + (ks + 1) * 32);
 #pragma unroll
-                    for (int b = 0; b < 4; ++b)
-                        fb[b] = *reinterpret_cast<const bf16x8_t *>(sb + fb_off + b * 32 * kLmRowBytes + ks * 32);
+                        for (int b = 0; b < 4; ++b)
+                            fb[(ks + 1) & 1][b] = *reinterpret_cast<const bf16x8_t *>(sb + fb_off + b * 32 * kLmRowBytes + (ks + 1) * 32);
+                    }
+#pragma unroll
+                    for (int jj = 0; jj < 2; ++jj) {
+                        const int j = 2 * ks + jj;
+                        *reinterpret_cast<lm_u32x4_t *>(da + st_off + j * 32 * kLmRowBytes) = ga[j];
+                        *reinterpret_cast<lm_u32x4_t *>(db + st_off + j * 32 * kLmRowBytes) = gb[j];
+                        ga[j] = *reinterpret_cast<const lm_u32x4_t *>(w_tile + (size_t)(aoff[j] + koff));
+                        gb[j] = *reinterpret_cast<const lm_u32x4_t *>(h_tile + (size_t)(boff[j] + koff));
+                    }
 #pragma unroll
                     for (int a = 0; a < 4; ++a)
 #pragma unroll
                         for (int b = 0; b < 4; ++b)
-                            acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[a], fb[b], acc[a][b], 0, 0, 0);
+                            acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[ks & 1][a], fb[ks & 1][b], acc[a][b], 0, 0, 0);
+                    // spread this k-step's memory instructions between its MFMAs
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);  // MFMA
+                        __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);  // LDS reads (next k-step's fragments)
+                        __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);  // LDS write (next chunk)
+                        __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);  // global load (chunk after next)
+                    }
                 }
-                __builtin_amdgcn_sched_barrier(0);
+                __syncthreads();
             }
-            __syncthreads();  // all MFMAs of the tile are done before the next tile (or the sweep's merge) reuses LDS
 
             // ---- fold the tile into the running (max, sum) of this lane's four token columns ----
             // acc[a][b][4 i + j] = z[vocab v0 + wm 128 + a 32 + 8 i + (lane >> 5) 4 + j][token column b]
