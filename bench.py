@@ -106,15 +106,14 @@ def time_steps(a3po, torch, w, b, mask, steps, warmup, dz, ws, out, adv):
 def measured_traffic(workload: str, phase: str):
     """HBM bytes per launch of the row kernel taken from rocprofv3 counters (profiles/), or None when
     there is no record for this workload or the kernel sources changed since the counters were taken."""
-    import glob
     import hashlib
     rec = os.path.join(ROOT, "profiles", "hbm_traffic_loss_rows_kernel.txt")
     if not os.path.exists(rec):
         return None
     h = hashlib.sha256()
-    for f in sorted(glob.glob(os.path.join(ROOT, "paper_2512_06547_amd", "csrc", "*"))):
-        h.update(os.path.basename(f).encode())
-        h.update(open(f, "rb").read())
+    for name in ("a3po_common.h", "a3po_rows.hip"):   # the row kernel and the helpers it inlines
+        h.update(name.encode())
+        h.update(open(os.path.join(ROOT, "paper_2512_06547_amd", "csrc", name), "rb").read())
     table, sha = {}, None
     for line in open(rec):
         parts = line.split("#")[0].split()

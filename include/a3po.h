@@ -58,7 +58,7 @@ typedef struct {
     float iw_min, iw_max;         /* extrema of pi_prox/pi_behav over counted tokens    */
 } a3po_stats;
 
-enum { A3PO_WS_LOSS_FWD_BWD = 0, A3PO_WS_FUSED_LMHEAD = 1 };
+enum { A3PO_WS_LOSS_FWD_BWD = 0, A3PO_WS_FUSED_LMHEAD = 1, A3PO_WS_FUSED_LMHEAD_LOSS = 2 };
 
 /* Bytes of device workspace the given entry point needs (256-byte aligned base). */
 size_t a3po_workspace_bytes(int which, int64_t T, int64_t V, int64_t H);
@@ -162,6 +162,31 @@ int a3po_loss_fwd_bwd_events(const void *logits, a3po_dtype dt, int64_t T, int64
 int a3po_fused_lmhead_logprob(const void *hidden, const void *weight, int64_t T, int64_t H, int64_t V,
                               const int32_t *chosen, float *logp_out, float *lse_out,
                               void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * The whole path from hidden states: LM-head projection, then everything a3po_loss_fwd_bwd does,
+ * then the gradient contracted back through the projection:
+ *   z = hidden weight^T,  loss / log-probs / statistics as in a3po_loss_fwd_bwd (same arguments),
+ *   dhidden[t, :] = sum_v dlogits[t, v] weight[v, :],   dweight[v, :] = sum_t dlogits[t, v] hidden[t, :].
+ * Logits exist only for a chunk of 8,192 tokens at a time, in bfloat16, inside the workspace: the
+ * log-probs therefore carry one bfloat16 rounding of each logit (abs error <= 2^-8 max|z|), unlike
+ * a3po_fused_lmhead_logprob, which keeps fp32 logits on chip.  The three contractions are plain
+ * GEMMs issued to rocBLAS (bfloat16 inputs, fp32 accumulation; dweight is accumulated over chunks
+ * in fp32 and rounded to bfloat16 once); everything between them is this library's kernels.
+ * hidden, dhidden [T, H]; weight, dweight [V, H]: row-major, contiguous, bfloat16, 16-byte
+ * aligned; H % 8 == 0 and V % 8 == 0.  Per-token arguments and outputs as in a3po_loss_fwd_bwd.
+ * workspace: a3po_workspace_bytes(A3PO_WS_FUSED_LMHEAD_LOSS, T, V, H) bytes, 256-byte aligned.
+ * Unlike the other entry points this one keeps one process-wide rocBLAS handle, created on first
+ * use (rocBLAS allocates its own scratch then); calls that share it must not overlap in time.
+ */
+int a3po_fused_lmhead_loss_fwd_bwd(const void *hidden, const void *weight, int64_t T, int64_t H, int64_t V,
+                                   const int32_t *chosen, const float *logp_behav,
+                                   const int32_t *versions, int32_t current_version,
+                                   const float *advantages, const uint8_t *loss_mask,
+                                   float clip_eps, float denom,
+                                   void *dhidden, void *dweight, float *logp_out, float *logp_prox_out,
+                                   float *loss_out, a3po_stats *stats_out,
+                                   void *workspace, size_t workspace_bytes, void *stream);
 
 #ifdef __cplusplus
 }

@@ -8,6 +8,7 @@ from .binding import (  # noqa: F401
     A3PO_F32,
     A3poError,
     fused_lmhead_logprob,
+    fused_lmhead_loss_fwd_bwd,
     STATS_DTYPE,
     grpo_advantages,
     lib,

@@ -17,6 +17,7 @@ _LIB_PATH = os.path.join(_PKG, "liba3po.so")
 A3PO_F32, A3PO_BF16 = 0, 1
 A3PO_WS_LOSS_FWD_BWD = 0
 A3PO_WS_FUSED_LMHEAD = 1
+A3PO_WS_FUSED_LMHEAD_LOSS = 2
 
 # layout of a3po_stats (include/a3po.h)
 STATS_DTYPE = np.dtype([("n_tokens", "<i8"), ("n_clipped", "<i8"), ("n_bad_index", "<i8"),
@@ -31,6 +32,8 @@ _SIGNATURES = {
     "a3po_proximal_interp": (ctypes.c_int, [_P, _P, _P, _I32, _I64, _P, _P, _P]),
     "a3po_grpo_advantages": (ctypes.c_int, [_P, _I64, _I32, _F32, _P, _I64, _P, _P]),
     "a3po_fused_lmhead_logprob": (ctypes.c_int, [_P, _P, _I64, _I64, _I64, _P, _P, _P, _P, _SZ, _P]),
+    "a3po_fused_lmhead_loss_fwd_bwd": (ctypes.c_int, [_P, _P, _I64, _I64, _I64, _P, _P, _P, _I32, _P, _P, _F32, _F32,
+                                                      _P, _P, _P, _P, _P, _P, _P, _SZ, _P]),
     "a3po_loss_fwd_bwd": (ctypes.c_int, [_P, ctypes.c_int, _I64, _I64, _I64, _P, _P, _P, _I32, _P, _P, _F32, _F32,
                                          _P, _P, _P, _P, _P, _P, _SZ, _P]),
     "a3po_loss_fwd_bwd_events": (ctypes.c_int, [_P, ctypes.c_int, _I64, _I64, _I64, _P, _P, _P, _I32, _P, _P, _F32,
@@ -208,6 +211,37 @@ def fused_lmhead_logprob(hidden, weight, chosen, want_lse=True, workspace=None):
     _check(lib().a3po_fused_lmhead_logprob(_ptr(hidden), _ptr(weight), T, H, V, _ptr(chosen), _ptr(logp), _ptr(lse),
                                            _ptr(workspace), workspace.numel(), _stream()), "a3po_fused_lmhead_logprob")
     return logp, lse
+
+
+def fused_lmhead_loss_fwd_bwd(hidden, weight, chosen, logp_behav, versions, current_version: int, advantages,
+                              loss_mask, clip_eps: float, denom: float = 0.0, workspace=None):
+    """a3po_fused_lmhead_loss_fwd_bwd -> dict(dhidden, dweight, logp, logp_prox, loss, stats, workspace)."""
+    torch = _torch()
+    assert hidden.is_cuda and weight.is_cuda and hidden.dtype == torch.bfloat16 and weight.dtype == torch.bfloat16
+    assert hidden.is_contiguous() and weight.is_contiguous() and hidden.dim() == 2 and weight.dim() == 2
+    T, H = hidden.shape
+    V = weight.shape[0]
+    assert weight.shape[1] == H
+    dev = hidden.device
+    _vec(chosen, torch.int32, T, "chosen")
+    _vec(logp_behav, torch.float32, T, "logp_behav")
+    _vec(versions, torch.int32, T, "versions")
+    _vec(advantages, torch.float32, T, "advantages")
+    _vec(loss_mask, torch.uint8, T, "loss_mask")
+    need = workspace_bytes(T, V, H, which=A3PO_WS_FUSED_LMHEAD_LOSS)
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=dev)
+    dh = torch.empty_like(hidden)
+    dw = torch.empty_like(weight)
+    logp = torch.empty(T, dtype=torch.float32, device=dev)
+    prox = torch.empty(T, dtype=torch.float32, device=dev)
+    loss = torch.empty(1, dtype=torch.float32, device=dev)
+    stats = torch.empty(STATS_DTYPE.itemsize, dtype=torch.uint8, device=dev)
+    _check(lib().a3po_fused_lmhead_loss_fwd_bwd(
+        _ptr(hidden), _ptr(weight), T, H, V, _ptr(chosen), _ptr(logp_behav), _ptr(versions), int(current_version),
+        _ptr(advantages), _ptr(loss_mask), float(clip_eps), float(denom), _ptr(dh), _ptr(dw), _ptr(logp), _ptr(prox),
+        _ptr(loss), _ptr(stats), _ptr(workspace), workspace.numel(), _stream()), "a3po_fused_lmhead_loss_fwd_bwd")
+    return dict(dhidden=dh, dweight=dw, logp=logp, logp_prox=prox, loss=loss, stats=stats, workspace=workspace)
 
 
 def stats_to_dict(stats_tensor) -> dict:

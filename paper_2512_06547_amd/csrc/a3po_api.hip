@@ -9,23 +9,8 @@ using namespace a3po;
 
 namespace {
 
-inline size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
-struct WsLayout {
-    size_t records, obj, iw, flags, total;
-};
-
-WsLayout loss_ws_layout(int64_t T)
-{
-    WsLayout l;
-    const size_t t = (size_t)(T > 0 ? T : 0);
-    l.records = kWsHeaderBytes;
-    l.obj = l.records + round_up(t * sizeof(TokenRecord), 256);
-    l.iw = l.obj + round_up(t * sizeof(float), 256);
-    l.flags = l.iw + round_up(t * sizeof(float), 256);
-    l.total = l.flags + round_up(t, 256);
-    return l;
-}
+using WsLayout = LossWsLayout;
 
 inline bool aligned(const void *p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 
@@ -48,6 +33,7 @@ size_t a3po_workspace_bytes(int which, int64_t T, int64_t V, int64_t H)
     (void)H;
     if (which == A3PO_WS_LOSS_FWD_BWD) return loss_ws_layout(T).total;
     if (which == A3PO_WS_FUSED_LMHEAD) return lmhead_workspace_bytes(T);
+    if (which == A3PO_WS_FUSED_LMHEAD_LOSS) return lmhead_bwd_workspace_bytes(T, V, H);
     return 0;
 }
 

@@ -35,12 +35,30 @@ struct LossArgs {
     uint8_t *ws_flags;
 };
 
+// Workspace of the loss path: header | TokenRecord[T] (16 bytes each) | obj[T] | iw[T] | flags[T]
+struct LossWsLayout {
+    size_t records, obj, iw, flags, total;
+};
+inline LossWsLayout loss_ws_layout(int64_t T)
+{
+    auto up = [](size_t x) { return (x + 255) / 256 * 256; };
+    const size_t t = (size_t)(T > 0 ? T : 0);
+    LossWsLayout l;
+    l.records = 256;
+    l.obj = l.records + up(t * 16);
+    l.iw = l.obj + up(t * sizeof(float));
+    l.flags = l.iw + up(t * sizeof(float));
+    l.total = l.flags + up(t);
+    return l;
+}
+
 // true when the single-pass register-resident kernel can take these rows
 bool rows_fit_on_chip(int dt, int64_t V, int64_t ld, const void *z, const void *dz);
 
 hipError_t launch_loss_prep(const LossArgs &a, hipStream_t s);
 hipError_t launch_loss_rows(const LossArgs &a, hipStream_t s);
 hipError_t launch_loss_finish(const LossArgs &a, hipStream_t s);
+hipError_t launch_reset_row_queue(void *ws_header, hipStream_t s);  // before re-running the row kernel on one header
 
 hipError_t launch_token_logprobs(const void *z, int dt, int64_t T, int64_t V, int64_t ld, const int32_t *chosen,
                                  float *logp, float *lse, void *chosen_logit, hipStream_t s);
@@ -52,5 +70,7 @@ hipError_t launch_grpo_advantages(const float *rewards, int64_t S, int32_t G, fl
 size_t lmhead_workspace_bytes(int64_t T);
 hipError_t launch_fused_lmhead_logprob(const void *hidden, const void *weight, int64_t T, int64_t H, int64_t V,
                                        const int32_t *chosen, float *logp, float *lse, void *workspace, hipStream_t s);
+
+size_t lmhead_bwd_workspace_bytes(int64_t T, int64_t V, int64_t H);
 
 }  // namespace a3po

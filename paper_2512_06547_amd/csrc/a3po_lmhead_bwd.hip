@@ -1,0 +1,174 @@
+// A-3PO loss forward + backward starting from hidden states and the LM-head weight.
+//
+// The logits of a chunk of tokens are materialised in bfloat16 (chunk x V), run through the fused
+// row kernel in place (log-softmax, proximal interpolation, clipped surrogate, gradient rows), and
+// the gradient chunk is contracted back:  dh = dz W  and  dW += dz^T h.  With 288 GB of HBM a
+// chunk of 8,192 tokens (2.5 GB at V = 151,936) is small change, so the projection is computed
+// once (6 T V H flops in total) instead of being recomputed for the backward pass.
+//
+// The three contractions are plain GEMMs and go to rocBLAS (bfloat16 in, fp32 accumulate); dW is
+// accumulated across chunks in fp32 and rounded to bfloat16 once at the end.  Everything between
+// the GEMMs is this library's own kernels.
+#include <mutex>
+
+#include <rocblas/rocblas.h>
+
+#include "a3po_common.h"
+#include "a3po_launch.h"
+
+namespace a3po {
+
+constexpr int64_t kLmBwdChunk = 8192;  // tokens whose logits live in HBM at a time
+
+struct LmBwdLayout {
+    size_t loss_ws, zchunk, dwacc, total;
+    int64_t chunk;
+};
+
+static LmBwdLayout lmhead_bwd_layout(int64_t T, int64_t V, int64_t H)
+{
+    auto up = [](size_t x) { return (x + 255) / 256 * 256; };
+    LmBwdLayout l;
+    l.chunk = T < kLmBwdChunk ? (T > 0 ? T : 1) : kLmBwdChunk;
+    l.loss_ws = 0;
+    l.zchunk = up(loss_ws_layout(T).total);
+    l.dwacc = l.zchunk + up((size_t)l.chunk * (size_t)V * 2);
+    l.total = l.dwacc + up((size_t)V * (size_t)H * sizeof(float));
+    return l;
+}
+
+size_t lmhead_bwd_workspace_bytes(int64_t T, int64_t V, int64_t H) { return lmhead_bwd_layout(T, V, H).total; }
+
+__global__ void f32_to_bf16_kernel(const float *__restrict__ src, uint16_t *__restrict__ dst, size_t n)
+{
+    const size_t i = ((size_t)blockIdx.x * blockDim.x + threadIdx.x) * 2;
+    if (i + 1 < n) {
+        *reinterpret_cast<uint32_t *>(dst + i) = pack_bf16x2(src[i], src[i + 1]);
+    } else if (i < n) {
+        dst[i] = (uint16_t)(pack_bf16x2(src[i], 0.0f) & 0xFFFFu);
+    }
+}
+
+static rocblas_handle blas_handle()
+{
+    static rocblas_handle handle = nullptr;
+    static std::once_flag once;
+    std::call_once(once, [] {
+        if (rocblas_create_handle(&handle) != rocblas_status_success) handle = nullptr;
+    });
+    return handle;
+}
+
+// column-major C[m,n] = alpha op(A) op(B) + beta C with bf16 A, B and fp32 accumulation
+static bool gemm_bf16(rocblas_handle hd, rocblas_operation ta, rocblas_operation tb, int64_t m, int64_t n, int64_t k,
+                      const void *A, int64_t lda, const void *B, int64_t ldb, float beta, void *C, int64_t ldc,
+                      rocblas_datatype c_type)
+{
+    const float alpha = 1.0f;
+    return rocblas_gemm_ex(hd, ta, tb, (rocblas_int)m, (rocblas_int)n, (rocblas_int)k, &alpha, A, rocblas_datatype_bf16_r,
+                           (rocblas_int)lda, B, rocblas_datatype_bf16_r, (rocblas_int)ldb, &beta, C, c_type,
+                           (rocblas_int)ldc, C, c_type, (rocblas_int)ldc, rocblas_datatype_f32_r,
+                           rocblas_gemm_algo_standard, 0, 0) == rocblas_status_success;
+}
+
+}  // namespace a3po
+
+using namespace a3po;
+
+extern "C" int a3po_fused_lmhead_loss_fwd_bwd(const void *hidden, const void *weight, int64_t T, int64_t H, int64_t V,
+                                              const int32_t *chosen, const float *logp_behav, const int32_t *versions,
+                                              int32_t current_version, const float *advantages,
+                                              const uint8_t *loss_mask, float clip_eps, float denom, void *dhidden,
+                                              void *dweight, float *logp_out, float *logp_prox_out, float *loss_out,
+                                              a3po_stats *stats_out, void *workspace, size_t workspace_bytes,
+                                              void *stream)
+{
+    auto aligned = [](const void *p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; };
+    if (T < 0 || V <= 0 || H <= 0 || H % 8 != 0 || V % 8 != 0 || V > (int64_t)0x7FFFFFFF) return A3PO_E_SIZE;
+    if (!(clip_eps >= 0.0f && clip_eps < 1.0f) || denom != denom) return A3PO_E_VALUE;
+    if (!loss_out || !weight || !dweight) return A3PO_E_NULL;
+    if (T > 0 && (!hidden || !dhidden || !chosen || !logp_behav || !versions || !advantages || !loss_mask || !logp_out))
+        return A3PO_E_NULL;
+    if (!aligned(hidden, 16) || !aligned(weight, 16) || !aligned(dhidden, 16) || !aligned(dweight, 16))
+        return A3PO_E_ALIGN;
+    const LmBwdLayout lay = lmhead_bwd_layout(T, V, H);
+    if (!workspace || workspace_bytes < lay.total) return A3PO_E_WORKSPACE;
+    if (!aligned(workspace, 256)) return A3PO_E_ALIGN;
+
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    rocblas_handle hd = blas_handle();
+    if (!hd || rocblas_set_stream(hd, s) != rocblas_status_success) return A3PO_E_LAUNCH;
+    if (rocblas_set_pointer_mode(hd, rocblas_pointer_mode_host) != rocblas_status_success) return A3PO_E_LAUNCH;
+
+    char *ws = static_cast<char *>(workspace);
+    const LossWsLayout lw = loss_ws_layout(T);
+    uint16_t *zc = reinterpret_cast<uint16_t *>(ws + lay.zchunk);
+    float *dwacc = reinterpret_cast<float *>(ws + lay.dwacc);
+    const uint16_t *h = static_cast<const uint16_t *>(hidden);
+    uint16_t *dh = static_cast<uint16_t *>(dhidden);
+
+    LossArgs a;
+    a.z = zc;
+    a.dz = zc;
+    a.dt = A3PO_BF16;
+    a.T = T;
+    a.V = V;
+    a.ld = V;
+    a.chosen = chosen;
+    a.lb = logp_behav;
+    a.versions = versions;
+    a.current_version = current_version;
+    a.adv = advantages;
+    a.mask = loss_mask;
+    a.clip_eps = clip_eps;
+    a.denom = denom;
+    a.logp_out = logp_out;
+    a.prox_out = logp_prox_out;
+    a.loss_out = loss_out;
+    a.stats_out = stats_out;
+    a.ws_header = ws;
+    a.ws_records = reinterpret_cast<TokenRecord *>(ws + lw.records);
+    a.ws_obj = reinterpret_cast<float *>(ws + lw.obj);
+    a.ws_iw = reinterpret_cast<float *>(ws + lw.iw);
+    a.ws_flags = reinterpret_cast<uint8_t *>(ws + lw.flags);
+
+    // token count, 1/N and the per-token records for the whole batch
+    if (launch_loss_prep(a, s) != hipSuccess) return A3PO_E_LAUNCH;
+
+    for (int64_t c0 = 0; c0 < T; c0 += lay.chunk) {
+        const int64_t n = T - c0 < lay.chunk ? T - c0 : lay.chunk;
+        // logits of the chunk: z^T [V, n] = W [H, V]^T h_chunk [H, n]   (column-major views)
+        if (!gemm_bf16(hd, rocblas_operation_transpose, rocblas_operation_none, V, n, H, weight, H, h + c0 * H, H, 0.0f,
+                       zc, V, rocblas_datatype_bf16_r))
+            return A3PO_E_LAUNCH;
+        // loss forward + gradient rows over the chunk, in place
+        LossArgs c = a;
+        c.T = n;
+        c.ws_records = a.ws_records + c0;
+        c.logp_out = logp_out + c0;
+        c.prox_out = logp_prox_out ? logp_prox_out + c0 : nullptr;
+        c.ws_obj = a.ws_obj + c0;
+        c.ws_iw = a.ws_iw + c0;
+        c.ws_flags = a.ws_flags + c0;
+        if (c0 > 0 && launch_reset_row_queue(ws, s) != hipSuccess) return A3PO_E_LAUNCH;
+        if (launch_loss_rows(c, s) != hipSuccess) return A3PO_E_LAUNCH;
+        // dh_chunk^T [H, n] = W [H, V] dz^T [V, n]
+        if (!gemm_bf16(hd, rocblas_operation_none, rocblas_operation_none, H, n, V, weight, H, zc, V, 0.0f, dh + c0 * H,
+                       H, rocblas_datatype_bf16_r))
+            return A3PO_E_LAUNCH;
+        // dW^T [H, V] += h_chunk [H, n] (dz^T [V, n])^T       (fp32 accumulator across chunks)
+        if (!gemm_bf16(hd, rocblas_operation_none, rocblas_operation_transpose, H, V, n, h + c0 * H, H, zc, V,
+                       c0 == 0 ? 0.0f : 1.0f, dwacc, H, rocblas_datatype_f32_r))
+            return A3PO_E_LAUNCH;
+    }
+    if (launch_loss_finish(a, s) != hipSuccess) return A3PO_E_LAUNCH;
+    const size_t nw = (size_t)V * (size_t)H;
+    if (T == 0) {
+        if (hipMemsetAsync(dweight, 0, nw * 2, s) != hipSuccess) return A3PO_E_LAUNCH;
+    } else {
+        hipLaunchKernelGGL(f32_to_bf16_kernel, dim3((unsigned)((nw / 2 + 255) / 256)), dim3(256), 0, s, dwacc,
+                           static_cast<uint16_t *>(dweight), nw);
+        if (hipGetLastError() != hipSuccess) return A3PO_E_LAUNCH;
+    }
+    return A3PO_OK;
+}

@@ -163,6 +163,14 @@ hipError_t launch_loss_prep(const LossArgs &a, hipStream_t s)
     return hipGetLastError();
 }
 
+__global__ void reset_row_queue_kernel(void *ws_header) { *row_queue_of(ws_header) = 0u; }
+
+hipError_t launch_reset_row_queue(void *ws_header, hipStream_t s)
+{
+    hipLaunchKernelGGL(reset_row_queue_kernel, dim3(1), dim3(1), 0, s, ws_header);
+    return hipGetLastError();
+}
+
 hipError_t launch_loss_finish(const LossArgs &a, hipStream_t s)
 {
     hipLaunchKernelGGL(loss_finish_kernel, dim3(1), dim3(kTokThreads), 0, s, a.ws_obj, a.ws_iw, a.ws_flags, a.T,

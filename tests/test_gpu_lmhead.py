@@ -91,3 +91,63 @@ def test_fused_lmhead_full_vocabulary_sampled_tokens(a3po):
     ref = oracle.token_logprobs(z, y[rows].copy())
     close(lse.cpu().numpy()[rows], ref["lse"], "lse")
     close(logp.cpu().numpy()[rows], ref["logp"], "logp")
+
+
+# ------------------------------------------------------------------------------------------ forward + backward
+
+def _bf16_round(x):
+    """float64 array -> nearest bfloat16 (RNE) as bit patterns and as float64 values"""
+    bits = bf16_bits(x)
+    return bits, synth.bf16_bits_to_f64(bits)
+
+
+@pytest.mark.parametrize("T,H,V", [(300, 64, 1000), (1, 8, 8), (8192 + 300, 64, 512)])
+def test_fused_lmhead_loss_fwd_bwd(a3po, T, H, V):
+    """The oracle follows the same staging as the GPU path (logits rounded once to bfloat16, gradient
+    rows rounded to bfloat16 before the two contractions), in fp64 otherwise.  Tolerances:
+    log-probs one bfloat16 ulp of the chosen logit (a rounding tie may fall the other way after fp32
+    accumulation) - in practice they agree to 1e-5; dh, dW: 2^-7 |ref| + 2^-9 sum |dz| |operand|
+    (bfloat16 output rounding plus fp32 accumulation of bfloat16 products)."""
+    r = np.random.default_rng(T + 7 * V)
+    cur = 50
+    h = bf16_bits(r.standard_normal((T, H)))
+    W = bf16_bits(r.standard_normal((V, H)) * (2.0 / np.sqrt(H)))
+    y = r.integers(0, V, T).astype(np.int32)
+    mask = (r.random(T) < 0.8).astype(np.uint8)
+    mask[0] = 1
+    ver = (cur - r.integers(0, 5, T)).astype(np.int32)
+    adv = r.standard_normal(T).astype(np.float32)
+    z = oracle.lmhead_logits(h, W)
+    zb, zr = _bf16_round(z)
+    lt = oracle.token_logprobs(zb, y)["logp"]
+    lb = synth.behav_from_target(lt, (r.standard_normal(T) * 0.15).astype(np.float32))
+    ref = oracle.loss_fwd_bwd(zb, y, lb, ver, cur, adv, mask, 0.2)
+    dzb, dzr = _bf16_round(ref["dz"])
+    dh_ref, dw_ref = oracle.lmhead_backward(dzr, h, W)
+    dh_abs, dw_abs = oracle.lmhead_backward(np.abs(dzr), h & 0x7FFF, W & 0x7FFF)
+
+    dev = lambda a: torch.from_numpy(a).cuda()
+    out = a3po.fused_lmhead_loss_fwd_bwd(dev(h).view(torch.bfloat16), dev(W).view(torch.bfloat16), dev(y), dev(lb),
+                                         dev(ver), cur, dev(adv), dev(mask), 0.2)
+    torch.cuda.synchronize()
+    st = a3po.stats_to_dict(out["stats"])
+    assert st["n_tokens"] == ref["stats"]["n_tokens"]
+    logp = out["logp"].cpu().numpy().astype(np.float64)
+    zy = np.abs(zr[np.arange(T), y])
+    assert (np.abs(logp - ref["logp"]) <= 2.0 ** -7 * np.maximum(1.0, zy) * (mask == 1) + 1e-30).all()
+    assert np.quantile(np.abs(logp - ref["logp"]), 0.99) < 2e-5
+    N = max(1, st["n_tokens"])
+    loss = float(out["loss"].cpu()[0])
+    sur = oracle.surrogate(ref["logp"], lb, ver, cur, adv, ref["eff_mask"], 0.2)
+    scale = (np.abs(sur["obj"]) * ref["eff_mask"]).sum() / N
+    assert abs(loss - ref["loss"]) <= 1e-4 * scale + 1e-6, (loss, ref["loss"])
+    dh = out["dhidden"].float().cpu().numpy().astype(np.float64)
+    dw = out["dweight"].float().cpu().numpy().astype(np.float64)
+    bad_h = np.abs(dh - dh_ref) > 2.0 ** -7 * np.abs(dh_ref) + 2.0 ** -9 * dh_abs + 1e-30
+    bad_w = np.abs(dw - dw_ref) > 2.0 ** -7 * np.abs(dw_ref) + 2.0 ** -9 * dw_abs + 1e-30
+    # a clip decision within the boundary band may differ for a token: allow those rows of dh to differ
+    near = (np.abs(sur["r"] - 1.2) < 1e-3) | (np.abs(sur["r"] - 0.8) < 1e-3)
+    assert not bad_h[~near].any(), f"dh: {bad_h.sum()} elements off"
+    if not near.any():
+        assert not bad_w.any(), f"dW: {bad_w.sum()} elements off"
+    assert np.abs(dh_ref).max() > 0 and np.abs(dw_ref).max() > 0
