@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the A-3PO loss forward+backward hot path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 1p5b|8b|long|tiny]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 1p5b|8b|long|tiny|lmhead8b]
 
 One step = one pass of the whole path over one synthetic batch already resident in HBM:
 GRPO advantages -> mask count / token records -> fused row kernel (log-softmax + gather,
@@ -156,6 +156,102 @@ def cpu_baseline(w, synth, oracle, rows, block=2048):
     return rows / total, total
 
 
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X published dense bf16 peak
+
+
+def bench_lmhead(args, torch, a3po, synth, log):
+    """The fused LM-head workload (hidden states x LM-head weight in front of the loss path): one step =
+    GRPO advantages + a3po_fused_lmhead_loss_fwd_bwd (projection, loss, gradient rows, dh, dW).  The
+    hand-written forward-only kernel (a3po_fused_lmhead_logprob) is timed beside it."""
+    import numpy as np
+    lw = synth.LMHEAD_WORKLOADS[args.workload]
+    w = lw.tokens
+    T, H, V = w.T, lw.H, w.V
+    tk = synth.token_arrays(w)
+    t0 = time.time()
+    W = torch.empty((V, H), dtype=torch.bfloat16, device="cuda")
+    for v0 in range(0, V, 16384):
+        n = min(16384, V - v0)
+        W[v0:v0 + n].copy_(torch.from_numpy(synth.weight_rows(lw, v0, n)).view(torch.bfloat16))
+    h = torch.empty((T, H), dtype=torch.bfloat16, device="cuda")
+    for r0 in range(0, T, 16384):
+        n = min(16384, T - r0)
+        h[r0:r0 + n].copy_(torch.from_numpy(synth.hidden_rows(lw, r0, n)).view(torch.bfloat16))
+    log(f"generated hidden {T}x{H} and weight {V}x{H} in {time.time() - t0:.1f}s")
+    dev = lambda a: torch.from_numpy(a).cuda()
+    y = dev(tk["chosen"])
+    ws_f = torch.empty(a3po.workspace_bytes(T, V, H, which=1), dtype=torch.uint8, device="cuda")
+    logp, _ = a3po.fused_lmhead_logprob(h, W, y, workspace=ws_f)
+    lb = torch.clamp(logp + dev(tk["noise"]), max=0.0).contiguous()
+    ver, mask, rewards, seq_id = dev(tk["versions"]), dev(tk["mask"]), dev(tk["rewards"]), dev(tk["seq_id"])
+    ws = torch.empty(a3po.workspace_bytes(T, V, H, which=2), dtype=torch.uint8, device="cuda")
+    adv = torch.empty(T, dtype=torch.float32, device="cuda")
+
+    def step():
+        a3po.grpo_advantages(rewards, w.G, seq_id, out=adv)
+        return a3po.fused_lmhead_loss_fwd_bwd(h, W, y, lb, ver, tk["current_version"], adv, mask, w.clip_eps,
+                                              workspace=ws)
+
+    for _ in range(args.warmup):
+        out = step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        out = step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    st = a3po.stats_to_dict(out["stats"])
+    ms = dt / args.steps * 1e3
+    flops = 6.0 * T * V * H
+    tf = flops / (ms * 1e-3) / 1e12
+    log(f"fwd+bwd: {ms:.1f} ms/step, {tf:.0f} TFLOP/s on 6TVH, stats {st}")
+
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a3po.fused_lmhead_logprob(h, W, y, workspace=ws_f)
+    e0.record()
+    nf = max(1, args.steps // 2)
+    for _ in range(nf):
+        a3po.fused_lmhead_logprob(h, W, y, workspace=ws_f)
+    e1.record()
+    torch.cuda.synchronize()
+    fms = e0.elapsed_time(e1) / nf
+    ftf = 2.0 * T * V * H / (fms * 1e-3) / 1e12
+    log(f"fused forward only: {fms:.1f} ms, {ftf:.0f} TFLOP/s on 2TVH")
+
+    cpu = None
+    if args.cpu_rows > 0:
+        import oracle
+        n = 16
+        hh = synth.hidden_rows(lw, 0, n)
+        Wh = np.concatenate([synth.weight_rows(lw, v0, min(16384, V - v0)) for v0 in range(0, V, 16384)])
+        t0 = time.perf_counter()
+        z = oracle.lmhead_logits(hh, Wh)
+        oracle.token_logprobs(z, tk["chosen"][:n].copy())
+        secs = time.perf_counter() - t0
+        cpu = {"value": n / secs, "unit": "tokens/s", "cores": oracle.threads(), "kind": "oracle",
+               "sample": f"projection + log-softmax (forward only, fp64) of the first {n} tokens, {secs:.2f} s wall"}
+        log(f"oracle forward: {n / secs:.2f} tokens/s on {oracle.threads()} threads")
+
+    line = {
+        "metric": "tokens/sec and MFMA TFLOP/s (% peak) for A-3PO loss fwd+bwd through the LM head, "
+                  "hidden 4,096 x vocab 151,936, 1 GPU",
+        "value": T * args.steps / dt, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": f"{lw.name}: {w.S} seq x {w.L} tok = {T} tokens, hidden {H}, vocab {V}, bf16; logits "
+                               f"materialised 8,192 tokens at a time (6 T V H flops), {st['n_tokens']} counted tokens",
+                   "tokens": T, "hidden": H, "vocab": V, "counted_tokens": st["n_tokens"]},
+        "roofline": {"bound": "mfma", "achieved": tf, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": tf / MFMA_BF16_PEAK_TFLOPS, "traffic": None, "flops": flops,
+                     "kernel": "whole step (3 rocBLAS GEMMs per chunk + loss_rows_kernel)"},
+        "fused_forward": {"ms": fms, "roofline": {"bound": "mfma", "achieved": ftf, "peak": MFMA_BF16_PEAK_TFLOPS,
+                                                  "unit": "TFLOP/s", "frac": ftf / MFMA_BF16_PEAK_TFLOPS,
+                                                  "flops": 2.0 * T * V * H, "kernel": "lmhead_lse_kernel"}},
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(line), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -181,6 +277,9 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     a3po.lib()
     torch.cuda.set_device(0)
+    if args.workload in synth.LMHEAD_WORKLOADS:
+        bench_lmhead(args, torch, a3po, synth, log)
+        return
     w = synth.WORKLOADS[args.workload]
     b = build_inputs(w, torch, a3po, synth, log)
 
