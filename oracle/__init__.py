@@ -68,6 +68,8 @@ def _load():
         lib.a3po_oracle_loss_fwd_bwd.restype = None
         lib.a3po_oracle_loss_fwd_bwd.argtypes = [_P, ctypes.c_int, _I64, _I64, _I64, _P, _P, _P, _I32,
                                                  _P, _P, _F64, _F64, _P, _P, _P, _P, _P, _P, _P, _P, _P]
+        lib.a3po_oracle_entropy.restype = None
+        lib.a3po_oracle_entropy.argtypes = [_P, ctypes.c_int, _I64, _I64, _I64, _P]
         lib.a3po_oracle_lmhead_logits.restype = None
         lib.a3po_oracle_lmhead_logits.argtypes = [_P, _P, _I64, _I64, _P, _I64, _P]
         lib.a3po_oracle_lmhead_backward.restype = None
@@ -120,6 +122,16 @@ def token_logprobs(z, y, V=None):
     _load().a3po_oracle_token_logprobs(z.ctypes.data, dt, T, V, ld, y.ctypes.data,
                                        logp.ctypes.data, lse.ctypes.data, raw.ctypes.data)
     return dict(logp=logp, lse=lse, chosen_raw=raw)
+
+
+def entropy(z, V=None):
+    """Per-token policy entropy -sum p log p of softmax(z)."""
+    z, dt = _logits(z)
+    T, ld = z.shape
+    V = ld if V is None else V
+    out = np.empty(T)
+    _load().a3po_oracle_entropy(z.ctypes.data, dt, T, V, ld, out.ctypes.data)
+    return out
 
 
 def alpha(versions, current_version):

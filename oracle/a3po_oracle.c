@@ -369,3 +369,31 @@ void a3po_oracle_lmhead_backward(const double *dz, const uint16_t *h, const uint
             }
     }
 }
+
+/*
+ * Policy entropy per token (the paper tracks it as stability evidence, Section 4.2.2, Fig. 4):
+ *   H_t = - sum_j p_j log p_j,   p_j = exp(z_j - lse_t),   log p_j = z_j - lse_t.
+ * lse_t is recomputed here from its definition (max, sum, log), terms with p_j = 0 contribute 0.
+ */
+void a3po_oracle_entropy(const void *z, int dt, int64_t T, int64_t V, int64_t ld, double *H_out)
+{
+#pragma omp parallel for schedule(dynamic, 16)
+    for (int64_t t = 0; t < T; ++t) {
+        const int64_t off = t * ld;
+        double M = load_z(z, dt, off);
+        for (int64_t j = 1; j < V; ++j) {
+            const double v = load_z(z, dt, off + j);
+            if (v > M) M = v;
+        }
+        double S = 0.0;
+        for (int64_t j = 0; j < V; ++j) S += exp(load_z(z, dt, off + j) - M);
+        const double lse = M + log(S);
+        double H = 0.0;
+        for (int64_t j = 0; j < V; ++j) {
+            const double lp = load_z(z, dt, off + j) - lse;
+            const double p = exp(lp);
+            if (p > 0.0) H -= p * lp;
+        }
+        H_out[t] = H;
+    }
+}

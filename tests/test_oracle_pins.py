@@ -515,3 +515,41 @@ def test_lmhead_backward_against_numpy_and_finite_differences():
             Wm_[v, k] -= eps
             num_dW[v, k] = (frozen_loss(hf, Wp) - frozen_loss(hf, Wm_)) / (2 * eps)
     assert np.abs(num_dW - dW).max() < 1e-6 * np.abs(dW).max() + 1e-10
+
+
+# ----------------------------------------------------------------------------- entropy, loss variants
+
+def test_entropy_closed_forms_and_scipy():
+    import scipy.stats
+    for V in (1, 2, 9, 1000):
+        assert abs(oracle.entropy(np.full((1, V), -2.5, dtype=np.float32))[0] - math.log(V)) < 1e-12
+    # two-point distribution with logit gap g: p = sigmoid(g); H = -p log p - (1-p) log(1-p)
+    g = 1.75
+    p = 1 / (1 + math.exp(-g))
+    H = oracle.entropy(np.array([[g, 0.0]], dtype=np.float32))[0]
+    assert abs(H - (-p * math.log(p) - (1 - p) * math.log(1 - p))) < 1e-14
+    # a dominant logit: entropy -> 0, and -inf-like tails do not produce NaN
+    assert oracle.entropy(np.array([[100.0, -1000.0, -1000.0]], dtype=np.float32))[0] < 1e-30
+    z = (rng.standard_normal((6, 501)) * 3).astype(np.float32)
+    ref = scipy.stats.entropy(scipy.special.softmax(z.astype(np.float64), axis=1), axis=1)
+    assert np.allclose(oracle.entropy(z), ref, rtol=1e-12, atol=1e-13)
+    zb = bf16_bits(z)
+    assert np.allclose(oracle.entropy(zb), scipy.stats.entropy(scipy.special.softmax(synth.bf16_bits_to_f64(zb), axis=1), axis=1),
+                       rtol=1e-12, atol=1e-13)
+
+
+def test_given_prox_variant_reduces_to_the_interpolated_one_and_to_coupled_ppo():
+    n = 500
+    lt, lb = _random_logps(n)
+    A = rng.standard_normal(n)
+    m = (rng.random(n) < 0.7).astype(np.uint8)
+    ver = (30 - rng.integers(0, 9, n)).astype(np.int32)
+    a = oracle.surrogate(lt, lb, ver, 30, A, m, 0.2)
+    b = oracle.decoupled_clip(lt, lb, a["lp"], A, m, 0.2)           # "recompute": prox supplied
+    assert a["loss"] == b["loss"] and np.array_equal(a["g"], b["g"])
+    c = oracle.decoupled_clip(lt, lb, lb, A, m, 0.2)                # prox = behaviour: Eq. 1 ("sync")
+    assert abs(c["loss"] + _coupled_ppo_objective(lt, lb, A, 0.2, m)) < 1e-13 and (c["iw"] == 1).all()
+    # an arbitrary recomputed prox: importance weight and ratio multiply back to w (Eq. 2)
+    lp = lt + rng.standard_normal(n) * 0.05
+    d = oracle.decoupled_clip(lt, lb, lp, A, m, 0.2)
+    assert np.allclose(d["iw"] * d["r"], np.exp(lt - lb), rtol=1e-12)
