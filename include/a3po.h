@@ -56,7 +56,36 @@ typedef struct {
     int64_t n_bad_index;          /* mask != 0 but chosen id outside [0,V)              */
     int64_t n_negative_staleness; /* counted tokens with current_version < version      */
     float iw_min, iw_max;         /* extrema of pi_prox/pi_behav over counted tokens    */
+    float entropy_mean;           /* mean policy entropy over counted tokens when the   */
+                                  /* call computed entropies, otherwise 0               */
+    float reserved;               /* written as 0                                       */
 } a3po_stats;
+
+/* How the proximal log-prob of Eq. 2 is obtained (the three methods the paper compares,
+ * Section 4.2: "loglinear", "recompute", "sync"). */
+typedef enum {
+    A3PO_PROX_INTERP = 0, /* A-3PO: Eq. 3 with the staleness coefficient of Eq. 4             */
+    A3PO_PROX_GIVEN = 1,  /* decoupled loss with a proximal log-prob the caller computed      */
+                          /* (an extra forward pass); versions are ignored                    */
+    A3PO_PROX_BEHAV = 2   /* proximal = behaviour policy: the coupled objective of Eq. 1      */
+                          /* (importance weight 1); versions are ignored                      */
+} a3po_prox_mode;
+
+/* Optional extras of a3po_loss_fwd_bwd_ex.  Host struct, read during the call only.
+ * A zero-filled struct selects the behaviour of a3po_loss_fwd_bwd. */
+typedef struct {
+    int32_t prox_mode;         /* a3po_prox_mode                                                */
+    int32_t reserved;          /* must be 0                                                     */
+    const float *logp_prox_in; /* device [T]; required for A3PO_PROX_GIVEN, ignored otherwise   */
+    float *entropy_out;        /* device [T], nullable: policy entropy -sum_j p_j log p_j of    */
+                               /* each counted row (0 for rows that do not enter the loss),     */
+                               /* accumulated in the same pass over the row as the log-sum-exp  */
+    float *iw_out;             /* device [T], nullable: pi_prox/pi_behav per token (0 if not    */
+                               /* counted)                                                      */
+    uint8_t *clipped_out;      /* device [T], nullable: 1 where the clipped branch is the min   */
+    void *event_before_rows;   /* hipEvent_t, nullable: recorded on `stream` immediately before */
+    void *event_after_rows;    /* and after the vocabulary-wide row kernel (never waited on)    */
+} a3po_loss_options;
 
 enum { A3PO_WS_LOSS_FWD_BWD = 0, A3PO_WS_FUSED_LMHEAD = 1, A3PO_WS_FUSED_LMHEAD_LOSS = 2 };
 
@@ -77,6 +106,16 @@ const char *a3po_strerror(int code);
 int a3po_token_logprobs(const void *logits, a3po_dtype dt, int64_t T, int64_t V, int64_t ld,
                         const int32_t *chosen, float *logp_out, float *lse_out,
                         void *chosen_logit_out, void *stream);
+
+/*
+ * a3po_token_logprobs plus the policy entropy of every row (the stability curve of Section
+ * 4.2.2, Fig. 4), accumulated in the same single read of the row:
+ *   entropy_out[t] = -sum_j p_j log p_j = lse_t - sum_j p_j z[t,j],   p_j = exp(z[t,j] - lse_t).
+ * entropy_out [T] float, required; the other arguments as above.
+ */
+int a3po_token_logprobs_entropy(const void *logits, a3po_dtype dt, int64_t T, int64_t V, int64_t ld,
+                                const int32_t *chosen, float *logp_out, float *lse_out,
+                                void *chosen_logit_out, float *entropy_out, void *stream);
 
 /*
  * Staleness-aware proximal log-prob, Eq. 3 with the coefficient of Eq. 4 (argument order
@@ -131,20 +170,28 @@ int a3po_loss_fwd_bwd(const void *logits, a3po_dtype dt, int64_t T, int64_t V, i
                       void *workspace, size_t workspace_bytes, void *stream);
 
 /*
- * Same as a3po_loss_fwd_bwd, and additionally records two caller-created hipEvent_t
- * (passed as void*, either may be NULL) on `stream` immediately before and after the
- * vocabulary-wide row kernel, so that a caller can time that kernel alone without a
- * profiler.  The events are only recorded, never waited on.
+ * a3po_loss_fwd_bwd with the extras of a3po_loss_options (opt == NULL: no extras):
+ *  - the two baselines the paper compares against through the same kernels: a caller-supplied
+ *    proximal log-prob ("recompute"; lp = logp_prox_in[t], iw = exp(lp - lb), r = exp(lt - lp)) and
+ *    the coupled objective of Eq. 1 ("sync"; lp = lb, so iw = 1 and r = exp(lt - lb));
+ *    `versions` may be NULL for both;
+ *  - per-token policy entropy (Section 4.2.2 tracks it) from the same read of the row, and its
+ *    mean over counted tokens in stats_out->entropy_mean;
+ *  - per-token importance weights and clip decisions, for histograms beyond the extrema and the
+ *    count in a3po_stats;
+ *  - two events around the row kernel, so a caller can time that kernel without a profiler.
+ * Returns A3PO_E_VALUE for an unknown prox_mode or a non-zero reserved field, A3PO_E_NULL when
+ * A3PO_PROX_GIVEN comes without logp_prox_in.
  */
-int a3po_loss_fwd_bwd_events(const void *logits, a3po_dtype dt, int64_t T, int64_t V, int64_t ld,
-                             const int32_t *chosen, const float *logp_behav,
-                             const int32_t *versions, int32_t current_version,
-                             const float *advantages, const uint8_t *loss_mask,
-                             float clip_eps, float denom,
-                             void *dlogits, float *logp_out, float *logp_prox_out,
-                             float *loss_out, a3po_stats *stats_out,
-                             void *workspace, size_t workspace_bytes, void *stream,
-                             void *event_before_rows, void *event_after_rows);
+int a3po_loss_fwd_bwd_ex(const void *logits, a3po_dtype dt, int64_t T, int64_t V, int64_t ld,
+                         const int32_t *chosen, const float *logp_behav,
+                         const int32_t *versions, int32_t current_version,
+                         const float *advantages, const uint8_t *loss_mask,
+                         float clip_eps, float denom,
+                         void *dlogits, float *logp_out, float *logp_prox_out,
+                         float *loss_out, a3po_stats *stats_out,
+                         void *workspace, size_t workspace_bytes, void *stream,
+                         const a3po_loss_options *opt);
 
 /*
  * Token log-probs straight from hidden states and the LM-head weight (the 8B-shape fused

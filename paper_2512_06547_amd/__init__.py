@@ -6,6 +6,9 @@ this package only marshals arguments.  PyTorch is used for device memory and str
 from .binding import (  # noqa: F401
     A3PO_BF16,
     A3PO_F32,
+    A3PO_PROX_BEHAV,
+    A3PO_PROX_GIVEN,
+    A3PO_PROX_INTERP,
     A3poError,
     fused_lmhead_logprob,
     fused_lmhead_loss_fwd_bwd,

@@ -15,15 +15,26 @@ _PKG = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_PKG, "liba3po.so")
 
 A3PO_F32, A3PO_BF16 = 0, 1
+A3PO_PROX_INTERP, A3PO_PROX_GIVEN, A3PO_PROX_BEHAV = 0, 1, 2
 A3PO_WS_LOSS_FWD_BWD = 0
 A3PO_WS_FUSED_LMHEAD = 1
 A3PO_WS_FUSED_LMHEAD_LOSS = 2
 
 # layout of a3po_stats (include/a3po.h)
 STATS_DTYPE = np.dtype([("n_tokens", "<i8"), ("n_clipped", "<i8"), ("n_bad_index", "<i8"),
-                        ("n_negative_staleness", "<i8"), ("iw_min", "<f4"), ("iw_max", "<f4")])
+                        ("n_negative_staleness", "<i8"), ("iw_min", "<f4"), ("iw_max", "<f4"),
+                        ("entropy_mean", "<f4"), ("reserved", "<f4")])
 
 _P, _I64, _I32, _F32, _SZ = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.c_float, ctypes.c_size_t
+
+
+
+class LossOptions(ctypes.Structure):
+    """a3po_loss_options (include/a3po.h)."""
+    _fields_ = [("prox_mode", ctypes.c_int32), ("reserved", ctypes.c_int32), ("logp_prox_in", ctypes.c_void_p),
+                ("entropy_out", ctypes.c_void_p), ("iw_out", ctypes.c_void_p), ("clipped_out", ctypes.c_void_p),
+                ("event_before_rows", ctypes.c_void_p), ("event_after_rows", ctypes.c_void_p)]
+
 
 _SIGNATURES = {
     "a3po_workspace_bytes": (_SZ, [ctypes.c_int, _I64, _I64, _I64]),
@@ -36,8 +47,9 @@ _SIGNATURES = {
                                                       _P, _P, _P, _P, _P, _P, _P, _SZ, _P]),
     "a3po_loss_fwd_bwd": (ctypes.c_int, [_P, ctypes.c_int, _I64, _I64, _I64, _P, _P, _P, _I32, _P, _P, _F32, _F32,
                                          _P, _P, _P, _P, _P, _P, _SZ, _P]),
-    "a3po_loss_fwd_bwd_events": (ctypes.c_int, [_P, ctypes.c_int, _I64, _I64, _I64, _P, _P, _P, _I32, _P, _P, _F32,
-                                                _F32, _P, _P, _P, _P, _P, _P, _SZ, _P, _P, _P]),
+    "a3po_loss_fwd_bwd_ex": (ctypes.c_int, [_P, ctypes.c_int, _I64, _I64, _I64, _P, _P, _P, _I32, _P, _P, _F32,
+                                            _F32, _P, _P, _P, _P, _P, _P, _SZ, _P, ctypes.POINTER(LossOptions)]),
+    "a3po_token_logprobs_entropy": (ctypes.c_int, [_P, ctypes.c_int, _I64, _I64, _I64, _P, _P, _P, _P, _P, _P]),
 }
 
 _lib = None
@@ -115,8 +127,9 @@ def workspace_bytes(T: int, V: int = 0, H: int = 0, which: int = A3PO_WS_LOSS_FW
     return int(lib().a3po_workspace_bytes(which, T, V, H))
 
 
-def token_logprobs(logits, chosen, V=None, want_lse=True, want_chosen_logit=True):
-    """a3po_token_logprobs -> (logp[T] f32, lse[T] f32 | None, chosen_logit[T] logits.dtype | None)."""
+def token_logprobs(logits, chosen, V=None, want_lse=True, want_chosen_logit=True, want_entropy=False):
+    """a3po_token_logprobs -> (logp[T] f32, lse[T] f32 | None, chosen_logit[T] logits.dtype | None);
+    with want_entropy, a3po_token_logprobs_entropy -> (..., entropy[T] f32)."""
     torch = _torch()
     dt, T, V, ld = _logits_meta(logits, V)
     _vec(chosen, torch.int32, T, "chosen")
@@ -124,9 +137,14 @@ def token_logprobs(logits, chosen, V=None, want_lse=True, want_chosen_logit=True
     logp = torch.empty(T, dtype=torch.float32, device=dev)
     lse = torch.empty(T, dtype=torch.float32, device=dev) if want_lse else None
     zy = torch.empty(T, dtype=logits.dtype, device=dev) if want_chosen_logit else None
-    _check(lib().a3po_token_logprobs(_ptr(logits), dt, T, V, ld, _ptr(chosen), _ptr(logp), _ptr(lse), _ptr(zy),
-                                     _stream()), "a3po_token_logprobs")
-    return logp, lse, zy
+    if not want_entropy:
+        _check(lib().a3po_token_logprobs(_ptr(logits), dt, T, V, ld, _ptr(chosen), _ptr(logp), _ptr(lse), _ptr(zy),
+                                         _stream()), "a3po_token_logprobs")
+        return logp, lse, zy
+    ent = torch.empty(T, dtype=torch.float32, device=dev)
+    _check(lib().a3po_token_logprobs_entropy(_ptr(logits), dt, T, V, ld, _ptr(chosen), _ptr(logp), _ptr(lse),
+                                             _ptr(zy), _ptr(ent), _stream()), "a3po_token_logprobs_entropy")
+    return logp, lse, zy, ent
 
 
 def proximal_interp(logp_behav, logp_theta, versions, current_version: int, want_alpha=True):
@@ -157,22 +175,28 @@ def grpo_advantages(rewards, G: int, seq_id, eps_adv: float = 1e-6, out=None):
 
 def loss_fwd_bwd(logits, chosen, logp_behav, versions, current_version: int, advantages, loss_mask,
                  clip_eps: float, denom: float = 0.0, V=None, dlogits=None, workspace=None, out=None,
-                 events=None):
-    """a3po_loss_fwd_bwd (or a3po_loss_fwd_bwd_events when ``events=(start, stop)`` raw hipEvent_t handles).
+                 events=None, prox_mode: int = A3PO_PROX_INTERP, logp_prox_in=None, want_entropy=False,
+                 want_iw=False, want_clipped=False):
+    """a3po_loss_fwd_bwd, or a3po_loss_fwd_bwd_ex when any extra is asked for: ``events=(start, stop)`` raw
+    hipEvent_t handles, ``prox_mode`` / ``logp_prox_in`` (the given-proximal and coupled variants; ``versions``
+    may then be None), ``want_entropy`` / ``want_iw`` / ``want_clipped`` per-token outputs.
 
     dlogits: None -> a new tensor like logits; or a tensor with the same dtype and strides (may be
-    ``logits`` itself for the in-place form).  ``out`` may carry preallocated
-    logp/logp_prox/loss/stats tensors from an earlier call.  Returns a dict with dlogits, logp, logp_prox,
-    loss (1-element tensor), stats (40-byte uint8 tensor, see STATS_DTYPE) and the workspace.
+    ``logits`` itself for the in-place form).  ``out`` may carry preallocated output tensors from an earlier
+    call.  Returns a dict with dlogits, logp, logp_prox, loss (1-element tensor), stats (uint8 tensor, see
+    STATS_DTYPE), the workspace, and entropy / iw / clipped when asked for.
     """
     torch = _torch()
     dt, T, V, ld = _logits_meta(logits, V)
     dev = logits.device
     _vec(chosen, torch.int32, T, "chosen")
     _vec(logp_behav, torch.float32, T, "logp_behav")
-    _vec(versions, torch.int32, T, "versions")
+    if versions is not None:
+        _vec(versions, torch.int32, T, "versions")
     _vec(advantages, torch.float32, T, "advantages")
     _vec(loss_mask, torch.uint8, T, "loss_mask")
+    if logp_prox_in is not None:
+        _vec(logp_prox_in, torch.float32, T, "logp_prox_in")
     if dlogits is None:
         dlogits = torch.empty_strided(logits.shape, logits.stride(), dtype=logits.dtype, device=dev)
     assert dlogits.dtype == logits.dtype and dlogits.shape == logits.shape and dlogits.stride() == logits.stride()
@@ -180,18 +204,35 @@ def loss_fwd_bwd(logits, chosen, logp_behav, versions, current_version: int, adv
     if workspace is None:
         workspace = torch.empty(need, dtype=torch.uint8, device=dev)
     out = {} if out is None else out
-    logp = out.get("logp") if out.get("logp") is not None else torch.empty(T, dtype=torch.float32, device=dev)
-    prox = out.get("logp_prox") if out.get("logp_prox") is not None else torch.empty(T, dtype=torch.float32, device=dev)
-    loss = out.get("loss") if out.get("loss") is not None else torch.empty(1, dtype=torch.float32, device=dev)
-    stats = out.get("stats") if out.get("stats") is not None else torch.empty(STATS_DTYPE.itemsize, dtype=torch.uint8, device=dev)
+
+    def buf(name, dtype, n=T):
+        t = out.get(name)
+        return t if t is not None else torch.empty(n, dtype=dtype, device=dev)
+
+    logp, prox = buf("logp", torch.float32), buf("logp_prox", torch.float32)
+    loss, stats = buf("loss", torch.float32, 1), buf("stats", torch.uint8, STATS_DTYPE.itemsize)
+    ent = buf("entropy", torch.float32) if want_entropy else None
+    iw = buf("iw", torch.float32) if want_iw else None
+    clipped = buf("clipped", torch.uint8) if want_clipped else None
     args = [_ptr(logits), dt, T, V, ld, _ptr(chosen), _ptr(logp_behav), _ptr(versions), int(current_version),
             _ptr(advantages), _ptr(loss_mask), float(clip_eps), float(denom), _ptr(dlogits), _ptr(logp), _ptr(prox),
             _ptr(loss), _ptr(stats), _ptr(workspace), workspace.numel(), _stream()]
-    if events is None:
+    extras = (events is not None or prox_mode != A3PO_PROX_INTERP or logp_prox_in is not None or want_entropy
+              or want_iw or want_clipped)
+    if not extras:
         _check(lib().a3po_loss_fwd_bwd(*args), "a3po_loss_fwd_bwd")
     else:
-        _check(lib().a3po_loss_fwd_bwd_events(*args, events[0], events[1]), "a3po_loss_fwd_bwd_events")
-    return dict(dlogits=dlogits, logp=logp, logp_prox=prox, loss=loss, stats=stats, workspace=workspace)
+        ev = events if events is not None else (None, None)
+        opt = LossOptions(int(prox_mode), 0, _ptr(logp_prox_in), _ptr(ent), _ptr(iw), _ptr(clipped), ev[0], ev[1])
+        _check(lib().a3po_loss_fwd_bwd_ex(*args, ctypes.byref(opt)), "a3po_loss_fwd_bwd_ex")
+    res = dict(dlogits=dlogits, logp=logp, logp_prox=prox, loss=loss, stats=stats, workspace=workspace)
+    if want_entropy:
+        res["entropy"] = ent
+    if want_iw:
+        res["iw"] = iw
+    if want_clipped:
+        res["clipped"] = clipped
+    return res
 
 
 def fused_lmhead_logprob(hidden, weight, chosen, want_lse=True, workspace=None):

@@ -59,7 +59,19 @@ int a3po_token_logprobs(const void *logits, a3po_dtype dt, int64_t T, int64_t V,
     if (T == 0) return A3PO_OK;
     if (!chosen || !logp_out) return A3PO_E_NULL;
     const hipError_t e = launch_token_logprobs(logits, (int)dt, T, V, ld, chosen, logp_out, lse_out, chosen_logit_out,
-                                               static_cast<hipStream_t>(stream));
+                                               nullptr, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? A3PO_OK : A3PO_E_LAUNCH;
+}
+
+int a3po_token_logprobs_entropy(const void *logits, a3po_dtype dt, int64_t T, int64_t V, int64_t ld,
+                                const int32_t *chosen, float *logp_out, float *lse_out, void *chosen_logit_out,
+                                float *entropy_out, void *stream)
+{
+    if (int rc = check_logits(logits, (int)dt, T, V, ld)) return rc;
+    if (T == 0) return A3PO_OK;
+    if (!chosen || !logp_out || !entropy_out) return A3PO_E_NULL;
+    const hipError_t e = launch_token_logprobs(logits, (int)dt, T, V, ld, chosen, logp_out, lse_out, chosen_logit_out,
+                                               entropy_out, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? A3PO_OK : A3PO_E_LAUNCH;
 }
 
@@ -101,18 +113,22 @@ int a3po_fused_lmhead_logprob(const void *hidden, const void *weight, int64_t T,
     return e == hipSuccess ? A3PO_OK : A3PO_E_LAUNCH;
 }
 
-int a3po_loss_fwd_bwd_events(const void *logits, a3po_dtype dt, int64_t T, int64_t V, int64_t ld,
-                             const int32_t *chosen, const float *logp_behav, const int32_t *versions,
-                             int32_t current_version, const float *advantages, const uint8_t *loss_mask,
-                             float clip_eps, float denom, void *dlogits, float *logp_out, float *logp_prox_out,
-                             float *loss_out, a3po_stats *stats_out, void *workspace, size_t workspace_bytes,
-                             void *stream, void *event_before_rows, void *event_after_rows)
+int a3po_loss_fwd_bwd_ex(const void *logits, a3po_dtype dt, int64_t T, int64_t V, int64_t ld, const int32_t *chosen,
+                         const float *logp_behav, const int32_t *versions, int32_t current_version,
+                         const float *advantages, const uint8_t *loss_mask, float clip_eps, float denom,
+                         void *dlogits, float *logp_out, float *logp_prox_out, float *loss_out,
+                         a3po_stats *stats_out, void *workspace, size_t workspace_bytes, void *stream,
+                         const a3po_loss_options *opt)
 {
+    const a3po_loss_options none = {};
+    const a3po_loss_options &o = opt ? *opt : none;
     if (int rc = check_logits(logits, (int)dt, T, V, ld)) return rc;
     if (!(clip_eps >= 0.0f && clip_eps < 1.0f) || std::isnan(denom)) return A3PO_E_VALUE;
+    if (o.prox_mode < A3PO_PROX_INTERP || o.prox_mode > A3PO_PROX_BEHAV || o.reserved != 0) return A3PO_E_VALUE;
     if (!loss_out) return A3PO_E_NULL;
-    if (T > 0 && (!dlogits || !chosen || !logp_behav || !versions || !advantages || !loss_mask || !logp_out))
-        return A3PO_E_NULL;
+    if (T > 0 && (!dlogits || !chosen || !logp_behav || !advantages || !loss_mask || !logp_out)) return A3PO_E_NULL;
+    if (T > 0 && o.prox_mode == A3PO_PROX_INTERP && !versions) return A3PO_E_NULL;
+    if (T > 0 && o.prox_mode == A3PO_PROX_GIVEN && !o.logp_prox_in) return A3PO_E_NULL;
     if (!aligned(dlogits, 16)) return A3PO_E_ALIGN;
     const WsLayout lay = loss_ws_layout(T);
     if (!workspace || workspace_bytes < lay.total) return A3PO_E_WORKSPACE;
@@ -139,6 +155,11 @@ int a3po_loss_fwd_bwd_events(const void *logits, a3po_dtype dt, int64_t T, int64
     a.prox_out = logp_prox_out;
     a.loss_out = loss_out;
     a.stats_out = stats_out;
+    a.prox_mode = o.prox_mode;
+    a.prox_in = o.logp_prox_in;
+    a.ent_out = o.entropy_out;
+    a.iw_out = o.iw_out;
+    a.clipped_out = o.clipped_out;
     a.ws_header = ws;
     a.ws_records = reinterpret_cast<TokenRecord *>(ws + lay.records);
     a.ws_obj = reinterpret_cast<float *>(ws + lay.obj);
@@ -146,10 +167,10 @@ int a3po_loss_fwd_bwd_events(const void *logits, a3po_dtype dt, int64_t T, int64
     a.ws_flags = reinterpret_cast<uint8_t *>(ws + lay.flags);
 
     if (launch_loss_prep(a, s) != hipSuccess) return A3PO_E_LAUNCH;
-    if (event_before_rows && hipEventRecord(static_cast<hipEvent_t>(event_before_rows), s) != hipSuccess)
+    if (o.event_before_rows && hipEventRecord(static_cast<hipEvent_t>(o.event_before_rows), s) != hipSuccess)
         return A3PO_E_LAUNCH;
     if (launch_loss_rows(a, s) != hipSuccess) return A3PO_E_LAUNCH;
-    if (event_after_rows && hipEventRecord(static_cast<hipEvent_t>(event_after_rows), s) != hipSuccess)
+    if (o.event_after_rows && hipEventRecord(static_cast<hipEvent_t>(o.event_after_rows), s) != hipSuccess)
         return A3PO_E_LAUNCH;
     if (launch_loss_finish(a, s) != hipSuccess) return A3PO_E_LAUNCH;
     return A3PO_OK;
@@ -161,9 +182,9 @@ int a3po_loss_fwd_bwd(const void *logits, a3po_dtype dt, int64_t T, int64_t V, i
                       float *logp_out, float *logp_prox_out, float *loss_out, a3po_stats *stats_out, void *workspace,
                       size_t workspace_bytes, void *stream)
 {
-    return a3po_loss_fwd_bwd_events(logits, dt, T, V, ld, chosen, logp_behav, versions, current_version, advantages,
-                                    loss_mask, clip_eps, denom, dlogits, logp_out, logp_prox_out, loss_out, stats_out,
-                                    workspace, workspace_bytes, stream, nullptr, nullptr);
+    return a3po_loss_fwd_bwd_ex(logits, dt, T, V, ld, chosen, logp_behav, versions, current_version, advantages,
+                                loss_mask, clip_eps, denom, dlogits, logp_out, logp_prox_out, loss_out, stats_out,
+                                workspace, workspace_bytes, stream, nullptr);
 }
 
 }  // extern "C"

@@ -146,6 +146,75 @@ __device__ __forceinline__ void fold(MaxSum &acc, const float *f)
     acc.s = s;
 }
 
+// z floored at -1e30 by one unsigned minimum: negative floats order like their bit patterns, so
+// anything below the floor (and -inf) becomes the floor; non-negative values pass unchanged.
+// Keeps p * z = 0 for z = -inf (p = 0) instead of NaN.
+__device__ __forceinline__ float finite_floor(float x)
+{
+    return __uint_as_float(min(__float_as_uint(x), 0xF149F2CAu));
+}
+
+// The same online reduction with a third running quantity u = sum_j exp(z_j - m) * z_j, from which
+// the policy entropy follows as H = lse - u / s  (H = -sum p log p, log p_j = z_j - lse).
+struct MaxSumU {
+    float m, s, u;
+};
+
+__device__ __forceinline__ MaxSumU combine(MaxSumU a, MaxSumU b)
+{
+    const float m = fmaxf(a.m, b.m);
+    const float fa = exp2_hw((a.m - m) * kLog2e), fb = exp2_hw((b.m - m) * kLog2e);
+    MaxSumU o;
+    o.m = m;
+    o.s = a.s * fa + b.s * fb;
+    o.u = a.u * fa + b.u * fb;
+    return o;
+}
+
+__device__ __forceinline__ MaxSumU wave_reduce(MaxSumU v)
+{
+#pragma unroll
+    for (int off = kWave / 2; off > 0; off >>= 1) {
+        MaxSumU o;
+        o.m = __shfl_xor(v.m, off, kWave);
+        o.s = __shfl_xor(v.s, off, kWave);
+        o.u = __shfl_xor(v.u, off, kWave);
+        v = combine(v, o);
+    }
+    return v;
+}
+
+// z = -inf (padding lanes, or a masked vocabulary entry) has exp(z - m) = 0; flooring z keeps the
+// product 0 instead of 0 * inf.
+template <int N>
+__device__ __forceinline__ void fold(MaxSumU &acc, const float *f)
+{
+    float vmax = f[0];
+#pragma unroll
+    for (int e = 1; e < N; ++e) vmax = fmaxf(vmax, f[e]);
+    const float m_new = fmaxf(acc.m, vmax);
+    const float nm = -m_new * kLog2e;
+    const float scale = exp2_hw((acc.m - m_new) * kLog2e);
+    float s = acc.s * scale, u = acc.u * scale;
+#pragma unroll
+    for (int e = 0; e < N; ++e) {
+        const float ex = exp2_hw(fmaf(f[e], kLog2e, nm));
+        s += ex;
+        u = fmaf(ex, finite_floor(f[e]), u);
+    }
+    acc.m = m_new;
+    acc.s = s;
+    acc.u = u;
+}
+
+// accumulator of a row reduction: (m, s) alone, or with u when the entropy is wanted
+template <bool ENT> struct RowAcc { using type = MaxSum; };
+template <> struct RowAcc<true> { using type = MaxSumU; };
+__device__ __forceinline__ void seed(MaxSum &a) { a.m = kNegFloor; a.s = 0.0f; }
+__device__ __forceinline__ void seed(MaxSumU &a) { a.m = kNegFloor; a.s = 0.0f; a.u = 0.0f; }
+__device__ __forceinline__ float entropy_of(const MaxSum &, float) { return 0.0f; }
+__device__ __forceinline__ float entropy_of(const MaxSumU &a, float lse) { return lse - a.u / a.s; }
+
 // ---- per-token A-3PO terms (Eq. 2 - Eq. 4 of the paper) -----------------------------------
 struct TokenTerms {
     float alpha, lp, iw, r, obj, g;
@@ -155,18 +224,30 @@ struct TokenTerms {
 // lt = log pi_theta, lb = log pi_behav.  inv_n = 1/N (0 when N == 0).
 // The ratios use the closed form of Section 3.1 (r = w^alpha, iw = w^(1-alpha), w = exp(lt-lb)),
 // which is algebraically the same as exp(lt - lp), exp(lp - lb) without the cancellation.
+// prox_mode: A3PO_PROX_INTERP (the paper's method, Eq. 3/4), A3PO_PROX_GIVEN (the proximal
+// log-prob was computed by the caller - the "recompute" baseline of Section 4.2; `version` then
+// carries its float bits), A3PO_PROX_BEHAV (proximal = behaviour policy: the coupled objective
+// of Eq. 1, the "sync" baseline).
 __device__ __forceinline__ TokenTerms token_terms(float lt, float lb, int32_t version, int32_t current_version,
-                                                  float A, float clip_eps, float inv_n)
+                                                  float A, float clip_eps, float inv_n, int prox_mode)
 {
     TokenTerms o;
-    const int64_t d = (int64_t)current_version - (int64_t)version;
-    o.negative_staleness = d < 0;
-    o.alpha = d >= 1 ? 1.0f / (float)d : 1.0f;
-    const float one_minus = 1.0f - o.alpha;
-    o.lp = o.alpha * lb + one_minus * lt;
-    const float delta = lt - lb;
-    o.r = expf(o.alpha * delta);
-    o.iw = expf(one_minus * delta);
+    if (prox_mode == A3PO_PROX_GIVEN) {
+        o.negative_staleness = false;
+        o.alpha = 0.0f;
+        o.lp = __int_as_float(version);
+        o.r = expf(lt - o.lp);
+        o.iw = expf(o.lp - lb);
+    } else {
+        const int64_t d = prox_mode == A3PO_PROX_BEHAV ? 0 : (int64_t)current_version - (int64_t)version;
+        o.negative_staleness = d < 0;
+        o.alpha = d >= 1 ? 1.0f / (float)d : 1.0f;
+        const float one_minus = 1.0f - o.alpha;
+        o.lp = o.alpha * lb + one_minus * lt;
+        const float delta = lt - lb;
+        o.r = expf(o.alpha * delta);
+        o.iw = expf(one_minus * delta);
+    }
     const float s1 = o.r * A;
     const float rc = fminf(fmaxf(o.r, 1.0f - clip_eps), 1.0f + clip_eps);
     const float s2 = rc * A;

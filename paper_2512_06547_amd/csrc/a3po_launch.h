@@ -27,6 +27,11 @@ struct LossArgs {
     float *prox_out;  // nullable
     float *loss_out;
     a3po_stats *stats_out;  // nullable
+    int prox_mode = 0;               // a3po_prox_mode
+    const float *prox_in = nullptr;  // [T], A3PO_PROX_GIVEN only
+    float *ent_out = nullptr;        // [T] policy entropy, nullable
+    float *iw_out = nullptr;         // [T] importance weights, nullable
+    uint8_t *clipped_out = nullptr;  // [T] clip decisions, nullable
     // workspace carve-up
     void *ws_header;
     TokenRecord *ws_records;  // [T], written by the prep kernel
@@ -61,7 +66,7 @@ hipError_t launch_loss_finish(const LossArgs &a, hipStream_t s);
 hipError_t launch_reset_row_queue(void *ws_header, hipStream_t s);  // before re-running the row kernel on one header
 
 hipError_t launch_token_logprobs(const void *z, int dt, int64_t T, int64_t V, int64_t ld, const int32_t *chosen,
-                                 float *logp, float *lse, void *chosen_logit, hipStream_t s);
+                                 float *logp, float *lse, void *chosen_logit, float *ent, hipStream_t s);
 hipError_t launch_proximal_interp(const float *lb, const float *lt, const int32_t *versions, int32_t current_version,
                                   int64_t T, float *lp, float *alpha, hipStream_t s);
 hipError_t launch_grpo_advantages(const float *rewards, int64_t S, int32_t G, float eps_adv, const int32_t *seq_id,

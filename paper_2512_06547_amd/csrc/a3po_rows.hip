@@ -20,21 +20,47 @@ constexpr int kRowWaves = kRowThreads / kWave;
 constexpr int kMaxVec = 20;  // 16-byte vectors per thread the fused kernel can hold
 
 // ---------------------------------------------------------------------------------------
-// block-wide (max,sum) all-reduce through LDS, two barriers; for the multi-pass kernels
-template <int WAVES>
-__device__ __forceinline__ MaxSum block_allreduce(MaxSum v, float *sm, float *ss)
+// block-wide all-reduce of a row accumulator through LDS, two barriers; for the multi-pass kernels.
+// `red` holds 3 * WAVES floats.
+__device__ __forceinline__ void put(float *red, int waves, int w, const MaxSum &v)
+{
+    red[w] = v.m;
+    red[waves + w] = v.s;
+}
+__device__ __forceinline__ void put(float *red, int waves, int w, const MaxSumU &v)
+{
+    red[w] = v.m;
+    red[waves + w] = v.s;
+    red[2 * waves + w] = v.u;
+}
+__device__ __forceinline__ void get(const float *red, int waves, int w, MaxSum &v)
+{
+    v.m = red[w];
+    v.s = red[waves + w];
+}
+__device__ __forceinline__ void get(const float *red, int waves, int w, MaxSumU &v)
+{
+    v.m = red[w];
+    v.s = red[waves + w];
+    v.u = red[2 * waves + w];
+}
+
+template <int WAVES, typename ACC>
+__device__ __forceinline__ ACC block_allreduce(ACC v, float *red)
 {
     v = wave_reduce(v);
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
-    __syncthreads();  // previous readers of sm/ss are done
-    if (lane == 0) {
-        sm[wave] = v.m;
-        ss[wave] = v.s;
-    }
+    __syncthreads();  // previous readers of red are done
+    if (lane == 0) put(red, WAVES, wave, v);
     __syncthreads();
-    MaxSum t = {sm[0], ss[0]};
+    ACC t;
+    get(red, WAVES, 0, t);
 #pragma unroll
-    for (int w = 1; w < WAVES; ++w) t = combine(t, MaxSum{sm[w], ss[w]});
+    for (int w = 1; w < WAVES; ++w) {
+        ACC o;
+        get(red, WAVES, w, o);
+        t = combine(t, o);
+    }
     return t;
 }
 
@@ -67,21 +93,62 @@ __device__ __forceinline__ void stream_store(char *p, const uint4 &v)
 }
 
 struct RowOutputs {
-    float *logp, *prox, *obj, *iw;
+    float *logp, *prox, *obj, *iw, *ent;
     uint8_t *flags;
 };
 
-template <typename DT, int NSWEEP>
+// One vector of the backward pass: f (logits) -> f (gradient entries without the chosen column's +g),
+// and for ENT the running sum of p_j z_j (elements past the row's end hold -inf: p = 0).
+template <int EPV, bool ENT>
+__device__ __forceinline__ void backward_vec(float *f, float neg_g, float nlse, float &pz)
+{
+#pragma unroll
+    for (int e = 0; e < EPV; ++e) {
+        const float p = exp2_hw(fmaf(f[e], kLog2e, nlse));
+        if constexpr (ENT) pz = fmaf(p, finite_floor(f[e]), pz);
+        f[e] = neg_g * p;
+    }
+}
+
+// Overwrites elements rem.. of a packed vector with -inf (the ragged tail of a row).
+template <typename DT>
+__device__ __forceinline__ void mask_tail(uint4 &v, int rem)
+{
+    uint32_t w[4] = {v.x, v.y, v.z, v.w};
+    if constexpr (DT::kBytes == 4) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            if (e >= rem) w[e] = 0xFF800000u;
+    } else {
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+            if (e >= rem) w[e >> 1] = (e & 1) ? ((w[e >> 1] & 0x0000FFFFu) | 0xFF800000u) : ((w[e >> 1] & 0xFFFF0000u) | 0x0000FF80u);
+    }
+    v = make_uint4(w[0], w[1], w[2], w[3]);
+}
+
+// ENT adds the policy entropy of each counted row, H = lse - sum_j p_j z_j.  The sum rides on the
+// backward pass, which evaluates every p_j anyway: one extra multiply-add per element, wave
+// partials in LDS, and thread 0 finishes the row's entropy after the *next* row's barrier (by then
+// every wave has left the backward pass), so no barrier is added.
+// The extra live values do not fit beside 19 resident vectors in 128 registers, so for long rows the
+// ENT variant parks the first STASH vectors it consumes in LDS between the forward and the backward
+// pass and issues the last STASH loads of the row only then, into the registers just freed
+// (a load pipeline of depth NSWEEP - STASH instead of NSWEEP).
+template <typename DT, int NSWEEP, bool ENT>
 __global__ __launch_bounds__(kRowThreads) void loss_rows_kernel(
     const void *z, void *dz, int64_t T, int64_t V, int64_t ld, const TokenRecord *__restrict__ records,
-    int32_t current_version, float clip_eps, const WsHeader *__restrict__ hdr, unsigned int *row_queue,
-    RowOutputs out)
+    int32_t current_version, float clip_eps, int prox_mode, const WsHeader *__restrict__ hdr,
+    unsigned int *row_queue, RowOutputs out)
 {
     constexpr int EPV = DT::kPerVec;
     constexpr int LAST = NSWEEP - 1;
+    constexpr int STASH = (ENT && NSWEEP >= 16) ? 2 : 0;  // consumed first: v[LAST], v[0]; loaded late: v[LAST-2], v[LAST-1]
     __shared__ float red_m[2][kRowWaves];
     __shared__ float red_s[2][kRowWaves];
+    __shared__ float ent_part[2][kRowWaves];
     __shared__ unsigned int next_row[2];
+    __shared__ uint4 stash[STASH ? STASH : 1][STASH ? kRowThreads : 1];
 
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1), wave = tid / kWave;
@@ -96,6 +163,19 @@ __global__ __launch_bounds__(kRowThreads) void loss_rows_kernel(
     const float inv_n = hdr->inv_n;
     const size_t row_bytes = (size_t)ld * DT::kBytes;
     int parity = 0;
+    // entropy of the previous counted row, finished after this row's barrier
+    int64_t pend_row = -1;
+    float pend_lse = 0.0f;
+    int pend_par = 0;
+    auto finish_pending_entropy = [&]() {
+        if (pend_row >= 0 && tid == 0) {
+            float sum = 0.0f;
+#pragma unroll
+            for (int w = 0; w < kRowWaves; ++w) sum += ent_part[pend_par][w];
+            out.ent[pend_row] = pend_lse - sum;
+        }
+        pend_row = -1;
+    };
 
     // Per-token inputs are uniform over the workgroup and come from the packed records the
     // prep kernel wrote (one 16-byte scalar load per row, fetched as soon as the row is known).
@@ -113,6 +193,7 @@ __global__ __launch_bounds__(kRowThreads) void loss_rows_kernel(
         __builtin_amdgcn_sched_barrier(0);
         char *out_row = reinterpret_cast<char *>(dz) + (size_t)row * row_bytes;
         const char *in_row = reinterpret_cast<const char *>(z) + (size_t)row * row_bytes;
+        const int row_par = parity;
 
         uint4 v[NSWEEP];
         float g = 0.0f, lse = 0.0f, zy = 0.0f;
@@ -128,7 +209,7 @@ __global__ __launch_bounds__(kRowThreads) void loss_rows_kernel(
             if (last_any) v[LAST] = stream_load(in_row + (size_t)LAST * kSweepBytes + voff);
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int k = 0; k < LAST; ++k) {
+            for (int k = 0; k < LAST - STASH; ++k) {
                 v[k] = stream_load(in_row + (size_t)k * kSweepBytes + voff);
                 __builtin_amdgcn_sched_barrier(0);
             }
@@ -136,14 +217,14 @@ __global__ __launch_bounds__(kRowThreads) void loss_rows_kernel(
             // ---- forward: online (max, sum) per thread, in the order the loads were issued ----
             MaxSum acc = {kNegFloor, 0.0f};
             {
+                if (last_tail) mask_tail<DT>(v[LAST], rem);  // once; the backward pass sees the same -inf
                 float f[EPV];
                 unpack<DT>(v[LAST], f);
-                if (last_tail) {
-#pragma unroll
-                    for (int e = 0; e < EPV; ++e)
-                        if (e >= rem) f[e] = -INFINITY;
-                }
                 fold<EPV>(acc, f);
+                if constexpr (STASH > 0) {
+                    stash[0][tid] = v[LAST];
+                    v[LAST - STASH] = stream_load(in_row + (size_t)(LAST - STASH) * kSweepBytes + voff);
+                }
             }
             if (tid == 0) next_row[parity] = claimed;  // the claim was issued before the row's loads
             __builtin_amdgcn_sched_barrier(0);
@@ -152,6 +233,13 @@ __global__ __launch_bounds__(kRowThreads) void loss_rows_kernel(
                 float f[EPV];
                 unpack<DT>(v[k], f);
                 fold<EPV>(acc, f);
+                if constexpr (STASH > 1) {
+                    if (k + 1 < STASH) {
+                        stash[k + 1][tid] = v[k];
+                        v[LAST - STASH + k + 1] =
+                            stream_load(in_row + (size_t)(LAST - STASH + k + 1) * kSweepBytes + voff);
+                    }
+                }
                 __builtin_amdgcn_sched_barrier(0);
             }
             zy = raw_to_float<DT>(zy_bits);
@@ -167,10 +255,12 @@ __global__ __launch_bounds__(kRowThreads) void loss_rows_kernel(
             const int64_t upcoming = (int64_t)gridDim.x + (int64_t)__builtin_amdgcn_readfirstlane(next_row[parity]);
             parity ^= 1;
             if (upcoming < T) nxt = records[upcoming];  // scalar load, lands during the backward pass
+            if constexpr (ENT) finish_pending_entropy();
 
             lse = tot.m + logf(tot.s);
             const float lt = zy - lse;
-            const TokenTerms tt = token_terms(lt, cur.lb, cur.ver, current_version, cur.A, clip_eps, inv_n);
+            const TokenTerms tt =
+                token_terms(lt, cur.lb, cur.ver, current_version, cur.A, clip_eps, inv_n, prox_mode);
             g = tt.g;
             if (tid == 0) {
                 out.logp[row] = lt;
@@ -186,6 +276,7 @@ __global__ __launch_bounds__(kRowThreads) void loss_rows_kernel(
                 next_row[parity] = claimed;
                 out.logp[row] = 0.0f;
                 if (out.prox) out.prox[row] = 0.0f;
+                if constexpr (ENT) out.ent[row] = 0.0f;
                 out.obj[row] = 0.0f;
                 out.iw[row] = 0.0f;
                 out.flags[row] = 0;
@@ -194,9 +285,11 @@ __global__ __launch_bounds__(kRowThreads) void loss_rows_kernel(
             next = (int64_t)gridDim.x + (int64_t)__builtin_amdgcn_readfirstlane(next_row[parity]);
             parity ^= 1;
             if (next < T) nxt = records[next];
+            if constexpr (ENT) finish_pending_entropy();
         }
 
-        if (g == 0.0f) {
+        const bool want_p = ENT ? live : g != 0.0f;  // the entropy needs every p_j of a counted row
+        if (!want_p) {
             // masked, invalid id, clipped, zero advantage or empty batch: the gradient row is zero
             const uint4 zero = make_uint4(0u, 0u, 0u, 0u);
 #pragma unroll
@@ -211,21 +304,32 @@ __global__ __launch_bounds__(kRowThreads) void loss_rows_kernel(
         }
 
         // ---- backward: dz = g * (onehot(y) - softmax(z)), written over the same lanes ----
+        // (with ENT a counted row whose g is 0 comes through here too and stores exact zeros)
         const float neg_g = -g;
         const float nlse = -lse * kLog2e;
+        float pz = 0.0f;
 #pragma unroll
-        for (int k = 0; k < LAST; ++k) {
+        for (int k = (STASH > 1 ? STASH - 1 : 0); k < LAST; ++k) {
             float f[EPV];
             unpack<DT>(v[k], f);
-#pragma unroll
-            for (int e = 0; e < EPV; ++e) f[e] = neg_g * exp2_hw(fmaf(f[e], kLog2e, nlse));
+            backward_vec<EPV, ENT>(f, neg_g, nlse, pz);
             stream_store(out_row + (size_t)k * kSweepBytes + voff, pack<DT>(f));
+            if constexpr (ENT) __builtin_amdgcn_sched_barrier(0);  // one vector's temporaries at a time
+        }
+        if constexpr (STASH > 1) {  // the vectors parked in LDS come last, into registers that are free by now
+#pragma unroll
+            for (int k = 0; k < STASH - 1; ++k) {
+                float f[EPV];
+                unpack<DT>(stash[k + 1][tid], f);
+                backward_vec<EPV, ENT>(f, neg_g, nlse, pz);
+                stream_store(out_row + (size_t)k * kSweepBytes + voff, pack<DT>(f));
+            }
         }
         if (last_any) {
             float f[EPV];
-            unpack<DT>(v[LAST], f);
-#pragma unroll
-            for (int e = 0; e < EPV; ++e) f[e] = neg_g * exp2_hw(fmaf(f[e], kLog2e, nlse));
+            if constexpr (STASH > 0) unpack<DT>(stash[0][tid], f);
+            else unpack<DT>(v[LAST], f);
+            backward_vec<EPV, ENT>(f, neg_g, nlse, pz);
             if (last_full) {
                 stream_store(out_row + (size_t)LAST * kSweepBytes + voff, pack<DT>(f));
             } else {
@@ -236,9 +340,21 @@ __global__ __launch_bounds__(kRowThreads) void loss_rows_kernel(
         }
         // The chosen column gets +g.  The thread that stored the vector holding column y
         // rewrites that one element afterwards (same thread, same address: program order).
-        if (tid == ((y / EPV) & (kRowThreads - 1)))
+        if (g != 0.0f && tid == ((y / EPV) & (kRowThreads - 1)))
             store_elem<DT>(out_row, y, neg_g * exp2_hw(fmaf(zy, kLog2e, nlse)) + g);
+        if constexpr (ENT) {
+#pragma unroll
+            for (int off = kWave / 2; off > 0; off >>= 1) pz += __shfl_xor(pz, off, kWave);
+            if (lane == 0) ent_part[row_par][wave] = pz;
+            pend_row = row;
+            pend_lse = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(lse)));
+            pend_par = row_par;
+        }
         row = next;
+    }
+    if constexpr (ENT) {
+        __syncthreads();
+        finish_pending_entropy();
     }
 }
 
@@ -249,7 +365,7 @@ __global__ __launch_bounds__(kRowThreads) void loss_rows_kernel(
 template <typename DT>
 __global__ __launch_bounds__(kRowThreads) void loss_rows_generic_kernel(const LossArgs a)
 {
-    __shared__ float sm[kRowWaves], ss[kRowWaves];
+    __shared__ float red[3 * kRowWaves];
     const int tid = threadIdx.x;
     const int64_t V = a.V;
     const float inv_n = reinterpret_cast<const WsHeader *>(a.ws_header)->inv_n;
@@ -265,19 +381,25 @@ __global__ __launch_bounds__(kRowThreads) void loss_rows_generic_kernel(const Lo
         if (live) {
             float m = kNegFloor;
             for (int64_t j = tid; j < V; j += blockDim.x) m = fmaxf(m, load_elem<DT>(in_row, j));
-            MaxSum t = block_allreduce<kRowWaves>(MaxSum{m, 0.0f}, sm, ss);
-            const float M = t.m;
-            float s = 0.0f;
+            const float M = block_allreduce<kRowWaves>(MaxSum{m, 0.0f}, red).m;
+            float s = 0.0f, u = 0.0f;
             const float nm = -M * kLog2e;
-            for (int64_t j = tid; j < V; j += blockDim.x) s += exp2_hw(fmaf(load_elem<DT>(in_row, j), kLog2e, nm));
-            t = block_allreduce<kRowWaves>(MaxSum{M, s}, sm, ss);
+            for (int64_t j = tid; j < V; j += blockDim.x) {
+                const float zj = load_elem<DT>(in_row, j);
+                const float ex = exp2_hw(fmaf(zj, kLog2e, nm));
+                s += ex;
+                u = fmaf(ex, finite_floor(zj), u);
+            }
+            const MaxSumU t = block_allreduce<kRowWaves>(MaxSumU{M, s, u}, red);
             lse = t.m + logf(t.s);
             const float lt = load_elem<DT>(in_row, y) - lse;
-            const TokenTerms tt = token_terms(lt, cur.lb, cur.ver, a.current_version, cur.A, a.clip_eps, inv_n);
+            const TokenTerms tt =
+                token_terms(lt, cur.lb, cur.ver, a.current_version, cur.A, a.clip_eps, inv_n, a.prox_mode);
             g = tt.g;
             if (tid == 0) {
                 a.logp_out[row] = lt;
                 if (a.prox_out) a.prox_out[row] = tt.lp;
+                if (a.ent_out) a.ent_out[row] = entropy_of(t, lse);
                 a.ws_obj[row] = tt.obj;
                 a.ws_iw[row] = tt.iw;
                 a.ws_flags[row] = (uint8_t)(kFlagCounted | (tt.clipped ? kFlagClipped : 0) |
@@ -286,6 +408,7 @@ __global__ __launch_bounds__(kRowThreads) void loss_rows_generic_kernel(const Lo
         } else if (tid == 0) {
             a.logp_out[row] = 0.0f;
             if (a.prox_out) a.prox_out[row] = 0.0f;
+            if (a.ent_out) a.ent_out[row] = 0.0f;
             a.ws_obj[row] = 0.0f;
             a.ws_iw[row] = 0.0f;
             a.ws_flags[row] = 0;
@@ -311,20 +434,22 @@ constexpr int kFwdThreads = 256;
 constexpr int kFwdWaves = kFwdThreads / kWave;
 constexpr int kFwdUnroll = 4;
 
-template <typename DT>
+template <typename DT, bool ENT>
 __global__ __launch_bounds__(kFwdThreads) void logprob_rows_kernel(const void *z, int64_t T, int64_t V, int64_t ld,
                                                                     const int32_t *chosen, float *logp, float *lse_out,
-                                                                    void *chosen_logit, int vec)
+                                                                    void *chosen_logit, float *ent_out, int vec)
 {
     constexpr int EPV = DT::kPerVec;
-    __shared__ float sm[kFwdWaves], ss[kFwdWaves];
+    using Acc = typename RowAcc<ENT>::type;
+    __shared__ float red[3 * kFwdWaves];
     const int tid = threadIdx.x;
     const int nfull = (int)(V / EPV);
     const size_t row_bytes = (size_t)ld * DT::kBytes;
 
     for (int64_t row = blockIdx.x; row < T; row += gridDim.x) {
         const char *in_row = reinterpret_cast<const char *>(z) + (size_t)row * row_bytes;
-        MaxSum acc = {kNegFloor, 0.0f};
+        Acc acc;
+        seed(acc);
         if (vec) {
             const uint4 *src = reinterpret_cast<const uint4 *>(in_row);
             int idx = tid;
@@ -354,12 +479,13 @@ __global__ __launch_bounds__(kFwdThreads) void logprob_rows_kernel(const void *z
                 fold<1>(acc, f);
             }
         }
-        const MaxSum tot = block_allreduce<kFwdWaves>(acc, sm, ss);
+        const Acc tot = block_allreduce<kFwdWaves>(acc, red);
         if (tid == 0) {
             const float lse = tot.m + logf(tot.s);
             const int32_t y = chosen[row];
             const bool ok = y >= 0 && (int64_t)y < V;
             if (lse_out) lse_out[row] = lse;
+            if constexpr (ENT) ent_out[row] = entropy_of(tot, lse);
             logp[row] = ok ? load_elem<DT>(in_row, y) - lse : 0.0f;
             if (chosen_logit) {
                 if constexpr (DT::kBytes == 4) {
@@ -407,13 +533,18 @@ static hipError_t launch_loss_rows_t(const LossArgs &a, hipStream_t s)
         return hipGetLastError();
     }
     const int sweeps = (int)((nvec + kRowThreads - 1) / kRowThreads);
-    const RowOutputs out = {a.logp_out, a.prox_out, a.ws_obj, a.ws_iw, a.ws_flags};
+    const RowOutputs out = {a.logp_out, a.prox_out, a.ws_obj, a.ws_iw, a.ent_out, a.ws_flags};
+    const WsHeader *hdr = reinterpret_cast<const WsHeader *>(a.ws_header);
+    unsigned int *queue = row_queue_of(a.ws_header);
     switch (sweeps) {
 #define A3PO_SWEEP_CASE(N) \
     case N: \
-        hipLaunchKernelGGL((loss_rows_kernel<DT, N>), dim3(grid), dim3(kRowThreads), 0, s, a.z, a.dz, a.T, a.V, a.ld, \
-                           a.ws_records, a.current_version, a.clip_eps, \
-                           reinterpret_cast<const WsHeader *>(a.ws_header), row_queue_of(a.ws_header), out); \
+        if (a.ent_out) \
+            hipLaunchKernelGGL((loss_rows_kernel<DT, N, true>), dim3(grid), dim3(kRowThreads), 0, s, a.z, a.dz, a.T, \
+                               a.V, a.ld, a.ws_records, a.current_version, a.clip_eps, a.prox_mode, hdr, queue, out); \
+        else \
+            hipLaunchKernelGGL((loss_rows_kernel<DT, N, false>), dim3(grid), dim3(kRowThreads), 0, s, a.z, a.dz, a.T, \
+                               a.V, a.ld, a.ws_records, a.current_version, a.clip_eps, a.prox_mode, hdr, queue, out); \
         break;
         A3PO_SWEEP_CASE(1) A3PO_SWEEP_CASE(2) A3PO_SWEEP_CASE(3) A3PO_SWEEP_CASE(4) A3PO_SWEEP_CASE(5)
         A3PO_SWEEP_CASE(6) A3PO_SWEEP_CASE(7) A3PO_SWEEP_CASE(8) A3PO_SWEEP_CASE(9) A3PO_SWEEP_CASE(10)
@@ -431,20 +562,29 @@ hipError_t launch_loss_rows(const LossArgs &a, hipStream_t s)
     return a.dt == A3PO_F32 ? launch_loss_rows_t<F32>(a, s) : launch_loss_rows_t<Bf16>(a, s);
 }
 
+template <typename DT>
+static void launch_logprob_rows_t(unsigned grid, hipStream_t s, const void *z, int64_t T, int64_t V, int64_t ld,
+                                  const int32_t *chosen, float *logp, float *lse, void *chosen_logit, float *ent,
+                                  int vec)
+{
+    if (ent)
+        hipLaunchKernelGGL((logprob_rows_kernel<DT, true>), dim3(grid), dim3(kFwdThreads), 0, s, z, T, V, ld, chosen,
+                           logp, lse, chosen_logit, ent, vec);
+    else
+        hipLaunchKernelGGL((logprob_rows_kernel<DT, false>), dim3(grid), dim3(kFwdThreads), 0, s, z, T, V, ld, chosen,
+                           logp, lse, chosen_logit, ent, vec);
+}
+
 hipError_t launch_token_logprobs(const void *z, int dt, int64_t T, int64_t V, int64_t ld, const int32_t *chosen,
-                                 float *logp, float *lse, void *chosen_logit, hipStream_t s)
+                                 float *logp, float *lse, void *chosen_logit, float *ent, hipStream_t s)
 {
     if (T == 0) return hipSuccess;
     const int64_t esz = dt == A3PO_F32 ? 4 : 2;
     const int vec = aligned16(z) && (ld * esz) % 16 == 0;
     const int64_t want = (int64_t)device_cu_count() * 8;
     const unsigned grid = (unsigned)(T < want ? T : want);
-    if (dt == A3PO_F32)
-        hipLaunchKernelGGL((logprob_rows_kernel<F32>), dim3(grid), dim3(kFwdThreads), 0, s, z, T, V, ld, chosen, logp,
-                           lse, chosen_logit, vec);
-    else
-        hipLaunchKernelGGL((logprob_rows_kernel<Bf16>), dim3(grid), dim3(kFwdThreads), 0, s, z, T, V, ld, chosen, logp,
-                           lse, chosen_logit, vec);
+    if (dt == A3PO_F32) launch_logprob_rows_t<F32>(grid, s, z, T, V, ld, chosen, logp, lse, chosen_logit, ent, vec);
+    else launch_logprob_rows_t<Bf16>(grid, s, z, T, V, ld, chosen, logp, lse, chosen_logit, ent, vec);
     return hipGetLastError();
 }
 

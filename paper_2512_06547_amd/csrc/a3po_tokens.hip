@@ -13,8 +13,9 @@ constexpr int kTokWaves = kTokThreads / kWave;
 // token does not enter the loss).
 __global__ __launch_bounds__(kTokThreads) void loss_prep_kernel(const int32_t *chosen, const uint8_t *mask,
                                                                 const float *lb, const int32_t *versions,
-                                                                const float *adv, int64_t T, int64_t V, float denom,
-                                                                WsHeader *hdr, TokenRecord *records)
+                                                                const float *adv, const float *prox_in, int64_t T,
+                                                                int64_t V, float denom, WsHeader *hdr,
+                                                                TokenRecord *records)
 {
     __shared__ long long s_cnt[kTokWaves], s_bad[kTokWaves];
     long long cnt = 0, bad = 0;
@@ -26,7 +27,8 @@ __global__ __launch_bounds__(kTokThreads) void loss_prep_kernel(const int32_t *c
         bad += (m && !ok) ? 1 : 0;
         TokenRecord r;
         r.y = (m && ok) ? y : -1;
-        r.ver = versions[t];
+        // a given proximal log-prob rides in the version slot; the coupled objective needs neither
+        r.ver = prox_in ? __float_as_int(prox_in[t]) : (versions ? versions[t] : 0);
         r.lb = lb[t];
         r.A = adv[t];
         records[t] = r;
@@ -59,20 +61,26 @@ __global__ __launch_bounds__(kTokThreads) void loss_prep_kernel(const int32_t *c
 
 // loss = -(1/N) sum over counted tokens of obj, accumulated in double in a fixed order
 // (thread-strided partials, then a fixed tree), so repeated runs agree bit for bit.
+// ent (nullable): per-token entropies the row kernel wrote; their mean over counted tokens goes to
+// the statistics.  iw_out / clipped_out (nullable): per-token copies for the caller.
 __global__ __launch_bounds__(kTokThreads) void loss_finish_kernel(const float *obj, const float *iw, const uint8_t *flags,
-                                                                  int64_t T, const WsHeader *hdr, float *loss_out,
-                                                                  a3po_stats *stats)
+                                                                  const float *ent, int64_t T, const WsHeader *hdr,
+                                                                  float *loss_out, a3po_stats *stats, float *iw_out,
+                                                                  uint8_t *clipped_out)
 {
-    __shared__ double s_sum[kTokWaves];
+    __shared__ double s_sum[kTokWaves], s_ent[kTokWaves];
     __shared__ long long s_clip[kTokWaves], s_neg[kTokWaves];
     __shared__ float s_min[kTokWaves], s_max[kTokWaves];
-    double sum = 0.0;
+    double sum = 0.0, esum = 0.0;
     long long clip = 0, neg = 0;
     float lo = INFINITY, hi = -INFINITY;
     for (int64_t t = threadIdx.x; t < T; t += kTokThreads) {
         const uint8_t f = flags[t];
+        if (iw_out) iw_out[t] = (f & kFlagCounted) ? iw[t] : 0.0f;
+        if (clipped_out) clipped_out[t] = (f & kFlagClipped) ? 1 : 0;
         if (f & kFlagCounted) {
             sum += (double)obj[t];
+            if (ent) esum += (double)ent[t];
             clip += (f & kFlagClipped) ? 1 : 0;
             neg += (f & kFlagNegStale) ? 1 : 0;
             const float w = iw[t];
@@ -83,6 +91,7 @@ __global__ __launch_bounds__(kTokThreads) void loss_finish_kernel(const float *o
 #pragma unroll
     for (int off = kWave / 2; off > 0; off >>= 1) {
         sum += __shfl_xor(sum, off, kWave);
+        esum += __shfl_xor(esum, off, kWave);
         clip += __shfl_xor(clip, off, kWave);
         neg += __shfl_xor(neg, off, kWave);
         lo = fminf(lo, __shfl_xor(lo, off, kWave));
@@ -91,6 +100,7 @@ __global__ __launch_bounds__(kTokThreads) void loss_finish_kernel(const float *o
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
     if (lane == 0) {
         s_sum[wave] = sum;
+        s_ent[wave] = esum;
         s_clip[wave] = clip;
         s_neg[wave] = neg;
         s_min[wave] = lo;
@@ -98,11 +108,12 @@ __global__ __launch_bounds__(kTokThreads) void loss_finish_kernel(const float *o
     }
     __syncthreads();
     if (threadIdx.x == 0) {
-        double S = 0.0;
+        double S = 0.0, E = 0.0;
         long long c = 0, n = 0;
         float mn = INFINITY, mx = -INFINITY;
         for (int w = 0; w < kTokWaves; ++w) {
             S += s_sum[w];
+            E += s_ent[w];
             c += s_clip[w];
             n += s_neg[w];
             mn = fminf(mn, s_min[w]);
@@ -116,6 +127,8 @@ __global__ __launch_bounds__(kTokThreads) void loss_finish_kernel(const float *o
             stats->n_negative_staleness = n;
             stats->iw_min = mn;
             stats->iw_max = mx;
+            stats->entropy_mean = (ent && hdr->n_counted > 0) ? (float)(E / (double)hdr->n_counted) : 0.0f;
+            stats->reserved = 0.0f;
         }
     }
 }
@@ -158,8 +171,10 @@ __global__ void grpo_advantages_kernel(const float *rewards, int64_t S, int32_t 
 
 hipError_t launch_loss_prep(const LossArgs &a, hipStream_t s)
 {
-    hipLaunchKernelGGL(loss_prep_kernel, dim3(1), dim3(kTokThreads), 0, s, a.chosen, a.mask, a.lb, a.versions, a.adv,
-                       a.T, a.V, a.denom, reinterpret_cast<WsHeader *>(a.ws_header), a.ws_records);
+    hipLaunchKernelGGL(loss_prep_kernel, dim3(1), dim3(kTokThreads), 0, s, a.chosen, a.mask, a.lb,
+                       a.prox_mode == A3PO_PROX_INTERP ? a.versions : nullptr, a.adv,
+                       a.prox_mode == A3PO_PROX_GIVEN ? a.prox_in : nullptr, a.T, a.V, a.denom,
+                       reinterpret_cast<WsHeader *>(a.ws_header), a.ws_records);
     return hipGetLastError();
 }
 
@@ -173,8 +188,9 @@ hipError_t launch_reset_row_queue(void *ws_header, hipStream_t s)
 
 hipError_t launch_loss_finish(const LossArgs &a, hipStream_t s)
 {
-    hipLaunchKernelGGL(loss_finish_kernel, dim3(1), dim3(kTokThreads), 0, s, a.ws_obj, a.ws_iw, a.ws_flags, a.T,
-                       reinterpret_cast<const WsHeader *>(a.ws_header), a.loss_out, a.stats_out);
+    hipLaunchKernelGGL(loss_finish_kernel, dim3(1), dim3(kTokThreads), 0, s, a.ws_obj, a.ws_iw, a.ws_flags, a.ent_out,
+                       a.T, reinterpret_cast<const WsHeader *>(a.ws_header), a.loss_out, a.stats_out, a.iw_out,
+                       a.clipped_out);
     return hipGetLastError();
 }
 
