@@ -81,14 +81,14 @@ def build_inputs(w, torch, a3po, synth, log):
                 rewards=dev(tk["rewards"]), seq_id=dev(tk["seq_id"]), cur=tk["current_version"], tk=tk)
 
 
-def time_steps(a3po, torch, w, b, mask, steps, warmup, dz, ws, out, adv):
+def time_steps(a3po, torch, w, b, mask, steps, warmup, dz, ws, out, adv, extra):
     """W untimed + K timed steps; returns (seconds for K steps, [ms of the row kernel per step])."""
     ev = HipEvents(steps)
 
     def step(events=None):
         a3po.grpo_advantages(b["rewards"], w.G, b["seq_id"], out=adv)
         a3po.loss_fwd_bwd(b["z"], b["chosen"], b["lb"], b["versions"], b["cur"], adv, mask, w.clip_eps,
-                          dlogits=dz, workspace=ws, out=out, events=events)
+                          dlogits=dz, workspace=ws, out=out, events=events, **extra)
 
     for _ in range(warmup):
         step()
@@ -261,6 +261,8 @@ def main():
     ap.add_argument("--cpu-rows", type=int, default=16384, help="rows of the oracle baseline sample (0 = skip)")
     ap.add_argument("--phase", default="both", choices=["both", "ragged", "ones"],
                     help="time the workload's own mask, an all-ones mask, or both (default)")
+    ap.add_argument("--entropy", action="store_true",
+                    help="also compute the per-token policy entropy in the row kernel (a3po_loss_fwd_bwd_ex)")
     ap.add_argument("--quiet", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -287,15 +289,16 @@ def main():
     ws = torch.empty(a3po.workspace_bytes(w.T, w.V), dtype=torch.uint8, device="cuda")
     adv = torch.empty(w.T, dtype=torch.float32, device="cuda")
     out = {}
+    extra = {"want_entropy": True} if args.entropy else {}
     first_mask = b["mask"] if args.phase in ("both", "ragged") else torch.ones_like(b["mask"])
     out.update(a3po.loss_fwd_bwd(b["z"], b["chosen"], b["lb"], b["versions"], b["cur"],
                                  a3po.grpo_advantages(b["rewards"], w.G, b["seq_id"], out=adv), first_mask,
-                                 w.clip_eps, dlogits=dz, workspace=ws))
+                                 w.clip_eps, dlogits=dz, workspace=ws, **extra))
     torch.cuda.synchronize()
     log(f"stats: {a3po.stats_to_dict(out['stats'])} loss={float(out['loss'].cpu()[0]):.6f}")
 
     def phase(mask, label):
-        dt_, kms_ = time_steps(a3po, torch, w, b, mask, args.steps, args.warmup, dz, ws, out, adv)
+        dt_, kms_ = time_steps(a3po, torch, w, b, mask, args.steps, args.warmup, dz, ws, out, adv, extra)
         torch.cuda.synchronize()
         st_ = a3po.stats_to_dict(out["stats"])
         kavg_ = sum(kms_) / len(kms_)
@@ -351,7 +354,8 @@ def main():
         "config": {"workload": f"{w.name}: {w.S} seq x {w.L} tok = {w.T} tokens, vocab {w.V}, {w.dtype} logits, "
                                f"GRPO group {w.G}, staleness 0..{w.stale_max}, "
                                f"{'ragged mask' if rag is not None else 'all-ones mask'} "
-                               f"({st['n_tokens']} counted tokens), separate gradient buffer",
+                               f"({st['n_tokens']} counted tokens), separate gradient buffer"
+                               f"{', per-token entropy' if args.entropy else ''}",
                    "tokens": w.T, "vocab": w.V, "counted_tokens": st["n_tokens"], "clipped_tokens": st["n_clipped"]},
         "roofline": {"bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": ach / HBM_PEAK_GBS,

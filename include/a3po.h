@@ -193,6 +193,47 @@ int a3po_loss_fwd_bwd_ex(const void *logits, a3po_dtype dt, int64_t T, int64_t V
                          void *workspace, size_t workspace_bytes, void *stream,
                          const a3po_loss_options *opt);
 
+/* ---- vocabulary-sharded variant (a tensor-parallel LM head: each shard holds a column slice) ------
+ *
+ * The vocabulary [0,V) is split into P contiguous column ranges [v0_p, v0_p + Vs_p); shard p holds
+ * logits_shard_p [T, Vs_p] (row stride ld_p; a column slice of a full matrix is such a shard with
+ * base = full + v0_p and ld = the full stride).  Forward: every shard reduces its columns to one
+ * partial per token (a3po_shard_partials); the P partial arrays are gathered into one [P, T] array
+ * (the exchange between shards is the caller's) and merged (a3po_shard_combine) into the same lse /
+ * log pi_theta / entropy the unsharded entry points give.  Backward: every shard writes its slice of
+ * the gradient from the merged values (a3po_shard_loss_bwd), evaluating Eq. 2 - Eq. 4 per token
+ * exactly as a3po_loss_fwd_bwd does, so loss and statistics come out identical on every shard.
+ * chosen[t] is always the GLOBAL token id.
+ */
+typedef struct {
+    float max;           /* max_j z[t, j] over the shard's columns                            */
+    float sum_exp;       /* sum_j exp(z[t, j] - max)                                          */
+    float chosen_logit;  /* z[t, chosen[t]] if the shard owns that column, else 0             */
+    float sum_exp_z;     /* sum_j exp(z[t, j] - max) * z[t, j]   (for the entropy)            */
+} a3po_shard_partial;
+
+/* partial_out [T].  logits_shard: dtype dt, [T, Vs], stride ld >= Vs, 16-byte aligned base; v0 >= 0 is
+ * the global id of the shard's first column.  Reads T * Vs elements once. */
+int a3po_shard_partials(const void *logits_shard, a3po_dtype dt, int64_t T, int64_t Vs, int64_t ld,
+                        const int32_t *chosen, int64_t v0, a3po_shard_partial *partial_out, void *stream);
+
+/* partials [P, T] (shard-major), merged in ascending shard order.  V = full vocabulary size (a chosen id
+ * outside [0,V) gives logp 0).  logp_out [T]; lse_out, entropy_out [T] nullable. */
+int a3po_shard_combine(const a3po_shard_partial *partials, int32_t P, int64_t T, const int32_t *chosen, int64_t V,
+                       float *logp_out, float *lse_out, float *entropy_out, void *stream);
+
+/* Loss and this shard's gradient slice from the merged log pi_theta and lse (both [T], as written by
+ * a3po_shard_combine):  dlogits_shard[t, j] = g_t ([v0 + j == chosen[t]] - exp(z[t, j] - lse[t])).
+ * Per-token arguments, loss_out, stats_out, workspace (A3PO_WS_LOSS_FWD_BWD size) and error codes as in
+ * a3po_loss_fwd_bwd; dlogits_shard may alias logits_shard exactly.  opt (nullable): prox_mode,
+ * logp_prox_in, iw_out and clipped_out are honoured; entropy_out and the events are ignored. */
+int a3po_shard_loss_bwd(const void *logits_shard, a3po_dtype dt, int64_t T, int64_t Vs, int64_t ld, int64_t v0,
+                        int64_t V, const int32_t *chosen, const float *logp_theta, const float *lse,
+                        const float *logp_behav, const int32_t *versions, int32_t current_version,
+                        const float *advantages, const uint8_t *loss_mask, float clip_eps, float denom,
+                        void *dlogits_shard, float *logp_prox_out, float *loss_out, a3po_stats *stats_out,
+                        void *workspace, size_t workspace_bytes, void *stream, const a3po_loss_options *opt);
+
 /*
  * Token log-probs straight from hidden states and the LM-head weight (the 8B-shape fused
  * workload; the paper itself starts from log pi_theta and never mentions the projection):

@@ -18,6 +18,9 @@ from .binding import (  # noqa: F401
     lib_path,
     loss_fwd_bwd,
     proximal_interp,
+    shard_combine,
+    shard_loss_bwd,
+    shard_partials,
     stats_to_dict,
     strerror,
     token_logprobs,

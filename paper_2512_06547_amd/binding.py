@@ -49,6 +49,11 @@ _SIGNATURES = {
                                          _P, _P, _P, _P, _P, _P, _SZ, _P]),
     "a3po_loss_fwd_bwd_ex": (ctypes.c_int, [_P, ctypes.c_int, _I64, _I64, _I64, _P, _P, _P, _I32, _P, _P, _F32,
                                             _F32, _P, _P, _P, _P, _P, _P, _SZ, _P, ctypes.POINTER(LossOptions)]),
+    "a3po_shard_partials": (ctypes.c_int, [_P, ctypes.c_int, _I64, _I64, _I64, _P, _I64, _P, _P]),
+    "a3po_shard_combine": (ctypes.c_int, [_P, _I32, _I64, _P, _I64, _P, _P, _P, _P]),
+    "a3po_shard_loss_bwd": (ctypes.c_int, [_P, ctypes.c_int, _I64, _I64, _I64, _I64, _I64, _P, _P, _P, _P, _P, _I32,
+                                           _P, _P, _F32, _F32, _P, _P, _P, _P, _P, _SZ, _P,
+                                           ctypes.POINTER(LossOptions)]),
     "a3po_token_logprobs_entropy": (ctypes.c_int, [_P, ctypes.c_int, _I64, _I64, _I64, _P, _P, _P, _P, _P, _P]),
 }
 
@@ -228,6 +233,71 @@ def loss_fwd_bwd(logits, chosen, logp_behav, versions, current_version: int, adv
     res = dict(dlogits=dlogits, logp=logp, logp_prox=prox, loss=loss, stats=stats, workspace=workspace)
     if want_entropy:
         res["entropy"] = ent
+    if want_iw:
+        res["iw"] = iw
+    if want_clipped:
+        res["clipped"] = clipped
+    return res
+
+
+def shard_partials(logits_shard, chosen, v0: int, Vs=None, out=None):
+    """a3po_shard_partials -> partial[T, 4] f32 (max, sum_exp, chosen_logit, sum_exp_z) of one column shard."""
+    torch = _torch()
+    dt, T, Vs, ld = _logits_meta(logits_shard, Vs)
+    _vec(chosen, torch.int32, T, "chosen")
+    part = torch.empty((T, 4), dtype=torch.float32, device=logits_shard.device) if out is None else out
+    assert part.is_contiguous() and part.dtype == torch.float32 and part.numel() == 4 * T
+    _check(lib().a3po_shard_partials(_ptr(logits_shard), dt, T, Vs, ld, _ptr(chosen), int(v0), _ptr(part), _stream()),
+           "a3po_shard_partials")
+    return part
+
+
+def shard_combine(partials, chosen, V: int, want_lse=True, want_entropy=False):
+    """a3po_shard_combine on partials[P, T, 4] -> (logp[T], lse[T] | None, entropy[T] | None)."""
+    torch = _torch()
+    assert partials.is_cuda and partials.dtype == torch.float32 and partials.is_contiguous() and partials.dim() == 3
+    P, T = partials.shape[0], partials.shape[1]
+    _vec(chosen, torch.int32, T, "chosen")
+    dev = partials.device
+    logp = torch.empty(T, dtype=torch.float32, device=dev)
+    lse = torch.empty(T, dtype=torch.float32, device=dev) if want_lse else None
+    ent = torch.empty(T, dtype=torch.float32, device=dev) if want_entropy else None
+    _check(lib().a3po_shard_combine(_ptr(partials), P, T, _ptr(chosen), int(V), _ptr(logp), _ptr(lse), _ptr(ent),
+                                    _stream()), "a3po_shard_combine")
+    return logp, lse, ent
+
+
+def shard_loss_bwd(logits_shard, v0: int, V: int, chosen, logp_theta, lse, logp_behav, versions, current_version: int,
+                   advantages, loss_mask, clip_eps: float, denom: float = 0.0, Vs=None, dlogits=None, workspace=None,
+                   prox_mode: int = A3PO_PROX_INTERP, logp_prox_in=None, want_iw=False, want_clipped=False):
+    """a3po_shard_loss_bwd -> dict(dlogits (the shard's slice), logp_prox, loss, stats, workspace[, iw, clipped])."""
+    torch = _torch()
+    dt, T, Vs, ld = _logits_meta(logits_shard, Vs)
+    dev = logits_shard.device
+    _vec(chosen, torch.int32, T, "chosen")
+    for name, t in (("logp_theta", logp_theta), ("lse", lse), ("logp_behav", logp_behav), ("advantages", advantages)):
+        _vec(t, torch.float32, T, name)
+    if versions is not None:
+        _vec(versions, torch.int32, T, "versions")
+    _vec(loss_mask, torch.uint8, T, "loss_mask")
+    if dlogits is None:
+        dlogits = torch.empty_strided(logits_shard.shape, logits_shard.stride(), dtype=logits_shard.dtype, device=dev)
+    assert dlogits.dtype == logits_shard.dtype and dlogits.shape == logits_shard.shape
+    assert dlogits.stride() == logits_shard.stride()
+    if workspace is None:
+        workspace = torch.empty(workspace_bytes(T, V), dtype=torch.uint8, device=dev)
+    prox = torch.empty(T, dtype=torch.float32, device=dev)
+    loss = torch.empty(1, dtype=torch.float32, device=dev)
+    stats = torch.empty(STATS_DTYPE.itemsize, dtype=torch.uint8, device=dev)
+    iw = torch.empty(T, dtype=torch.float32, device=dev) if want_iw else None
+    clipped = torch.empty(T, dtype=torch.uint8, device=dev) if want_clipped else None
+    opt = LossOptions(int(prox_mode), 0, _ptr(logp_prox_in), None, _ptr(iw), _ptr(clipped), None, None)
+    _check(lib().a3po_shard_loss_bwd(_ptr(logits_shard), dt, T, Vs, ld, int(v0), int(V), _ptr(chosen),
+                                     _ptr(logp_theta), _ptr(lse), _ptr(logp_behav), _ptr(versions),
+                                     int(current_version), _ptr(advantages), _ptr(loss_mask), float(clip_eps),
+                                     float(denom), _ptr(dlogits), _ptr(prox), _ptr(loss), _ptr(stats), _ptr(workspace),
+                                     workspace.numel(), _stream(), ctypes.byref(opt)), "a3po_shard_loss_bwd")
+    res = dict(dlogits=dlogits, logp_prox=prox, loss=loss, stats=stats, workspace=workspace)
     if want_iw:
         res["iw"] = iw
     if want_clipped:

@@ -10,7 +10,7 @@ ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 OBJ = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "liba3po.so")
-SOURCES = ["a3po_api.hip", "a3po_rows.hip", "a3po_tokens.hip", "a3po_lmhead.hip", "a3po_lmhead_bwd.hip"]
+SOURCES = ["a3po_api.hip", "a3po_rows.hip", "a3po_tokens.hip", "a3po_shard.hip", "a3po_lmhead.hip", "a3po_lmhead_bwd.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 # packed fp32 VALU forms are switched off for every device translation unit
 # (the atomic optimizer would turn the row queue's one-lane atomic into a wave-wide scan that

@@ -187,4 +187,90 @@ int a3po_loss_fwd_bwd(const void *logits, a3po_dtype dt, int64_t T, int64_t V, i
                                 workspace, workspace_bytes, stream, nullptr);
 }
 
+int a3po_shard_partials(const void *logits_shard, a3po_dtype dt, int64_t T, int64_t Vs, int64_t ld,
+                        const int32_t *chosen, int64_t v0, a3po_shard_partial *partial_out, void *stream)
+{
+    if (int rc = check_logits(logits_shard, (int)dt, T, Vs, ld)) return rc;
+    if (v0 < 0 || v0 + Vs > (int64_t)0x7FFFFFFF) return A3PO_E_SIZE;
+    if (T == 0) return A3PO_OK;
+    if (!chosen || !partial_out) return A3PO_E_NULL;
+    if (!aligned(partial_out, 16)) return A3PO_E_ALIGN;
+    const hipError_t e = launch_shard_partials(logits_shard, (int)dt, T, Vs, ld, chosen, v0, partial_out,
+                                               static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? A3PO_OK : A3PO_E_LAUNCH;
+}
+
+int a3po_shard_combine(const a3po_shard_partial *partials, int32_t P, int64_t T, const int32_t *chosen, int64_t V,
+                       float *logp_out, float *lse_out, float *entropy_out, void *stream)
+{
+    if (T < 0 || P <= 0 || V <= 0) return A3PO_E_SIZE;
+    if (T == 0) return A3PO_OK;
+    if (!partials || !chosen || !logp_out) return A3PO_E_NULL;
+    if (!aligned(partials, 16)) return A3PO_E_ALIGN;
+    const hipError_t e = launch_shard_combine(partials, P, T, chosen, V, logp_out, lse_out, entropy_out,
+                                              static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? A3PO_OK : A3PO_E_LAUNCH;
+}
+
+int a3po_shard_loss_bwd(const void *logits_shard, a3po_dtype dt, int64_t T, int64_t Vs, int64_t ld, int64_t v0,
+                        int64_t V, const int32_t *chosen, const float *logp_theta, const float *lse,
+                        const float *logp_behav, const int32_t *versions, int32_t current_version,
+                        const float *advantages, const uint8_t *loss_mask, float clip_eps, float denom,
+                        void *dlogits_shard, float *logp_prox_out, float *loss_out, a3po_stats *stats_out,
+                        void *workspace, size_t workspace_bytes, void *stream, const a3po_loss_options *opt)
+{
+    const a3po_loss_options none = {};
+    const a3po_loss_options &o = opt ? *opt : none;
+    if (int rc = check_logits(logits_shard, (int)dt, T, Vs, ld)) return rc;
+    if (v0 < 0 || V <= 0 || v0 + Vs > V || V > (int64_t)0x7FFFFFFF) return A3PO_E_SIZE;
+    if (!(clip_eps >= 0.0f && clip_eps < 1.0f) || std::isnan(denom)) return A3PO_E_VALUE;
+    if (o.prox_mode < A3PO_PROX_INTERP || o.prox_mode > A3PO_PROX_BEHAV || o.reserved != 0) return A3PO_E_VALUE;
+    if (!loss_out) return A3PO_E_NULL;
+    if (T > 0 && (!dlogits_shard || !chosen || !logp_theta || !lse || !logp_behav || !advantages || !loss_mask))
+        return A3PO_E_NULL;
+    if (T > 0 && o.prox_mode == A3PO_PROX_INTERP && !versions) return A3PO_E_NULL;
+    if (T > 0 && o.prox_mode == A3PO_PROX_GIVEN && !o.logp_prox_in) return A3PO_E_NULL;
+    if (!aligned(dlogits_shard, 16)) return A3PO_E_ALIGN;
+    const WsLayout lay = loss_ws_layout(T);
+    if (!workspace || workspace_bytes < lay.total) return A3PO_E_WORKSPACE;
+    if (!aligned(workspace, 256)) return A3PO_E_ALIGN;
+
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    char *ws = static_cast<char *>(workspace);
+    LossArgs a;
+    a.z = logits_shard;
+    a.dz = dlogits_shard;
+    a.dt = (int)dt;
+    a.T = T;
+    a.V = V;  // the prep kernel validates chosen ids against the full vocabulary
+    a.ld = ld;
+    a.chosen = chosen;
+    a.lb = logp_behav;
+    a.versions = versions;
+    a.current_version = current_version;
+    a.adv = advantages;
+    a.mask = loss_mask;
+    a.clip_eps = clip_eps;
+    a.denom = denom;
+    a.logp_out = nullptr;
+    a.prox_out = logp_prox_out;
+    a.loss_out = loss_out;
+    a.stats_out = stats_out;
+    a.prox_mode = o.prox_mode;
+    a.prox_in = o.logp_prox_in;
+    a.iw_out = o.iw_out;
+    a.clipped_out = o.clipped_out;
+    a.ws_header = ws;
+    a.ws_records = reinterpret_cast<TokenRecord *>(ws + lay.records);
+    a.ws_obj = reinterpret_cast<float *>(ws + lay.obj);
+    a.ws_iw = reinterpret_cast<float *>(ws + lay.iw);
+    a.ws_flags = reinterpret_cast<uint8_t *>(ws + lay.flags);
+    if (launch_loss_prep(a, s) != hipSuccess) return A3PO_E_LAUNCH;
+    LossArgs b = a;
+    b.V = Vs;  // the row kernel walks the shard's columns
+    if (launch_shard_bwd_rows(b, v0, logp_theta, lse, s) != hipSuccess) return A3PO_E_LAUNCH;
+    if (launch_loss_finish(a, s) != hipSuccess) return A3PO_E_LAUNCH;
+    return A3PO_OK;
+}
+
 }  // extern "C"

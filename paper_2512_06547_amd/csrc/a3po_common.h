@@ -103,6 +103,21 @@ __device__ __forceinline__ void store_elem(void *row, int64_t e, float v)
     else reinterpret_cast<uint16_t *>(row)[e] = (uint16_t)(pack_bf16x2(v, 0.0f) & 0xFFFFu);
 }
 
+// non-temporal 16-byte row accesses: every byte of a logit row is touched exactly once
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ uint4 stream_load(const char *p)
+{
+    const u32x4_t t = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t *>(p));
+    return make_uint4(t.x, t.y, t.z, t.w);
+}
+
+__device__ __forceinline__ void stream_store(char *p, const uint4 &v)
+{
+    const u32x4_t t = {v.x, v.y, v.z, v.w};
+    __builtin_nontemporal_store(t, reinterpret_cast<u32x4_t *>(p));
+}
+
 // ---- (max, sum) pairs of an online log-sum-exp:  sum_j exp(z_j) = s * exp(m) ----------------
 struct MaxSum {
     float m, s;
@@ -215,6 +230,50 @@ __device__ __forceinline__ void seed(MaxSumU &a) { a.m = kNegFloor; a.s = 0.0f; 
 __device__ __forceinline__ float entropy_of(const MaxSum &, float) { return 0.0f; }
 __device__ __forceinline__ float entropy_of(const MaxSumU &a, float lse) { return lse - a.u / a.s; }
 
+// block-wide all-reduce of a row accumulator through LDS, two barriers; for the multi-pass kernels.
+// `red` holds 3 * WAVES floats.
+__device__ __forceinline__ void put(float *red, int waves, int w, const MaxSum &v)
+{
+    red[w] = v.m;
+    red[waves + w] = v.s;
+}
+__device__ __forceinline__ void put(float *red, int waves, int w, const MaxSumU &v)
+{
+    red[w] = v.m;
+    red[waves + w] = v.s;
+    red[2 * waves + w] = v.u;
+}
+__device__ __forceinline__ void get(const float *red, int waves, int w, MaxSum &v)
+{
+    v.m = red[w];
+    v.s = red[waves + w];
+}
+__device__ __forceinline__ void get(const float *red, int waves, int w, MaxSumU &v)
+{
+    v.m = red[w];
+    v.s = red[waves + w];
+    v.u = red[2 * waves + w];
+}
+
+template <int WAVES, typename ACC>
+__device__ __forceinline__ ACC block_allreduce(ACC v, float *red)
+{
+    v = wave_reduce(v);
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+    __syncthreads();  // previous readers of red are done
+    if (lane == 0) put(red, WAVES, wave, v);
+    __syncthreads();
+    ACC t;
+    get(red, WAVES, 0, t);
+#pragma unroll
+    for (int w = 1; w < WAVES; ++w) {
+        ACC o;
+        get(red, WAVES, w, o);
+        t = combine(t, o);
+    }
+    return t;
+}
+
 // ---- per-token A-3PO terms (Eq. 2 - Eq. 4 of the paper) -----------------------------------
 struct TokenTerms {
     float alpha, lp, iw, r, obj, g;
@@ -266,6 +325,12 @@ enum : uint8_t { kFlagCounted = 1, kFlagClipped = 2, kFlagNegStale = 4 };
 struct alignas(16) TokenRecord {
     int32_t y, ver;
     float lb, A;
+};
+
+// Per-token outputs of a vocabulary-wide loss kernel (logp / ent only where that kernel produces them).
+struct RowOutputs {
+    float *logp, *prox, *obj, *iw, *ent;
+    uint8_t *flags;
 };
 
 // Workspace header written by the prep kernel, read by the row kernel and the finish kernel.

@@ -72,6 +72,13 @@ hipError_t launch_proximal_interp(const float *lb, const float *lt, const int32_
 hipError_t launch_grpo_advantages(const float *rewards, int64_t S, int32_t G, float eps_adv, const int32_t *seq_id,
                                   int64_t T, float *adv, hipStream_t s);
 
+hipError_t launch_shard_partials(const void *z, int dt, int64_t T, int64_t Vs, int64_t ld, const int32_t *chosen,
+                                 int64_t v0, a3po_shard_partial *out, hipStream_t s);
+hipError_t launch_shard_combine(const a3po_shard_partial *parts, int32_t P, int64_t T, const int32_t *chosen, int64_t V,
+                                float *logp, float *lse, float *ent, hipStream_t s);
+// a.V is the shard width here; a.ws_records must come from a prep launch made with the full vocabulary size
+hipError_t launch_shard_bwd_rows(const LossArgs &a, int64_t v0, const float *logp_theta, const float *lse, hipStream_t s);
+
 size_t lmhead_workspace_bytes(int64_t T);
 hipError_t launch_fused_lmhead_logprob(const void *hidden, const void *weight, int64_t T, int64_t H, int64_t V,
                                        const int32_t *chosen, float *logp, float *lse, void *workspace, hipStream_t s);

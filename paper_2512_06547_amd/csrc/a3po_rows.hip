@@ -20,51 +20,6 @@ constexpr int kRowWaves = kRowThreads / kWave;
 constexpr int kMaxVec = 20;  // 16-byte vectors per thread the fused kernel can hold
 
 // ---------------------------------------------------------------------------------------
-// block-wide all-reduce of a row accumulator through LDS, two barriers; for the multi-pass kernels.
-// `red` holds 3 * WAVES floats.
-__device__ __forceinline__ void put(float *red, int waves, int w, const MaxSum &v)
-{
-    red[w] = v.m;
-    red[waves + w] = v.s;
-}
-__device__ __forceinline__ void put(float *red, int waves, int w, const MaxSumU &v)
-{
-    red[w] = v.m;
-    red[waves + w] = v.s;
-    red[2 * waves + w] = v.u;
-}
-__device__ __forceinline__ void get(const float *red, int waves, int w, MaxSum &v)
-{
-    v.m = red[w];
-    v.s = red[waves + w];
-}
-__device__ __forceinline__ void get(const float *red, int waves, int w, MaxSumU &v)
-{
-    v.m = red[w];
-    v.s = red[waves + w];
-    v.u = red[2 * waves + w];
-}
-
-template <int WAVES, typename ACC>
-__device__ __forceinline__ ACC block_allreduce(ACC v, float *red)
-{
-    v = wave_reduce(v);
-    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
-    __syncthreads();  // previous readers of red are done
-    if (lane == 0) put(red, WAVES, wave, v);
-    __syncthreads();
-    ACC t;
-    get(red, WAVES, 0, t);
-#pragma unroll
-    for (int w = 1; w < WAVES; ++w) {
-        ACC o;
-        get(red, WAVES, w, o);
-        t = combine(t, o);
-    }
-    return t;
-}
-
-// ---------------------------------------------------------------------------------------
 // Fused forward+backward, register-resident rows.
 //
 // NSWEEP is the exact number of 1024-lane sweeps of 16-byte vectors a row needs:
@@ -77,25 +32,6 @@ __device__ __forceinline__ ACC block_allreduce(ACC v, float *red)
 // balance out by themselves.  The queue counter is zeroed by the prep kernel.
 // Loads and stores of logit rows are non-temporal: every byte is touched exactly once.
 constexpr uint32_t kSweepBytes = kRowThreads * 16;
-
-typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
-
-__device__ __forceinline__ uint4 stream_load(const char *p)
-{
-    const u32x4_t t = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t *>(p));
-    return make_uint4(t.x, t.y, t.z, t.w);
-}
-
-__device__ __forceinline__ void stream_store(char *p, const uint4 &v)
-{
-    const u32x4_t t = {v.x, v.y, v.z, v.w};
-    __builtin_nontemporal_store(t, reinterpret_cast<u32x4_t *>(p));
-}
-
-struct RowOutputs {
-    float *logp, *prox, *obj, *iw, *ent;
-    uint8_t *flags;
-};
 
 // One vector of the backward pass: f (logits) -> f (gradient entries without the chosen column's +g),
 // and for ENT the running sum of p_j z_j (elements past the row's end hold -inf: p = 0).

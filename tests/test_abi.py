@@ -91,3 +91,25 @@ def test_host_validation_rejects_bad_arguments_before_launch(lib):
     assert call(a18=ctypes.c_void_p(0x10010)) == -4
     assert call(a13=ctypes.c_void_p(0x1008)) == -4
     assert call(a1=2) == -3 and call(a4=32) == -2
+
+
+def test_ex_entry_point_validates_its_options_before_launch(lib):
+    from paper_2512_06547_amd.binding import LossOptions
+    fake = ctypes.c_void_p(0x1000)
+    base = [fake, 1, 4, 64, 64, fake, fake, fake, 3, fake, fake, 0.2, 0.0, fake, fake, None, fake, None,
+            ctypes.c_void_p(0x10000), 1 << 20, None]
+    ex = lib.a3po_loss_fwd_bwd_ex
+
+    def call(opt, versions=fake):
+        a = list(base)
+        a[7] = versions
+        return ex(*a, ctypes.byref(opt))
+
+    assert call(LossOptions(prox_mode=3)) == -7 and call(LossOptions(prox_mode=-1)) == -7
+    assert call(LossOptions(prox_mode=0, reserved=1)) == -7
+    assert call(LossOptions(prox_mode=1)) == -1                          # given-prox without the array
+    assert call(LossOptions(prox_mode=0), versions=None) == -1           # interpolation needs versions
+    te = lib.a3po_token_logprobs_entropy
+    assert te(fake, 0, 1, 8, 8, fake, fake, None, None, None, None) == -1   # entropy_out is required
+    assert te(fake, 0, 0, 8, 8, None, None, None, None, None, None) == 0
+    assert te(fake, 5, 1, 8, 8, fake, fake, None, None, fake, None) == -3
