@@ -19,10 +19,10 @@
  *    on different streams, as long as they do not share output buffers or a workspace.
  *  - Logits are row-major [T, V] with a row stride of `ld` elements (ld >= V), float32
  *    or bfloat16.  Row t pairs with chosen[t]; any next-token shift is the caller's.
- *    Base pointers of logits / dlogits must be 16-byte aligned.  Rows whose byte stride
- *    is a multiple of 16 and that fit on chip (V <= 163,840 bfloat16 / 81,920 float32)
- *    take the single-pass kernels; everything else takes a slower multi-pass kernel
- *    with identical results up to rounding order.
+ *    Base pointers of logits / dlogits must be aligned to their element size.  Rows whose base
+ *    and byte stride are multiples of 16 and that fit on chip (V <= 163,840 bfloat16 / 81,920
+ *    float32) take the single-pass kernels; everything else takes slower element-wise multi-pass
+ *    kernels with identical results up to rounding order.
  */
 #ifndef A3PO_H
 #define A3PO_H
@@ -75,7 +75,10 @@ typedef enum {
  * A zero-filled struct selects the behaviour of a3po_loss_fwd_bwd. */
 typedef struct {
     int32_t prox_mode;         /* a3po_prox_mode                                                */
-    int32_t reserved;          /* must be 0                                                     */
+    int32_t accumulate;        /* 0: loss_out / stats_out are overwritten.  1: this call's share is     */
+                               /* added to what they hold (micro-batches of one gradient update: sums   */
+                               /* add, extrema and the entropy mean merge); they must have been written */
+                               /* by an earlier call on the same stream                                 */
     const float *logp_prox_in; /* device [T]; required for A3PO_PROX_GIVEN, ignored otherwise   */
     float *entropy_out;        /* device [T], nullable: policy entropy -sum_j p_j log p_j of    */
                                /* each counted row (0 for rows that do not enter the loss),     */
@@ -85,6 +88,9 @@ typedef struct {
     uint8_t *clipped_out;      /* device [T], nullable: 1 where the clipped branch is the min   */
     void *event_before_rows;   /* hipEvent_t, nullable: recorded on `stream` immediately before */
     void *event_after_rows;    /* and after the vocabulary-wide row kernel (never waited on)    */
+    const float *denom_dev;    /* device [1], nullable: when set, replaces the `denom` argument (read   */
+                               /* on the stream, so a count produced by a3po_count_tokens needs no host */
+                               /* round trip); a value <= 0 selects this call's own token count         */
 } a3po_loss_options;
 
 enum { A3PO_WS_LOSS_FWD_BWD = 0, A3PO_WS_FUSED_LMHEAD = 1, A3PO_WS_FUSED_LMHEAD_LOSS = 2 };
@@ -180,8 +186,10 @@ int a3po_loss_fwd_bwd(const void *logits, a3po_dtype dt, int64_t T, int64_t V, i
  *  - per-token importance weights and clip decisions, for histograms beyond the extrema and the
  *    count in a3po_stats;
  *  - two events around the row kernel, so a caller can time that kernel without a profiler.
- * Returns A3PO_E_VALUE for an unknown prox_mode or a non-zero reserved field, A3PO_E_NULL when
- * A3PO_PROX_GIVEN comes without logp_prox_in.
+ *  - mini-batch support: a denominator read from device memory and accumulation of loss and
+ *    statistics over the micro-batches of one gradient update (see a3po_plan_microbatches).
+ * Returns A3PO_E_VALUE for an unknown prox_mode or an accumulate flag other than 0 / 1, A3PO_E_NULL
+ * when A3PO_PROX_GIVEN comes without logp_prox_in.
  */
 int a3po_loss_fwd_bwd_ex(const void *logits, a3po_dtype dt, int64_t T, int64_t V, int64_t ld,
                          const int32_t *chosen, const float *logp_behav,
@@ -192,6 +200,42 @@ int a3po_loss_fwd_bwd_ex(const void *logits, a3po_dtype dt, int64_t T, int64_t V
                          float *loss_out, a3po_stats *stats_out,
                          void *workspace, size_t workspace_bytes, void *stream,
                          const a3po_loss_options *opt);
+
+/* ---- mini-batches (Section 4.1: a training step makes 4 gradient updates, one per mini-batch, and a
+ * forward/backward pass holds at most 10,240 tokens) -------------------------------------------------
+ *
+ * Layout: sequences are packed back to back without padding, so row t of the logits is token t of the
+ * packed stream and sequence s owns rows [offset_s, offset_s + seq_len[s]).  A mini-batch is a
+ * contiguous run of sequences and one gradient update; it is cut into micro-batches, contiguous runs
+ * of whole sequences whose token total stays within the budget.  Each micro-batch is one call of
+ * a3po_loss_fwd_bwd_ex on its row range with the mini-batch's token count as denominator
+ * (a3po_count_tokens -> a3po_loss_options.denom_dev) and accumulate = 1 after the first, so that loss,
+ * statistics and gradients add up to exactly those of the mini-batch evaluated in one piece.
+ */
+
+/*
+ * Plans the split.  HOST pointers.  seq_len [S] (>= 0).  Mini-batch k (0 <= k < n_minibatches) holds
+ * sequences [k*S/n, (k+1)*S/n) (integer division; empty when S < n).  Inside a mini-batch, sequences are
+ * taken in order and a new micro-batch starts whenever the next sequence would push the token total
+ * over max_tokens; a sequence longer than max_tokens gets a micro-batch of its own.  Empty sequences
+ * ride along with their neighbours.
+ * Outputs: micro_first_seq [capacity + 1]: micro-batch i holds sequences micro_first_seq[i] ..
+ * micro_first_seq[i+1]-1; micro_minibatch [capacity]: the mini-batch it belongs to; *n_micro_out: how
+ * many micro-batches there are.  capacity >= S + n_minibatches always suffices.
+ * Returns A3PO_E_SIZE for S < 0, n_minibatches <= 0, max_tokens <= 0, a negative length or a capacity
+ * that is too small (nothing useful is written then).
+ */
+int a3po_plan_microbatches(const int64_t *seq_len, int64_t S, int32_t n_minibatches, int64_t max_tokens,
+                           int64_t *micro_first_seq, int32_t *micro_minibatch, int64_t capacity,
+                           int64_t *n_micro_out);
+
+/*
+ * Number of tokens that enter the loss (mask != 0 and 0 <= chosen < V) among T tokens, written as a
+ * float to denom_out [1] (device; the denominator of a mini-batch) and, if count_out is not NULL, as
+ * an integer to count_out [1] (device).  Exact up to 2^24 tokens as a float.
+ */
+int a3po_count_tokens(const int32_t *chosen, const uint8_t *loss_mask, int64_t T, int64_t V,
+                      float *denom_out, int64_t *count_out, void *stream);
 
 /* ---- vocabulary-sharded variant (a tensor-parallel LM head: each shard holds a column slice) ------
  *
@@ -212,7 +256,7 @@ typedef struct {
     float sum_exp_z;     /* sum_j exp(z[t, j] - max) * z[t, j]   (for the entropy)            */
 } a3po_shard_partial;
 
-/* partial_out [T].  logits_shard: dtype dt, [T, Vs], stride ld >= Vs, 16-byte aligned base; v0 >= 0 is
+/* partial_out [T].  logits_shard: dtype dt, [T, Vs], stride ld >= Vs (16-byte aligned base and stride for the vector path); v0 >= 0 is
  * the global id of the shard's first column.  Reads T * Vs elements once. */
 int a3po_shard_partials(const void *logits_shard, a3po_dtype dt, int64_t T, int64_t Vs, int64_t ld,
                         const int32_t *chosen, int64_t v0, a3po_shard_partial *partial_out, void *stream);

@@ -271,3 +271,29 @@ def lmhead_backward(dz, h, W, want_dh=True, want_dw=True):
     _load().a3po_oracle_lmhead_backward(dz.ctypes.data, h.ctypes.data, W.ctypes.data, T, H, V,
                                         dh.ctypes.data if want_dh else None, dW.ctypes.data if want_dw else None)
     return dh, dW
+
+
+def plan_microbatches(seq_len, n_minibatches, max_tokens):
+    """Reference plan of the mini-batch / micro-batch split (Section 4.1: 4 gradient updates per step,
+    at most 10,240 tokens per pass), in plain Python.
+
+    Mini-batch k holds sequences [k*S//n, (k+1)*S//n).  Inside a mini-batch sequences are taken in
+    order; a non-empty sequence that would push the open micro-batch past ``max_tokens`` closes it and
+    opens the next one (so a sequence longer than the budget sits alone).  Returns
+    (micro_first_seq, micro_minibatch) as lists: micro-batch i = sequences
+    micro_first_seq[i] .. micro_first_seq[i+1]-1.
+    """
+    S = len(seq_len)
+    first, owner = [], []
+    for k in range(n_minibatches):
+        lo, hi = k * S // n_minibatches, (k + 1) * S // n_minibatches
+        tokens = None                      # None: no micro-batch open in this mini-batch yet
+        for s in range(lo, hi):
+            n = int(seq_len[s])
+            if tokens is None or (tokens > 0 and n > 0 and tokens + n > max_tokens):
+                first.append(s)
+                owner.append(k)
+                tokens = 0
+            tokens += n
+    first.append(S)
+    return first, owner

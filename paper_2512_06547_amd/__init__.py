@@ -10,6 +10,8 @@ from .binding import (  # noqa: F401
     A3PO_PROX_GIVEN,
     A3PO_PROX_INTERP,
     A3poError,
+    count_tokens,
+    plan_microbatches,
     fused_lmhead_logprob,
     fused_lmhead_loss_fwd_bwd,
     STATS_DTYPE,

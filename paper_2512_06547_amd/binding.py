@@ -31,9 +31,10 @@ _P, _I64, _I32, _F32, _SZ = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, cty
 
 class LossOptions(ctypes.Structure):
     """a3po_loss_options (include/a3po.h)."""
-    _fields_ = [("prox_mode", ctypes.c_int32), ("reserved", ctypes.c_int32), ("logp_prox_in", ctypes.c_void_p),
+    _fields_ = [("prox_mode", ctypes.c_int32), ("accumulate", ctypes.c_int32), ("logp_prox_in", ctypes.c_void_p),
                 ("entropy_out", ctypes.c_void_p), ("iw_out", ctypes.c_void_p), ("clipped_out", ctypes.c_void_p),
-                ("event_before_rows", ctypes.c_void_p), ("event_after_rows", ctypes.c_void_p)]
+                ("event_before_rows", ctypes.c_void_p), ("event_after_rows", ctypes.c_void_p),
+                ("denom_dev", ctypes.c_void_p)]
 
 
 _SIGNATURES = {
@@ -49,6 +50,8 @@ _SIGNATURES = {
                                          _P, _P, _P, _P, _P, _P, _SZ, _P]),
     "a3po_loss_fwd_bwd_ex": (ctypes.c_int, [_P, ctypes.c_int, _I64, _I64, _I64, _P, _P, _P, _I32, _P, _P, _F32,
                                             _F32, _P, _P, _P, _P, _P, _P, _SZ, _P, ctypes.POINTER(LossOptions)]),
+    "a3po_count_tokens": (ctypes.c_int, [_P, _P, _I64, _I64, _P, _P, _P]),
+    "a3po_plan_microbatches": (ctypes.c_int, [_P, _I64, _I32, _I64, _P, _P, _I64, _P]),
     "a3po_shard_partials": (ctypes.c_int, [_P, ctypes.c_int, _I64, _I64, _I64, _P, _I64, _P, _P]),
     "a3po_shard_combine": (ctypes.c_int, [_P, _I32, _I64, _P, _I64, _P, _P, _P, _P]),
     "a3po_shard_loss_bwd": (ctypes.c_int, [_P, ctypes.c_int, _I64, _I64, _I64, _I64, _I64, _P, _P, _P, _P, _P, _I32,
@@ -181,10 +184,11 @@ def grpo_advantages(rewards, G: int, seq_id, eps_adv: float = 1e-6, out=None):
 def loss_fwd_bwd(logits, chosen, logp_behav, versions, current_version: int, advantages, loss_mask,
                  clip_eps: float, denom: float = 0.0, V=None, dlogits=None, workspace=None, out=None,
                  events=None, prox_mode: int = A3PO_PROX_INTERP, logp_prox_in=None, want_entropy=False,
-                 want_iw=False, want_clipped=False):
+                 want_iw=False, want_clipped=False, denom_dev=None, accumulate=False):
     """a3po_loss_fwd_bwd, or a3po_loss_fwd_bwd_ex when any extra is asked for: ``events=(start, stop)`` raw
     hipEvent_t handles, ``prox_mode`` / ``logp_prox_in`` (the given-proximal and coupled variants; ``versions``
-    may then be None), ``want_entropy`` / ``want_iw`` / ``want_clipped`` per-token outputs.
+    may then be None), ``want_entropy`` / ``want_iw`` / ``want_clipped`` per-token outputs, ``denom_dev`` (a
+    1-element float32 device tensor that replaces ``denom``) and ``accumulate`` (add to the loss / stats in ``out``).
 
     dlogits: None -> a new tensor like logits; or a tensor with the same dtype and strides (may be
     ``logits`` itself for the in-place form).  ``out`` may carry preallocated output tensors from an earlier
@@ -223,12 +227,13 @@ def loss_fwd_bwd(logits, chosen, logp_behav, versions, current_version: int, adv
             _ptr(advantages), _ptr(loss_mask), float(clip_eps), float(denom), _ptr(dlogits), _ptr(logp), _ptr(prox),
             _ptr(loss), _ptr(stats), _ptr(workspace), workspace.numel(), _stream()]
     extras = (events is not None or prox_mode != A3PO_PROX_INTERP or logp_prox_in is not None or want_entropy
-              or want_iw or want_clipped)
+              or want_iw or want_clipped or denom_dev is not None or accumulate)
     if not extras:
         _check(lib().a3po_loss_fwd_bwd(*args), "a3po_loss_fwd_bwd")
     else:
         ev = events if events is not None else (None, None)
-        opt = LossOptions(int(prox_mode), 0, _ptr(logp_prox_in), _ptr(ent), _ptr(iw), _ptr(clipped), ev[0], ev[1])
+        opt = LossOptions(int(prox_mode), int(bool(accumulate)), _ptr(logp_prox_in), _ptr(ent), _ptr(iw),
+                          _ptr(clipped), ev[0], ev[1], _ptr(denom_dev))
         _check(lib().a3po_loss_fwd_bwd_ex(*args, ctypes.byref(opt)), "a3po_loss_fwd_bwd_ex")
     res = dict(dlogits=dlogits, logp=logp, logp_prox=prox, loss=loss, stats=stats, workspace=workspace)
     if want_entropy:
@@ -238,6 +243,32 @@ def loss_fwd_bwd(logits, chosen, logp_behav, versions, current_version: int, adv
     if want_clipped:
         res["clipped"] = clipped
     return res
+
+
+def count_tokens(chosen, loss_mask, V: int, want_count=False):
+    """a3po_count_tokens -> denom (1-element f32 device tensor) [, count (1-element i64 device tensor)]."""
+    torch = _torch()
+    T = chosen.numel()
+    _vec(chosen, torch.int32, T, "chosen")
+    _vec(loss_mask, torch.uint8, T, "loss_mask")
+    denom = torch.empty(1, dtype=torch.float32, device=chosen.device)
+    cnt = torch.empty(1, dtype=torch.int64, device=chosen.device) if want_count else None
+    _check(lib().a3po_count_tokens(_ptr(chosen), _ptr(loss_mask), T, int(V), _ptr(denom), _ptr(cnt), _stream()),
+           "a3po_count_tokens")
+    return (denom, cnt) if want_count else denom
+
+
+def plan_microbatches(seq_len, n_minibatches: int, max_tokens: int, capacity=None):
+    """a3po_plan_microbatches on a host int64 array -> (micro_first_seq[n+1], micro_minibatch[n]) NumPy arrays."""
+    seq_len = np.ascontiguousarray(np.asarray(seq_len, dtype=np.int64))
+    S = seq_len.shape[0]
+    cap = S + int(max(n_minibatches, 0)) if capacity is None else int(capacity)
+    first = np.zeros(max(cap, 0) + 1, dtype=np.int64)
+    mb = np.zeros(max(cap, 1), dtype=np.int32)
+    n = ctypes.c_int64(0)
+    _check(lib().a3po_plan_microbatches(seq_len.ctypes.data, S, int(n_minibatches), int(max_tokens), first.ctypes.data,
+                                        mb.ctypes.data, cap, ctypes.addressof(n)), "a3po_plan_microbatches")
+    return first[:n.value + 1].copy(), mb[:n.value].copy()
 
 
 def shard_partials(logits_shard, chosen, v0: int, Vs=None, out=None):
@@ -291,7 +322,7 @@ def shard_loss_bwd(logits_shard, v0: int, V: int, chosen, logp_theta, lse, logp_
     stats = torch.empty(STATS_DTYPE.itemsize, dtype=torch.uint8, device=dev)
     iw = torch.empty(T, dtype=torch.float32, device=dev) if want_iw else None
     clipped = torch.empty(T, dtype=torch.uint8, device=dev) if want_clipped else None
-    opt = LossOptions(int(prox_mode), 0, _ptr(logp_prox_in), None, _ptr(iw), _ptr(clipped), None, None)
+    opt = LossOptions(int(prox_mode), 0, _ptr(logp_prox_in), None, _ptr(iw), _ptr(clipped), None, None, None)
     _check(lib().a3po_shard_loss_bwd(_ptr(logits_shard), dt, T, Vs, ld, int(v0), int(V), _ptr(chosen),
                                      _ptr(logp_theta), _ptr(lse), _ptr(logp_behav), _ptr(versions),
                                      int(current_version), _ptr(advantages), _ptr(loss_mask), float(clip_eps),

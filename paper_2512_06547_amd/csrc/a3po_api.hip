@@ -19,7 +19,7 @@ int check_logits(const void *logits, int dt, int64_t T, int64_t V, int64_t ld)
     if (dt != A3PO_F32 && dt != A3PO_BF16) return A3PO_E_DTYPE;
     if (T < 0 || V <= 0 || ld < V || V > (int64_t)0x7FFFFFFF) return A3PO_E_SIZE;
     if (T > 0 && !logits) return A3PO_E_NULL;
-    if (!aligned(logits, 16)) return A3PO_E_ALIGN;
+    if (!aligned(logits, dt == A3PO_F32 ? 4 : 2)) return A3PO_E_ALIGN;  // element alignment; 16 bytes selects the fast kernels
     return A3PO_OK;
 }
 
@@ -124,12 +124,13 @@ int a3po_loss_fwd_bwd_ex(const void *logits, a3po_dtype dt, int64_t T, int64_t V
     const a3po_loss_options &o = opt ? *opt : none;
     if (int rc = check_logits(logits, (int)dt, T, V, ld)) return rc;
     if (!(clip_eps >= 0.0f && clip_eps < 1.0f) || std::isnan(denom)) return A3PO_E_VALUE;
-    if (o.prox_mode < A3PO_PROX_INTERP || o.prox_mode > A3PO_PROX_BEHAV || o.reserved != 0) return A3PO_E_VALUE;
+    if (o.prox_mode < A3PO_PROX_INTERP || o.prox_mode > A3PO_PROX_BEHAV || (o.accumulate != 0 && o.accumulate != 1))
+        return A3PO_E_VALUE;
     if (!loss_out) return A3PO_E_NULL;
     if (T > 0 && (!dlogits || !chosen || !logp_behav || !advantages || !loss_mask || !logp_out)) return A3PO_E_NULL;
     if (T > 0 && o.prox_mode == A3PO_PROX_INTERP && !versions) return A3PO_E_NULL;
     if (T > 0 && o.prox_mode == A3PO_PROX_GIVEN && !o.logp_prox_in) return A3PO_E_NULL;
-    if (!aligned(dlogits, 16)) return A3PO_E_ALIGN;
+    if (!aligned(dlogits, dt == A3PO_F32 ? 4 : 2)) return A3PO_E_ALIGN;
     const WsLayout lay = loss_ws_layout(T);
     if (!workspace || workspace_bytes < lay.total) return A3PO_E_WORKSPACE;
     if (!aligned(workspace, 256)) return A3PO_E_ALIGN;
@@ -160,6 +161,8 @@ int a3po_loss_fwd_bwd_ex(const void *logits, a3po_dtype dt, int64_t T, int64_t V
     a.ent_out = o.entropy_out;
     a.iw_out = o.iw_out;
     a.clipped_out = o.clipped_out;
+    a.denom_dev = o.denom_dev;
+    a.accumulate = o.accumulate;
     a.ws_header = ws;
     a.ws_records = reinterpret_cast<TokenRecord *>(ws + lay.records);
     a.ws_obj = reinterpret_cast<float *>(ws + lay.obj);
@@ -185,6 +188,52 @@ int a3po_loss_fwd_bwd(const void *logits, a3po_dtype dt, int64_t T, int64_t V, i
     return a3po_loss_fwd_bwd_ex(logits, dt, T, V, ld, chosen, logp_behav, versions, current_version, advantages,
                                 loss_mask, clip_eps, denom, dlogits, logp_out, logp_prox_out, loss_out, stats_out,
                                 workspace, workspace_bytes, stream, nullptr);
+}
+
+int a3po_count_tokens(const int32_t *chosen, const uint8_t *loss_mask, int64_t T, int64_t V, float *denom_out,
+                      int64_t *count_out, void *stream)
+{
+    if (T < 0 || V <= 0) return A3PO_E_SIZE;
+    if (!denom_out || (T > 0 && (!chosen || !loss_mask))) return A3PO_E_NULL;
+    const hipError_t e =
+        launch_count_tokens(chosen, loss_mask, T, V, denom_out, count_out, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? A3PO_OK : A3PO_E_LAUNCH;
+}
+
+int a3po_plan_microbatches(const int64_t *seq_len, int64_t S, int32_t n_minibatches, int64_t max_tokens,
+                           int64_t *micro_first_seq, int32_t *micro_minibatch, int64_t capacity, int64_t *n_micro_out)
+{
+    if (S < 0 || n_minibatches <= 0 || max_tokens <= 0 || capacity < 0) return A3PO_E_SIZE;
+    if (!micro_first_seq || !micro_minibatch || !n_micro_out || (S > 0 && !seq_len)) return A3PO_E_NULL;
+    for (int64_t s = 0; s < S; ++s)
+        if (seq_len[s] < 0) return A3PO_E_SIZE;
+    // first pass counts, second pass writes: nothing is written unless everything fits
+    for (int pass = 0; pass < 2; ++pass) {
+        int64_t n = 0;
+        for (int32_t k = 0; k < n_minibatches; ++k) {
+            const int64_t lo = (int64_t)k * S / n_minibatches, hi = (int64_t)(k + 1) * S / n_minibatches;
+            int64_t tokens = 0;
+            bool open = false;
+            for (int64_t s = lo; s < hi; ++s) {
+                if (!open || (tokens > 0 && seq_len[s] > 0 && tokens + seq_len[s] > max_tokens)) {
+                    if (pass == 1) {
+                        micro_first_seq[n] = s;
+                        micro_minibatch[n] = k;
+                    }
+                    ++n;
+                    tokens = 0;
+                    open = true;
+                }
+                tokens += seq_len[s];
+            }
+        }
+        if (pass == 0 && n > capacity) return A3PO_E_SIZE;
+        if (pass == 1) {
+            micro_first_seq[n] = S;
+            *n_micro_out = n;
+        }
+    }
+    return A3PO_OK;
 }
 
 int a3po_shard_partials(const void *logits_shard, a3po_dtype dt, int64_t T, int64_t Vs, int64_t ld,
@@ -224,13 +273,14 @@ int a3po_shard_loss_bwd(const void *logits_shard, a3po_dtype dt, int64_t T, int6
     if (int rc = check_logits(logits_shard, (int)dt, T, Vs, ld)) return rc;
     if (v0 < 0 || V <= 0 || v0 + Vs > V || V > (int64_t)0x7FFFFFFF) return A3PO_E_SIZE;
     if (!(clip_eps >= 0.0f && clip_eps < 1.0f) || std::isnan(denom)) return A3PO_E_VALUE;
-    if (o.prox_mode < A3PO_PROX_INTERP || o.prox_mode > A3PO_PROX_BEHAV || o.reserved != 0) return A3PO_E_VALUE;
+    if (o.prox_mode < A3PO_PROX_INTERP || o.prox_mode > A3PO_PROX_BEHAV || (o.accumulate != 0 && o.accumulate != 1))
+        return A3PO_E_VALUE;
     if (!loss_out) return A3PO_E_NULL;
     if (T > 0 && (!dlogits_shard || !chosen || !logp_theta || !lse || !logp_behav || !advantages || !loss_mask))
         return A3PO_E_NULL;
     if (T > 0 && o.prox_mode == A3PO_PROX_INTERP && !versions) return A3PO_E_NULL;
     if (T > 0 && o.prox_mode == A3PO_PROX_GIVEN && !o.logp_prox_in) return A3PO_E_NULL;
-    if (!aligned(dlogits_shard, 16)) return A3PO_E_ALIGN;
+    if (!aligned(dlogits_shard, dt == A3PO_F32 ? 4 : 2)) return A3PO_E_ALIGN;
     const WsLayout lay = loss_ws_layout(T);
     if (!workspace || workspace_bytes < lay.total) return A3PO_E_WORKSPACE;
     if (!aligned(workspace, 256)) return A3PO_E_ALIGN;
@@ -260,6 +310,8 @@ int a3po_shard_loss_bwd(const void *logits_shard, a3po_dtype dt, int64_t T, int6
     a.prox_in = o.logp_prox_in;
     a.iw_out = o.iw_out;
     a.clipped_out = o.clipped_out;
+    a.denom_dev = o.denom_dev;
+    a.accumulate = o.accumulate;
     a.ws_header = ws;
     a.ws_records = reinterpret_cast<TokenRecord *>(ws + lay.records);
     a.ws_obj = reinterpret_cast<float *>(ws + lay.obj);

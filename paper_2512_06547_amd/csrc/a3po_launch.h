@@ -32,6 +32,8 @@ struct LossArgs {
     float *ent_out = nullptr;        // [T] policy entropy, nullable
     float *iw_out = nullptr;         // [T] importance weights, nullable
     uint8_t *clipped_out = nullptr;  // [T] clip decisions, nullable
+    const float *denom_dev = nullptr;  // device [1], overrides denom when set
+    int accumulate = 0;              // add to loss_out / stats_out instead of overwriting
     // workspace carve-up
     void *ws_header;
     TokenRecord *ws_records;  // [T], written by the prep kernel
@@ -63,6 +65,8 @@ bool rows_fit_on_chip(int dt, int64_t V, int64_t ld, const void *z, const void *
 hipError_t launch_loss_prep(const LossArgs &a, hipStream_t s);
 hipError_t launch_loss_rows(const LossArgs &a, hipStream_t s);
 hipError_t launch_loss_finish(const LossArgs &a, hipStream_t s);
+hipError_t launch_count_tokens(const int32_t *chosen, const uint8_t *mask, int64_t T, int64_t V, float *denom_out,
+                               int64_t *count_out, hipStream_t s);
 hipError_t launch_reset_row_queue(void *ws_header, hipStream_t s);  // before re-running the row kernel on one header
 
 hipError_t launch_token_logprobs(const void *z, int dt, int64_t T, int64_t V, int64_t ld, const int32_t *chosen,

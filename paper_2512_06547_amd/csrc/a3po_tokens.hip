@@ -14,9 +14,10 @@ constexpr int kTokWaves = kTokThreads / kWave;
 __global__ __launch_bounds__(kTokThreads) void loss_prep_kernel(const int32_t *chosen, const uint8_t *mask,
                                                                 const float *lb, const int32_t *versions,
                                                                 const float *adv, const float *prox_in, int64_t T,
-                                                                int64_t V, float denom, WsHeader *hdr,
-                                                                TokenRecord *records)
+                                                                int64_t V, float denom, const float *denom_dev,
+                                                                WsHeader *hdr, TokenRecord *records)
 {
+    if (denom_dev) denom = *denom_dev;
     __shared__ long long s_cnt[kTokWaves], s_bad[kTokWaves];
     long long cnt = 0, bad = 0;
     for (int64_t t = threadIdx.x; t < T; t += kTokThreads) {
@@ -66,7 +67,7 @@ __global__ __launch_bounds__(kTokThreads) void loss_prep_kernel(const int32_t *c
 __global__ __launch_bounds__(kTokThreads) void loss_finish_kernel(const float *obj, const float *iw, const uint8_t *flags,
                                                                   const float *ent, int64_t T, const WsHeader *hdr,
                                                                   float *loss_out, a3po_stats *stats, float *iw_out,
-                                                                  uint8_t *clipped_out)
+                                                                  uint8_t *clipped_out, int accumulate)
 {
     __shared__ double s_sum[kTokWaves], s_ent[kTokWaves];
     __shared__ long long s_clip[kTokWaves], s_neg[kTokWaves];
@@ -119,17 +120,55 @@ __global__ __launch_bounds__(kTokThreads) void loss_finish_kernel(const float *o
             mn = fminf(mn, s_min[w]);
             mx = fmaxf(mx, s_max[w]);
         }
-        *loss_out = (float)(-(S * (double)hdr->inv_n));
+        const float share = (float)(-(S * (double)hdr->inv_n));
+        *loss_out = accumulate ? *loss_out + share : share;
         if (stats) {
-            stats->n_tokens = hdr->n_counted;
-            stats->n_clipped = c;
-            stats->n_bad_index = hdr->n_bad;
-            stats->n_negative_staleness = n;
-            stats->iw_min = mn;
-            stats->iw_max = mx;
-            stats->entropy_mean = (ent && hdr->n_counted > 0) ? (float)(E / (double)hdr->n_counted) : 0.0f;
-            stats->reserved = 0.0f;
+            a3po_stats o;
+            o.n_tokens = hdr->n_counted;
+            o.n_clipped = c;
+            o.n_bad_index = hdr->n_bad;
+            o.n_negative_staleness = n;
+            o.iw_min = mn;
+            o.iw_max = mx;
+            o.entropy_mean = (ent && hdr->n_counted > 0) ? (float)(E / (double)hdr->n_counted) : 0.0f;
+            o.reserved = 0.0f;
+            if (accumulate) {  // merge with what earlier micro-batches of the same update left
+                const a3po_stats p = *stats;
+                const long long tot = p.n_tokens + o.n_tokens;
+                o.entropy_mean = (ent && tot > 0)
+                                     ? (float)(((double)p.entropy_mean * (double)p.n_tokens + E) / (double)tot)
+                                     : 0.0f;
+                o.n_tokens = tot;
+                o.n_clipped += p.n_clipped;
+                o.n_bad_index += p.n_bad_index;
+                o.n_negative_staleness += p.n_negative_staleness;
+                o.iw_min = fminf(o.iw_min, p.iw_min);
+                o.iw_max = fmaxf(o.iw_max, p.iw_max);
+            }
+            *stats = o;
         }
+    }
+}
+
+// Counted tokens (mask != 0 and a valid chosen id) of a mini-batch, as the denominator of its micro-batches.
+__global__ __launch_bounds__(kTokThreads) void count_tokens_kernel(const int32_t *chosen, const uint8_t *mask, int64_t T,
+                                                                   int64_t V, float *denom_out, int64_t *count_out)
+{
+    __shared__ long long s_cnt[kTokWaves];
+    long long cnt = 0;
+    for (int64_t t = threadIdx.x; t < T; t += kTokThreads) {
+        const int32_t y = chosen[t];
+        cnt += (mask[t] != 0 && y >= 0 && (int64_t)y < V) ? 1 : 0;
+    }
+#pragma unroll
+    for (int off = kWave / 2; off > 0; off >>= 1) cnt += __shfl_xor(cnt, off, kWave);
+    if ((threadIdx.x & (kWave - 1)) == 0) s_cnt[threadIdx.x / kWave] = cnt;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        long long c = 0;
+        for (int w = 0; w < kTokWaves; ++w) c += s_cnt[w];
+        *denom_out = (float)c;
+        if (count_out) *count_out = c;
     }
 }
 
@@ -173,8 +212,15 @@ hipError_t launch_loss_prep(const LossArgs &a, hipStream_t s)
 {
     hipLaunchKernelGGL(loss_prep_kernel, dim3(1), dim3(kTokThreads), 0, s, a.chosen, a.mask, a.lb,
                        a.prox_mode == A3PO_PROX_INTERP ? a.versions : nullptr, a.adv,
-                       a.prox_mode == A3PO_PROX_GIVEN ? a.prox_in : nullptr, a.T, a.V, a.denom,
+                       a.prox_mode == A3PO_PROX_GIVEN ? a.prox_in : nullptr, a.T, a.V, a.denom, a.denom_dev,
                        reinterpret_cast<WsHeader *>(a.ws_header), a.ws_records);
+    return hipGetLastError();
+}
+
+hipError_t launch_count_tokens(const int32_t *chosen, const uint8_t *mask, int64_t T, int64_t V, float *denom_out,
+                               int64_t *count_out, hipStream_t s)
+{
+    hipLaunchKernelGGL(count_tokens_kernel, dim3(1), dim3(kTokThreads), 0, s, chosen, mask, T, V, denom_out, count_out);
     return hipGetLastError();
 }
 
@@ -190,7 +236,7 @@ hipError_t launch_loss_finish(const LossArgs &a, hipStream_t s)
 {
     hipLaunchKernelGGL(loss_finish_kernel, dim3(1), dim3(kTokThreads), 0, s, a.ws_obj, a.ws_iw, a.ws_flags, a.ent_out,
                        a.T, reinterpret_cast<const WsHeader *>(a.ws_header), a.loss_out, a.stats_out, a.iw_out,
-                       a.clipped_out);
+                       a.clipped_out, a.accumulate);
     return hipGetLastError();
 }
 

@@ -63,7 +63,7 @@ def test_host_validation_rejects_bad_arguments_before_launch(lib):
     assert tl(fake, 0, 1, 0, 8, fake, fake, None, None, None) == -2          # V <= 0
     assert tl(fake, 0, 1, 9, 8, fake, fake, None, None, None) == -2          # ld < V
     assert tl(None, 0, 1, 8, 8, fake, fake, None, None, None) == -1          # null logits
-    assert tl(ctypes.c_void_p(0x1004), 0, 1, 8, 8, fake, fake, None, None, None) == -4   # alignment
+    assert tl(ctypes.c_void_p(0x1002), 0, 1, 8, 8, fake, fake, None, None, None) == -4   # not element aligned
     assert tl(fake, 0, 1, 8, 8, None, fake, None, None, None) == -1          # null chosen
     assert tl(fake, 0, 0, 8, 8, None, None, None, None, None) == 0           # T == 0 is success
     pi = lib.a3po_proximal_interp
@@ -89,7 +89,7 @@ def test_host_validation_rejects_bad_arguments_before_launch(lib):
     assert call(a16=None) == -1 and call(a13=None) == -1 and call(a9=None) == -1
     assert call(a19=16) == -5 and call(a18=None) == -5
     assert call(a18=ctypes.c_void_p(0x10010)) == -4
-    assert call(a13=ctypes.c_void_p(0x1008)) == -4
+    assert call(a13=ctypes.c_void_p(0x1001)) == -4 and call(a0=ctypes.c_void_p(0x1001)) == -4
     assert call(a1=2) == -3 and call(a4=32) == -2
 
 
@@ -106,10 +106,63 @@ def test_ex_entry_point_validates_its_options_before_launch(lib):
         return ex(*a, ctypes.byref(opt))
 
     assert call(LossOptions(prox_mode=3)) == -7 and call(LossOptions(prox_mode=-1)) == -7
-    assert call(LossOptions(prox_mode=0, reserved=1)) == -7
+    assert call(LossOptions(prox_mode=0, accumulate=2)) == -7
     assert call(LossOptions(prox_mode=1)) == -1                          # given-prox without the array
     assert call(LossOptions(prox_mode=0), versions=None) == -1           # interpolation needs versions
     te = lib.a3po_token_logprobs_entropy
     assert te(fake, 0, 1, 8, 8, fake, fake, None, None, None, None) == -1   # entropy_out is required
     assert te(fake, 0, 0, 8, 8, None, None, None, None, None, None) == 0
     assert te(fake, 5, 1, 8, 8, fake, fake, None, None, fake, None) == -3
+
+
+def _check_plan_invariants(seq_len, n_mb, budget, first, owner):
+    """What any correct plan must satisfy, checked by brute force (independent of how it was produced)."""
+    S = len(seq_len)
+    assert first[0] == (0 if len(owner) else S) and first[-1] == S and len(first) == len(owner) + 1
+    assert all(a <= b for a, b in zip(first, first[1:])) and all(a <= b for a, b in zip(owner, owner[1:]))
+    for i, k in enumerate(owner):
+        lo, hi = k * S // n_mb, (k + 1) * S // n_mb
+        a, b = first[i], first[i + 1]
+        assert lo <= a < b <= hi, "a micro-batch holds at least one sequence and stays inside its mini-batch"
+        tok = sum(seq_len[a:b])
+        nonempty = [s for s in range(a, b) if seq_len[s] > 0]
+        assert tok <= budget or len(nonempty) == 1, "budget respected unless a single sequence exceeds it"
+        if i + 1 < len(owner) and owner[i + 1] == k:   # greedy: the sequence that opened the next one did not fit
+            nxt = first[i + 1]
+            assert seq_len[nxt] > 0 and tok + seq_len[nxt] > budget
+    covered = sorted(s for i in range(len(owner)) for s in range(first[i], first[i + 1]))
+    assert covered == [s for k in range(n_mb) for s in range(k * S // n_mb, (k + 1) * S // n_mb)] == list(range(S))
+
+
+def test_microbatch_planner_against_reference_and_invariants(lib):
+    import numpy as np
+    import oracle
+    import paper_2512_06547_amd as a3po
+    # hand-worked: budget 10, two mini-batches of three sequences each
+    first, owner = a3po.plan_microbatches([4, 5, 3, 12, 0, 2], 2, 10)
+    assert first.tolist() == [0, 2, 3, 5, 6] and owner.tolist() == [0, 0, 1, 1]   # the empty sequence rides with the oversize one
+    rng = np.random.default_rng(3)
+    for trial in range(300):
+        S = int(rng.integers(0, 40))
+        n_mb = int(rng.integers(1, 7))
+        budget = int(rng.integers(1, 60))
+        lens = rng.integers(0, 40, size=S)
+        lens[rng.random(S) < 0.15] = 0
+        first, owner = a3po.plan_microbatches(lens, n_mb, budget)
+        rf, ro = oracle.plan_microbatches(lens, n_mb, budget)
+        assert first.tolist() == rf and owner.tolist() == ro, (lens, n_mb, budget)
+        _check_plan_invariants(lens.tolist(), n_mb, budget, rf, ro)
+    # the paper's first setup: 1,024 sequences of at most 1,024 tokens, 4 updates, 10,240 tokens per pass
+    lens = rng.integers(64, 1025, size=1024)
+    first, owner = a3po.plan_microbatches(lens, 4, 10240)
+    _check_plan_invariants(lens.tolist(), 4, 10240, first.tolist(), owner.tolist())
+    assert np.bincount(owner, minlength=4).min() > 0
+    # errors: nothing fits in a capacity that is too small, bad sizes
+    with pytest.raises(a3po.A3poError) as e:
+        a3po.plan_microbatches([5, 5, 5, 5], 1, 5, capacity=3)
+    assert e.value.code == -2
+    for bad in (dict(n_minibatches=0, max_tokens=5), dict(n_minibatches=2, max_tokens=0)):
+        with pytest.raises(a3po.A3poError):
+            a3po.plan_microbatches([1, 2], **bad)
+    with pytest.raises(a3po.A3poError):
+        a3po.plan_microbatches([1, -2], 1, 5)
