@@ -156,6 +156,64 @@ def cpu_baseline(w, synth, oracle, rows, block=2048):
     return rows / total, total
 
 
+def secondary_kernels(a3po, torch, w, b, adv, dz, ws, log, reps=10, shards=8):
+    """Context for the other vocabulary-wide kernels on the same batch (torch events on the current stream, which
+    is the stream the binding launches on): forward-only log-probs with and without entropy (read-once:
+    V * b bytes per row), and the vocabulary-sharded path on `shards` column views (forward partials: V * b per
+    row; backward: V * b read + V * b written per live row, V * b written per dead row)."""
+    T, V = w.T, w.V
+    row = V * w.elem_bytes
+
+    def timed(f):
+        for _ in range(2):
+            f()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            f()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+    res = {}
+    ms = timed(lambda: a3po.token_logprobs(b["z"], b["chosen"], want_chosen_logit=False))
+    res["token_logprobs"] = {"ms": ms, "gbs": T * row / ms / 1e6, "frac": T * row / ms / 1e6 / HBM_PEAK_GBS}
+    ms = timed(lambda: a3po.token_logprobs(b["z"], b["chosen"], want_chosen_logit=False, want_entropy=True))
+    res["token_logprobs_entropy"] = {"ms": ms, "gbs": T * row / ms / 1e6, "frac": T * row / ms / 1e6 / HBM_PEAK_GBS}
+    if V % (shards * 8) == 0:
+        Vs = V // shards
+        parts = torch.empty((shards, T, 4), dtype=torch.float32, device="cuda")
+        views = [b["z"][:, p * Vs:(p + 1) * Vs] for p in range(shards)]
+        dviews = [dz[:, p * Vs:(p + 1) * Vs] for p in range(shards)]
+
+        def fwd():
+            for p in range(shards):
+                a3po.shard_partials(views[p], b["chosen"], p * Vs, out=parts[p])
+            return a3po.shard_combine(parts, b["chosen"], V)
+
+        ms = timed(fwd)
+        res["shard_forward"] = {"shards": shards, "ms": ms, "gbs": T * row / ms / 1e6,
+                                "frac": T * row / ms / 1e6 / HBM_PEAK_GBS}
+        logp, lse, _ = fwd()
+        ones = torch.ones_like(b["mask"])
+        last = {}
+
+        def bwd():
+            for p in range(shards):
+                last.update(a3po.shard_loss_bwd(views[p], p * Vs, V, b["chosen"], logp, lse, b["lb"], b["versions"],
+                                                b["cur"], adv, ones, w.clip_eps, dlogits=dviews[p], workspace=ws))
+
+        ms = timed(bwd)
+        st = a3po.stats_to_dict(last["stats"])
+        live = int((adv != 0).sum().item()) - st["n_clipped"]   # rows whose gradient is not identically zero
+        nbytes = row * (2 * live + (T - live))
+        res["shard_backward"] = {"shards": shards, "ms": ms, "gbs": nbytes / ms / 1e6,
+                                 "frac": nbytes / ms / 1e6 / HBM_PEAK_GBS, "live_rows": live}
+    for k, v in res.items():
+        log(f"{k}: {v['ms']:.3f} ms, {v['gbs']:.0f} GB/s")
+    return res
+
+
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X published dense bf16 peak
 
 
@@ -263,6 +321,8 @@ def main():
                     help="time the workload's own mask, an all-ones mask, or both (default)")
     ap.add_argument("--entropy", action="store_true",
                     help="also compute the per-token policy entropy in the row kernel (a3po_loss_fwd_bwd_ex)")
+    ap.add_argument("--no-secondary", dest="secondary", action="store_false",
+                    help="skip the short timing of the forward-only and vocabulary-sharded kernels")
     ap.add_argument("--quiet", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -328,6 +388,8 @@ def main():
     copy_gbs = 2 * b["z"].numel() * w.elem_bytes * 10 / (e0.elapsed_time(e1) * 1e-3) / 1e9
     log(f"plain copy of the logits matrix: {copy_gbs:.0f} GB/s (read+write)")
 
+    secondary = secondary_kernels(a3po, torch, w, b, adv, dz, ws, log) if args.secondary else None
+
     cpu = None
     if args.cpu_rows > 0:
         import oracle
@@ -370,6 +432,7 @@ def main():
                          "algorithmic_bytes": one["bytes"]}},
         "cpu_baseline": cpu,
         "plain_copy_gbs": copy_gbs,
+        "secondary_kernels": secondary,
     }
     print(json.dumps(line), flush=True)
 

@@ -368,7 +368,7 @@ __global__ __launch_bounds__(kRowThreads) void loss_rows_generic_kernel(const Lo
 // rows dealt round-robin.  `vec` selects 16-byte loads (aligned rows) or element loads.
 constexpr int kFwdThreads = 256;
 constexpr int kFwdWaves = kFwdThreads / kWave;
-constexpr int kFwdUnroll = 4;
+constexpr int kFwdUnroll = 8;  // 16-byte vectors in flight per thread
 
 template <typename DT, bool ENT>
 __global__ __launch_bounds__(kFwdThreads) void logprob_rows_kernel(const void *z, int64_t T, int64_t V, int64_t ld,
@@ -387,12 +387,11 @@ __global__ __launch_bounds__(kFwdThreads) void logprob_rows_kernel(const void *z
         Acc acc;
         seed(acc);
         if (vec) {
-            const uint4 *src = reinterpret_cast<const uint4 *>(in_row);
             int idx = tid;
             for (; idx + (kFwdUnroll - 1) * kFwdThreads < nfull; idx += kFwdUnroll * kFwdThreads) {
                 uint4 v[kFwdUnroll];
 #pragma unroll
-                for (int u = 0; u < kFwdUnroll; ++u) v[u] = src[idx + u * kFwdThreads];
+                for (int u = 0; u < kFwdUnroll; ++u) v[u] = stream_load(in_row + (size_t)(idx + u * kFwdThreads) * 16);
 #pragma unroll
                 for (int u = 0; u < kFwdUnroll; ++u) {
                     float f[EPV];
@@ -402,7 +401,7 @@ __global__ __launch_bounds__(kFwdThreads) void logprob_rows_kernel(const void *z
             }
             for (; idx < nfull; idx += kFwdThreads) {
                 float f[EPV];
-                unpack<DT>(src[idx], f);
+                unpack<DT>(stream_load(in_row + (size_t)idx * 16), f);
                 fold<EPV>(acc, f);
             }
             for (int64_t j = (int64_t)nfull * EPV + tid; j < V; j += kFwdThreads) {

@@ -12,9 +12,19 @@
 
 namespace a3po {
 
-constexpr int kShardThreads = 512;
+// launch shape of the streaming kernels (overridable at build time for tuning sweeps)
+#ifndef A3PO_SHARD_THREADS
+#define A3PO_SHARD_THREADS 256
+#endif
+#ifndef A3PO_SHARD_UNROLL
+#define A3PO_SHARD_UNROLL 8
+#endif
+#ifndef A3PO_SHARD_BLOCKS_PER_CU
+#define A3PO_SHARD_BLOCKS_PER_CU 8
+#endif
+constexpr int kShardThreads = A3PO_SHARD_THREADS;
 constexpr int kShardWaves = kShardThreads / kWave;
-constexpr int kShardUnroll = 4;
+constexpr int kShardUnroll = A3PO_SHARD_UNROLL;  // 16-byte vectors in flight per thread
 
 // ---------------------------------------------------------------------------------------
 // partial (max, sum exp, chosen logit if owned, sum exp * z) of one shard, one workgroup per row
@@ -206,7 +216,7 @@ static unsigned shard_grid(int64_t T)
     if (hipGetDevice(&dev) != hipSuccess ||
         hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
         n = 256;
-    const int64_t want = (int64_t)n * 4;  // 4 x 512 threads fill a compute unit
+    const int64_t want = (int64_t)n * A3PO_SHARD_BLOCKS_PER_CU;
     return (unsigned)(T < want ? T : want);
 }
 
