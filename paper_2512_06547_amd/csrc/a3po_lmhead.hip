@@ -8,10 +8,9 @@
 //
 // Tiling.  A workgroup of 256 threads (4 wavefronts, one per SIMD) computes a 256 (vocabulary) x
 // 256 (tokens) tile, each wavefront a 128 x 128 quarter = 4 x 4 MFMA tiles = 256 accumulator
-// registers.  K (the hidden size) is walked in chunks of 64 through LDS, double buffered:
-// global -> registers for chunk c+1 is issued before the MFMAs of chunk c.  LDS rows are padded
-// from 128 to 144 bytes so that the 16-byte fragment reads of 16 consecutive rows hit distinct
-// banks.
+// registers.  K (the hidden size) is walked in stages of 32 through a ring of LDS buffers that
+// direct global -> LDS loads fill a few stages ahead; the 16-byte pieces of a row are stored
+// permuted so that fragment reads are free of bank conflicts without padding.
 //
 // Schedule.  256 persistent workgroups = 8 XCDs x 32.  Inside an XCD the 32 workgroups form a
 // 4 (token tiles) x 8 (vocabulary tiles) block that moves through the vocabulary together, so at
@@ -26,10 +25,6 @@
 namespace a3po {
 
 constexpr int kLmTile = 256;         // tile edge, both sides
-constexpr int kLmChunk = 64;         // K elements per LDS stage
-constexpr int kLmRowBytes = 144;     // 64 bf16 = 128 bytes + 16 bytes of padding
-constexpr int kLmOperandBytes = kLmTile * kLmRowBytes;  // 36,864
-constexpr int kLmLdsBytes = 4 * kLmOperandBytes;        // 2 stages x 2 operands = 147,456
 constexpr int kLmThreads = 256;
 constexpr int kLmVocabStrides = 8;   // vocabulary tiles walked with this stride (partials per token)
 constexpr int kLmTokenTilesPerXcd = 4;
@@ -69,9 +64,39 @@ __device__ __forceinline__ void fold_column(const f32x16_t (&acc)[4][4], int b, 
     run_s = s;
 }
 
+// ---------------------------------------------------------------------------------------
+// Operands reach LDS by direct global -> LDS loads (global_load_lds_dwordx4: lane l of a wavefront
+// lands at lds_base + 16 l; no staging registers, no LDS write instructions), into a ring of
+// kDmaStages stages of 32 K-elements each, with up to kDmaStages - 1 stages in flight.
+//
+// LDS layout of one operand stage: 256 rows x 64 bytes, unpadded (a direct load fills 16 rows x 64
+// bytes contiguously).  The 16-byte piece p of row r is stored at physical piece p ^ ((r >> 2) & 3):
+// the permutation is applied on the global side (each lane fetches the logical piece that belongs
+// at its physical position), so a fragment read - 16 consecutive rows, same logical piece - touches
+// 16 distinct bank groups.
+//
+// Schedule of stage i (two k-steps of 16 MFMAs): the first k-step runs while the second k-step's
+// fragments are read; then the wavefront waits for its own loads of stage i+1 and for its reads of
+// stage i, all wavefronts meet at one barrier (stage i+1 is now visible, the slot of stage i is
+// free), the loads of stage i + kDmaStages are issued into that slot, and the second k-step runs
+// while the first fragments of stage i+1 are read.
+constexpr int kDmaStages = 4;
+constexpr int kDmaK = 32;                                  // K elements per stage
+constexpr int kDmaRowBytes = kDmaK * 2;                    // 64
+constexpr int kDmaOperandBytes = kLmTile * kDmaRowBytes;   // 16,384
+constexpr int kDmaStageBytes = 2 * kDmaOperandBytes;       // 32,768
+constexpr int kDmaLdsBytes = kDmaStages * kDmaStageBytes;  // 131,072 of the compute unit's 163,840
+
+typedef __attribute__((address_space(3))) void *lds_ptr_t;
+
+__device__ __forceinline__ void dma16(const char *g, char *l)
+{
+    __builtin_amdgcn_global_load_lds(reinterpret_cast<const lm_u32x4_t *>(g), (lds_ptr_t)l, 16, 0, 0);
+}
+
 __global__ __launch_bounds__(kLmThreads) void lmhead_lse_kernel(const uint16_t *__restrict__ W,
-                                                                const uint16_t *__restrict__ h, int64_t T, int64_t H,
-                                                                int64_t V, float2 *__restrict__ partial)
+                                                                    const uint16_t *__restrict__ h, int64_t T,
+                                                                    int64_t H, int64_t V, float2 *__restrict__ partial)
 {
     extern __shared__ __align__(16) char lds[];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -80,30 +105,30 @@ __global__ __launch_bounds__(kLmThreads) void lmhead_lse_kernel(const uint16_t *
     const int mt = slot & (kLmTokenTilesPerXcd - 1), nt = slot / kLmTokenTilesPerXcd;
     const int ntt = (int)((T + kLmTile - 1) / kLmTile), nvt = (int)((V + kLmTile - 1) / kLmTile);
     const int ngroups = (ntt + kLmTokenTilesPerXcd - 1) / kLmTokenTilesPerXcd;
-    const int nchunks = (int)(H / kLmChunk);
+    const int nstages = (int)(H / kDmaK);
+    const int wave_s = __builtin_amdgcn_readfirstlane(wave);  // the wavefront number in a scalar register
 
-    // global -> LDS staging: thread owns the 16-byte piece `piece` of rows lrow + 32 j
-    const int piece = tid & 7, lrow = tid >> 3;
-    const uint32_t st_off = (uint32_t)lrow * kLmRowBytes + (uint32_t)piece * 16;
-    // fragment reads: row (lane & 31) of an MFMA tile, k half (lane >> 5)
-    const uint32_t fa_off = (uint32_t)(wm * 128 + (lane & 31)) * kLmRowBytes + (uint32_t)(lane >> 5) * 16;
-    const uint32_t fb_off = (uint32_t)(wn * 128 + (lane & 31)) * kLmRowBytes + (uint32_t)(lane >> 5) * 16;
+    // direct loads: instruction j of an operand covers tile rows (4 j + wave) 16 .. + 15; lane -> row lane >> 2,
+    // physical piece lane & 3, which holds logical piece (lane & 3) ^ ((row >> 2) & 3) = (lane & 3) ^ ((lane >> 4) & 3)
+    const int drow = lane >> 2;
+    const uint32_t dpiece = (uint32_t)((lane & 3) ^ ((lane >> 4) & 3)) * 16u;
+    // fragment reads: row lane & 31 of a 32-row MFMA tile, k half lane >> 5 of k-step s: logical piece 2 s + (lane >> 5),
+    // physical piece that ^ ((row >> 2) & 3) = that ^ ((lane >> 2) & 3)
+    const uint32_t fr0 = (uint32_t)(lane & 31) * kDmaRowBytes + (uint32_t)(((lane >> 5) ^ ((lane >> 2) & 3)) * 16);
+    const uint32_t fr1 = (uint32_t)(lane & 31) * kDmaRowBytes + (uint32_t)(((2 + (lane >> 5)) ^ ((lane >> 2) & 3)) * 16);
+    const uint32_t fa_base = (uint32_t)(wm * 128) * kDmaRowBytes;
+    const uint32_t fb_base = kDmaOperandBytes + (uint32_t)(wn * 128) * kDmaRowBytes;
 
     for (int g = xcd; g < ngroups; g += 8) {
         const int tt = g * kLmTokenTilesPerXcd + mt;
         if (tt >= ntt) continue;  // uniform over the workgroup
         const int64_t t0 = (int64_t)tt * kLmTile;
-
-        // per-thread element offsets of its 8 staging rows inside the token tile (clamped: tokens
-        // past the end are computed but never written)
         const char *h_tile = reinterpret_cast<const char *>(h + t0 * H);
-        const int t_last = (int)(T - 1 - t0);  // last valid row of this tile (>= 0)
-        uint32_t boff[8];                      // byte offsets inside the tile (< 2^32: 256 rows x H x 2)
+        const int t_last = (int)(T - 1 - t0);
+        uint32_t boff[4];  // rows past the end are clamped (computed, never written)
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            const int r = min(lrow + 32 * j, t_last);
-            boff[j] = (uint32_t)r * (uint32_t)H * 2u + (uint32_t)piece * 16u;
-        }
+        for (int j = 0; j < 4; ++j)
+            boff[j] = (uint32_t)min((4 * j + wave) * 16 + drow, t_last) * (uint32_t)H * 2u + dpiece;
         float run_m[4], run_s[4];
 #pragma unroll
         for (int tn = 0; tn < 4; ++tn) {
@@ -115,12 +140,10 @@ __global__ __launch_bounds__(kLmThreads) void lmhead_lse_kernel(const uint16_t *
             const int64_t v0 = (int64_t)vt * kLmTile;
             const char *w_tile = reinterpret_cast<const char *>(W + v0 * H);
             const int v_last = (int)(V - 1 - v0);
-            uint32_t aoff[8];  // rows past the vocabulary are clamped here and masked below
+            uint32_t aoff[4];  // rows past the vocabulary are clamped here and masked in the fold
 #pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const int r = min(lrow + 32 * j, v_last);
-                aoff[j] = (uint32_t)r * (uint32_t)H * 2u + (uint32_t)piece * 16u;
-            }
+            for (int j = 0; j < 4; ++j)
+                aoff[j] = (uint32_t)min((4 * j + wave) * 16 + drow, v_last) * (uint32_t)H * 2u + dpiece;
             f32x16_t acc[4][4];
 #pragma unroll
             for (int a = 0; a < 4; ++a)
@@ -129,96 +152,101 @@ __global__ __launch_bounds__(kLmThreads) void lmhead_lse_kernel(const uint16_t *
 #pragma unroll
                     for (int e = 0; e < 16; ++e) acc[a][b][e] = 0.0f;
 
-            // K loop, one barrier per chunk.  While the MFMAs of chunk c run from LDS buffer c & 1,
-            // the chunk staged in registers (c+1) is written to the other buffer and the global
-            // loads of chunk c+2 are issued into the registers just freed; LDS writes, global loads
-            // and the fragment reads of the next k-step are interleaved with the MFMAs.  The barrier
-            // at the end of iteration c publishes buffer (c+1) & 1 and guarantees that nobody still
-            // reads buffer c & 1 when iteration c+1 overwrites it.  Past the last chunk the loads are
-            // clamped to it (re-read) instead of branching.
-            lm_u32x4_t ga[8], gb[8];
+            // the two direct loads number q (weight rows, hidden rows) of K-stage `st` (clamped to the last one)
+            // into ring slot `sl`; LDS destinations and the K offset are wave-uniform (scalar registers)
+            auto load_pair = [&](int st, int sl, int q) {
+                const uint32_t koff = (uint32_t)min(st, nstages - 1) * (uint32_t)kDmaRowBytes;
+                char *dst = lds + sl * kDmaStageBytes + wave_s * 1024 + q * 4096;
+                dma16(w_tile + koff + aoff[q], dst);
+                dma16(h_tile + koff + boff[q], dst + kDmaOperandBytes);
+            };
+
+            // prologue: fill the whole ring, then wait for stage 0 and read its first fragments
 #pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                ga[j] = *reinterpret_cast<const lm_u32x4_t *>(w_tile + aoff[j]);
-                gb[j] = *reinterpret_cast<const lm_u32x4_t *>(h_tile + boff[j]);
-            }
+            for (int st = 0; st < kDmaStages; ++st) {
 #pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                *reinterpret_cast<lm_u32x4_t *>(lds + st_off + j * 32 * kLmRowBytes) = ga[j];
-                *reinterpret_cast<lm_u32x4_t *>(lds + kLmOperandBytes + st_off + j * 32 * kLmRowBytes) = gb[j];
+                for (int q = 0; q < 4; ++q) load_pair(st, st, q);
             }
             {
-                const uint32_t koff = (uint32_t)min(1, nchunks - 1) * (kLmChunk * 2);
-#pragma unroll
-                for (int j = 0; j < 8; ++j) {
-                    ga[j] = *reinterpret_cast<const lm_u32x4_t *>(w_tile + (size_t)(aoff[j] + koff));
-                    gb[j] = *reinterpret_cast<const lm_u32x4_t *>(h_tile + (size_t)(boff[j] + koff));
-                }
+                constexpr int kAllow = 8 * (kDmaStages - 1);  // everything issued after stage 0
+                __builtin_amdgcn_s_waitcnt(0x0F70 | (kAllow & 15) | ((kAllow >> 4) << 14));
             }
             __syncthreads();
+            bf16x8_t fa[2][4], fb[2][4];
+#pragma unroll
+            for (int a = 0; a < 4; ++a)
+                fa[0][a] = *reinterpret_cast<const bf16x8_t *>(lds + fa_base + a * 32 * kDmaRowBytes + fr0);
+#pragma unroll
+            for (int b = 0; b < 4; ++b)
+                fb[0][b] = *reinterpret_cast<const bf16x8_t *>(lds + fb_base + b * 32 * kDmaRowBytes + fr0);
+
+            int sl = 0;  // ring slot of the stage being computed
 #pragma unroll 1
-            for (int c = 0; c < nchunks; ++c) {
-                const char *sa = lds + (c & 1) * 2 * kLmOperandBytes;
-                const char *sb = sa + kLmOperandBytes;
-                char *da = lds + ((c + 1) & 1) * 2 * kLmOperandBytes;
-                char *db = da + kLmOperandBytes;
-                const uint32_t koff = (uint32_t)min(c + 2, nchunks - 1) * (kLmChunk * 2);
-                bf16x8_t fa[2][4], fb[2][4];
+            for (int i = 0; i < nstages; ++i) {
+                const char *cur = lds + sl * kDmaStageBytes;
+                const int nsl = sl + 1 == kDmaStages ? 0 : sl + 1;
+                const char *nxt = lds + nsl * kDmaStageBytes;
+                __builtin_amdgcn_sched_barrier(0);
+                // ---- first k-step; the second k-step's fragments are read meanwhile ----
 #pragma unroll
-                for (int a = 0; a < 4; ++a)
-                    fa[0][a] = *reinterpret_cast<const bf16x8_t *>(sa + fa_off + a * 32 * kLmRowBytes);
+                for (int q = 0; q < 4; ++q) {
+                    if (q < 2) {
 #pragma unroll
-                for (int b = 0; b < 4; ++b)
-                    fb[0][b] = *reinterpret_cast<const bf16x8_t *>(sb + fb_off + b * 32 * kLmRowBytes);
+                        for (int a = 2 * q; a < 2 * q + 2; ++a)
+                            fa[1][a] = *reinterpret_cast<const bf16x8_t *>(cur + fa_base + a * 32 * kDmaRowBytes + fr1);
+                    } else {
 #pragma unroll
-                for (int ks = 0; ks < 4; ++ks) {
-                    if (ks < 3) {
-#pragma unroll
-                        for (int a = 0; a < 4; ++a)
-                            fa[(ks + 1) & 1][a] = *reinterpret_cast<const bf16x8_t *>(sa + fa_off + a * 32 * kLmRowBytes + (ks + 1) * 32);
-#pragma unroll
-                        for (int b = 0; b < 4; ++b)
-                            fb[(ks + 1) & 1][b] = *reinterpret_cast<const bf16x8_t *>(sb + fb_off + b * 32 * kLmRowBytes + (ks + 1) * 32);
+                        for (int b = 2 * q - 4; b < 2 * q - 2; ++b)
+                            fb[1][b] = *reinterpret_cast<const bf16x8_t *>(cur + fb_base + b * 32 * kDmaRowBytes + fr1);
                     }
 #pragma unroll
-                    for (int jj = 0; jj < 2; ++jj) {
-                        const int j = 2 * ks + jj;
-                        *reinterpret_cast<lm_u32x4_t *>(da + st_off + j * 32 * kLmRowBytes) = ga[j];
-                        *reinterpret_cast<lm_u32x4_t *>(db + st_off + j * 32 * kLmRowBytes) = gb[j];
-                        ga[j] = *reinterpret_cast<const lm_u32x4_t *>(w_tile + (size_t)(aoff[j] + koff));
-                        gb[j] = *reinterpret_cast<const lm_u32x4_t *>(h_tile + (size_t)(boff[j] + koff));
-                    }
-#pragma unroll
-                    for (int a = 0; a < 4; ++a)
-#pragma unroll
-                        for (int b = 0; b < 4; ++b)
-                            acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[ks & 1][a], fb[ks & 1][b], acc[a][b], 0, 0, 0);
-                    // spread this k-step's memory instructions between its MFMAs
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);  // MFMA
-                        __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);  // LDS reads (next k-step's fragments)
-                        __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);  // LDS write (next chunk)
-                        __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);  // global load (chunk after next)
-                    }
+                    for (int b = 0; b < 4; ++b)
+                        acc[q][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[0][q], fb[0][b], acc[q][b], 0, 0, 0);
+                    __builtin_amdgcn_sched_barrier(0);
                 }
+                // ---- stage i+1 has landed (own loads: the kDmaStages - 2 stages after it may still be in
+                // flight), stage i is no longer read (own reads, lgkmcnt(0)): meet ----
+                __builtin_amdgcn_s_waitcnt(0x0070 | (8 * (kDmaStages - 2) & 15) | ((8 * (kDmaStages - 2) >> 4) << 14));
                 __syncthreads();
+                __builtin_amdgcn_sched_barrier(0);
+                // ---- second k-step; the first fragments of stage i+1 are read and the freed slot is refilled
+                // meanwhile, two direct loads per group of four MFMAs ----
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    load_pair(i + kDmaStages, sl, q);
+                    if (q < 2) {
+#pragma unroll
+                        for (int a = 2 * q; a < 2 * q + 2; ++a)
+                            fa[0][a] = *reinterpret_cast<const bf16x8_t *>(nxt + fa_base + a * 32 * kDmaRowBytes + fr0);
+                    } else {
+#pragma unroll
+                        for (int b = 2 * q - 4; b < 2 * q - 2; ++b)
+                            fb[0][b] = *reinterpret_cast<const bf16x8_t *>(nxt + fb_base + b * 32 * kDmaRowBytes + fr0);
+                    }
+#pragma unroll
+                    for (int b = 0; b < 4; ++b)
+                        acc[q][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[1][q], fb[1][b], acc[q][b], 0, 0, 0);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+                sl = nsl;
             }
+            // drain: the clamped loads past the last stage must have landed before the ring is refilled
+            __builtin_amdgcn_s_waitcnt(0x0070);  // vmcnt(0) lgkmcnt(0)
+            __syncthreads();
 
             // ---- fold the tile into the running (max, sum) of this lane's four token columns ----
-            // acc[a][b][4 i + j] = z[vocab v0 + wm 128 + a 32 + 8 i + (lane >> 5) 4 + j][token column b]
-            const bool ragged = v0 + kLmTile > V;  // last vocabulary tile: rows past V are masked
-            const int vlim = (int)(V - v0) - wm * 128 - (lane >> 5) * 4;  // row offsets >= vlim are past V
+            const bool ragged = v0 + kLmTile > V;
+            const int vlim = (int)(V - v0) - wm * 128 - (lane >> 5) * 4;
 #pragma unroll
             for (int b = 0; b < 4; ++b) {
                 if (ragged) fold_column<true>(acc, b, vlim, run_m[b], run_s[b]);
                 else fold_column<false>(acc, b, vlim, run_m[b], run_s[b]);
-                __builtin_amdgcn_sched_barrier(0);  // one token column at a time
+                __builtin_amdgcn_sched_barrier(0);
             }
         }
 
         // ---- end of the sweep: merge the two lane halves, then the two vocabulary halves ----
-        float2 *red = reinterpret_cast<float2 *>(lds);  // [2][256]; tile buffers are idle after the last barrier
+        float2 *red = reinterpret_cast<float2 *>(lds);  // [2][256]; the ring is idle after the drain barrier
 #pragma unroll
         for (int b = 0; b < 4; ++b) {
             MaxSum mine = {run_m[b], run_s[b]};
@@ -287,12 +315,12 @@ hipError_t launch_fused_lmhead_logprob(const void *hidden, const void *weight, i
     static bool attr_set = false;
     if (!attr_set) {
         const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(lmhead_lse_kernel),
-                                                 hipFuncAttributeMaxDynamicSharedMemorySize, kLmLdsBytes);
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, kDmaLdsBytes);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
     float2 *partial = reinterpret_cast<float2 *>(workspace);
-    hipLaunchKernelGGL(lmhead_lse_kernel, dim3(256), dim3(kLmThreads), kLmLdsBytes, s,
+    hipLaunchKernelGGL(lmhead_lse_kernel, dim3(256), dim3(kLmThreads), kDmaLdsBytes, s,
                        reinterpret_cast<const uint16_t *>(weight), reinterpret_cast<const uint16_t *>(hidden), T, H, V,
                        partial);
     hipError_t e = hipGetLastError();

@@ -18,7 +18,10 @@
 
 namespace a3po {
 
-constexpr int64_t kLmBwdChunk = 8192;  // tokens whose logits live in HBM at a time
+#ifndef A3PO_LM_BWD_CHUNK
+#define A3PO_LM_BWD_CHUNK 8192
+#endif
+constexpr int64_t kLmBwdChunk = A3PO_LM_BWD_CHUNK;  // tokens whose logits live in HBM at a time
 
 struct LmBwdLayout {
     size_t loss_ws, zchunk, dwacc, total;
