@@ -209,8 +209,33 @@ def secondary_kernels(a3po, torch, w, b, adv, dz, ws, log, reps=10, shards=8):
         nbytes = row * (2 * live + (T - live))
         res["shard_backward"] = {"shards": shards, "ms": ms, "gbs": nbytes / ms / 1e6,
                                  "frac": nbytes / ms / 1e6 / HBM_PEAK_GBS, "live_rows": live}
+    # the same batch as 4 gradient updates of micro-batches within the paper's 10,240-token budget (Section 4.1):
+    # plan on the host, one token count per mini-batch kept on the device, one loss call per micro-batch
+    import numpy as np
+    first, owner = a3po.plan_microbatches(np.full(w.S, w.L, dtype=np.int64), 4, 10240)
+    spans = [(int(first[i]) * w.L, int(first[i + 1]) * w.L, int(owner[i])) for i in range(len(owner))]
+    mb_rows = {k: (min(a for a, _, o in spans if o == k), max(b_ for _, b_, o in spans if o == k))
+               for k in set(owner.tolist())}
+    mb_out = {}
+
+    def minibatched():
+        seen = set()
+        for a, e, k in spans:
+            if k not in seen:
+                r0, r1 = mb_rows[k]
+                mb_out[("denom", k)] = a3po.count_tokens(b["chosen"][r0:r1], b["mask"][r0:r1], V)
+            o = mb_out.get(("out", k), {})
+            mb_out[("out", k)] = a3po.loss_fwd_bwd(
+                b["z"][a:e], b["chosen"][a:e], b["lb"][a:e], b["versions"][a:e], b["cur"], adv[a:e], b["mask"][a:e],
+                w.clip_eps, V=V, dlogits=dz[a:e], workspace=ws, denom_dev=mb_out[("denom", k)], accumulate=k in seen,
+                out=dict(loss=o.get("loss"), stats=o.get("stats"), logp=o.get("logp"), logp_prox=o.get("logp_prox")))
+            seen.add(k)
+
+    ms = timed(minibatched)
+    res["minibatched_step"] = {"ms": ms, "calls": len(spans), "minibatches": len(mb_rows), "token_budget": 10240,
+                               "tokens_per_s": T / ms * 1e3}
     for k, v in res.items():
-        log(f"{k}: {v['ms']:.3f} ms, {v['gbs']:.0f} GB/s")
+        log(f"{k}: {v['ms']:.3f} ms" + (f", {v['gbs']:.0f} GB/s" if "gbs" in v else f", {v['tokens_per_s'] / 1e6:.2f} M tokens/s"))
     return res
 
 
