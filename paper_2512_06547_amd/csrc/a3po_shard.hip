@@ -208,6 +208,148 @@ __global__ __launch_bounds__(kShardThreads) void shard_bwd_rows_kernel(
 }
 
 // ---------------------------------------------------------------------------------------
+// The same gradient slice in bursts.  A workgroup of 1024 threads takes an item of up to 19 x 1024 (float32: 16 x 1024)
+// sixteen-byte vectors - several whole shard rows when they are short, one row, or one column chunk
+// of a long row - loads all of it into registers, then computes and stores all of it: the
+// read-a-burst / write-a-burst rhythm of the fused row kernel, which HBM rewards over fine-grained
+// interleaving of loads and stores (about 5.9 against 5.0 TB/s on the same matrix).
+// Vector path only (16-byte aligned bases and stride).  Per-row scalars of the item's rows are
+// evaluated by the first threads and handed over through LDS (double-buffered by item parity, so one
+// barrier per item suffices); the chosen column's +g is added in registers by the thread that holds
+// that element.  Items come from the workspace's queue counter.
+constexpr int kBurstThreads = 1024;
+template <typename DT> struct BurstVec { static constexpr int value = 19; };  // vectors per thread and item
+template <> struct BurstVec<F32> { static constexpr int value = 16; };  // (what fits in 128 registers)
+
+// hides a value's origin from the optimizer, so that index arithmetic is redone where it is needed
+// instead of being kept in registers across the bursts (there are none to spare)
+__device__ __forceinline__ int opaque(int x)
+{
+    asm volatile("" : "+v"(x));
+    return x;
+}
+
+struct BurstShape {
+    int nvec_row;    // 16-byte vectors per shard row (the last one may be partial)
+    int rows;        // rows per item (1 when a row is cut into chunks)
+    int chunks;      // column chunks per row
+    int chunk_vec;   // vectors per chunk
+    uint32_t magic;  // floor(2^32 / nvec_row) + 1: i / nvec_row == umulhi(i, magic) for i, nvec_row < 2^16
+    int64_t items;
+};
+
+// SINGLE: an item is one row (or one column chunk of a row): no index divisions in the bursts.
+template <typename DT, bool SINGLE>
+__global__ __launch_bounds__(kBurstThreads) void shard_bwd_burst_kernel(
+    const void *z, void *dz, int64_t T, int64_t Vs, int64_t ld, int64_t v0, const TokenRecord *__restrict__ records,
+    const float *__restrict__ logp_theta, const float *__restrict__ lse_in, int32_t current_version, float clip_eps,
+    int prox_mode, const WsHeader *__restrict__ hdr, unsigned int *queue, RowOutputs out, BurstShape sh)
+{
+    constexpr int EPV = DT::kPerVec;
+    constexpr int kBurstVec = BurstVec<DT>::value;
+    __shared__ float s_negg[2][kBurstThreads], s_nlse[2][kBurstThreads];
+    __shared__ int s_ycol[2][kBurstThreads];  // chosen column inside the shard, or -1
+    __shared__ unsigned int s_next[2];
+    const int tid = threadIdx.x;
+    const size_t row_bytes = (size_t)ld * DT::kBytes;
+    const float inv_n = hdr->inv_n;
+    const int rem = (int)(Vs % EPV);  // elements of the partial last vector of a row (0 = none)
+    int par = 0;
+
+    int64_t item = blockIdx.x;
+    while (item < sh.items) {
+        const int64_t r0 = (item / sh.chunks) * sh.rows;
+        const int chunk = (int)(item % sh.chunks);
+        const int c0 = chunk * sh.chunk_vec;                          // first vector column of the item
+        const int cw = min(sh.chunk_vec, sh.nvec_row - c0);           // vector columns of the item
+        const int nrows = (int)min((int64_t)sh.rows, T - r0);
+        const int nvec = nrows * cw;
+        if (tid == 0) s_next[par] = atomicAdd(queue, 1u);
+        if (tid < nrows) {
+            const int64_t row = r0 + tid;
+            const TokenRecord cur = records[row];
+            float g = 0.0f, lse = 0.0f;
+            if (cur.y >= 0) {
+                lse = lse_in[row];
+                const TokenTerms tt =
+                    token_terms(logp_theta[row], cur.lb, cur.ver, current_version, cur.A, clip_eps, inv_n, prox_mode);
+                g = tt.g;
+                if (chunk == 0) {
+                    if (out.prox) out.prox[row] = tt.lp;
+                    out.obj[row] = tt.obj;
+                    out.iw[row] = tt.iw;
+                    out.flags[row] = (uint8_t)(kFlagCounted | (tt.clipped ? kFlagClipped : 0) |
+                                               (tt.negative_staleness ? kFlagNegStale : 0));
+                }
+            } else if (chunk == 0) {
+                if (out.prox) out.prox[row] = 0.0f;
+                out.obj[row] = 0.0f;
+                out.iw[row] = 0.0f;
+                out.flags[row] = 0;
+            }
+            const int64_t yl = (int64_t)cur.y - v0;
+            s_negg[par][tid] = -g;
+            s_nlse[par][tid] = -lse * kLog2e;
+            s_ycol[par][tid] = (cur.y >= 0 && yl >= 0 && yl < Vs) ? (int)yl : -1;
+        }
+        __syncthreads();
+        const int64_t next = (int64_t)gridDim.x + (int64_t)s_next[par];
+
+        // ---- which of this thread's vectors belong to a row with a gradient (one bit each), so that the
+        // loads below are issued back to back without waiting on LDS in between ----
+        uint32_t live = 0;
+#pragma unroll
+        for (int k = 0; k < kBurstVec; ++k) {
+            const int i = k * kBurstThreads + tid;
+            if (i < nvec && s_negg[par][SINGLE ? 0 : (int)__umulhi((uint32_t)i, sh.magic)] != 0.0f) live |= 1u << k;
+        }
+        // ---- the read burst (row and column of a vector are recomputed rather than kept in registers) ----
+        uint4 v[kBurstVec];
+#pragma unroll
+        for (int k = 0; k < kBurstVec; ++k) {
+            if (live >> k & 1u) {
+                const int i = opaque(k * kBurstThreads + tid);
+                const int r = SINGLE ? 0 : (int)__umulhi((uint32_t)i, sh.magic), c = c0 + (i - r * cw);
+                v[k] = stream_load(reinterpret_cast<const char *>(z) + (size_t)(r0 + r) * row_bytes + (size_t)c * 16);
+            }
+        }
+        // the whole workgroup finishes reading before anyone writes: phases of 16 wavefronts, not of one
+        __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
+        __syncthreads();
+        // ---- the write burst ----
+#pragma unroll
+        for (int k = 0; k < kBurstVec; ++k) {
+            const int i = opaque(k * kBurstThreads + tid);
+            if (i >= nvec) continue;
+            const int r = SINGLE ? 0 : (int)__umulhi((uint32_t)i, sh.magic), c = c0 + (i - r * cw);
+            const float neg_g = s_negg[par][r];
+            char *dst = reinterpret_cast<char *>(dz) + (size_t)(r0 + r) * row_bytes + (size_t)c * 16;
+            float f[EPV];
+            if (neg_g != 0.0f) {
+                const float nlse = s_nlse[par][r];
+                unpack<DT>(v[k], f);
+                const int ye = s_ycol[par][r] - c * EPV;  // the chosen column's place in this vector
+#pragma unroll
+                for (int e = 0; e < EPV; ++e) {
+                    f[e] = neg_g * exp2_hw(fmaf(f[e], kLog2e, nlse));
+                    if (e == ye) f[e] -= neg_g;  // + g
+                }
+            } else {
+#pragma unroll
+                for (int e = 0; e < EPV; ++e) f[e] = 0.0f;
+            }
+            if (rem != 0 && c == sh.nvec_row - 1) {  // partial last vector: the columns beyond belong to a neighbour
+                for (int e = 0; e < rem; ++e) store_elem<DT>(dst, e, f[e]);
+            } else {
+                stream_store(dst, pack<DT>(f));
+            }
+        }
+        par ^= 1;
+        item = next;
+    }
+}
+
+// ---------------------------------------------------------------------------------------
 static bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 static unsigned shard_grid(int64_t T)
@@ -244,6 +386,25 @@ hipError_t launch_shard_combine(const a3po_shard_partial *parts, int32_t P, int6
     return hipGetLastError();
 }
 
+static BurstShape burst_shape(int64_t T, int64_t Vs, int64_t esz)
+{
+    const int64_t cap = (int64_t)(esz == 4 ? BurstVec<F32>::value : BurstVec<Bf16>::value) * kBurstThreads;
+    BurstShape sh;
+    sh.nvec_row = (int)((Vs * esz + 15) / 16);
+    if (sh.nvec_row <= cap) {
+        sh.rows = (int)(cap / sh.nvec_row < kBurstThreads ? cap / sh.nvec_row : kBurstThreads);
+        sh.chunks = 1;
+        sh.chunk_vec = sh.nvec_row;
+    } else {
+        sh.rows = 1;
+        sh.chunks = (int)((sh.nvec_row + cap - 1) / cap);
+        sh.chunk_vec = (sh.nvec_row + sh.chunks - 1) / sh.chunks;
+    }
+    sh.magic = (uint32_t)((1ull << 32) / (uint64_t)sh.nvec_row + 1);  // used only when rows > 1 (then cw == nvec_row)
+    sh.items = ((T + sh.rows - 1) / sh.rows) * sh.chunks;
+    return sh;
+}
+
 hipError_t launch_shard_bwd_rows(const LossArgs &a, int64_t v0, const float *logp_theta, const float *lse, hipStream_t s)
 {
     if (a.T == 0) return hipSuccess;
@@ -251,6 +412,27 @@ hipError_t launch_shard_bwd_rows(const LossArgs &a, int64_t v0, const float *log
     const int vec = aligned16(a.z) && aligned16(a.dz) && (a.ld * esz) % 16 == 0;
     const RowOutputs out = {nullptr, a.prox_out, a.ws_obj, a.ws_iw, nullptr, a.ws_flags};
     const WsHeader *hdr = reinterpret_cast<const WsHeader *>(a.ws_header);
+    if (vec) {  // bursts; the queue counter in the workspace header was zeroed by the prep kernel
+        const BurstShape sh = burst_shape(a.T, a.V, esz);
+        int dev = 0, cus = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
+            cus = 256;
+        const unsigned grid = (unsigned)(sh.items < cus ? sh.items : cus);
+#define A3PO_BURST_LAUNCH(DT, SINGLE) \
+    hipLaunchKernelGGL((shard_bwd_burst_kernel<DT, SINGLE>), dim3(grid), dim3(kBurstThreads), 0, s, a.z, a.dz, a.T, a.V, \
+                       a.ld, v0, a.ws_records, logp_theta, lse, a.current_version, a.clip_eps, a.prox_mode, hdr, \
+                       row_queue_of(a.ws_header), out, sh)
+        if (a.dt == A3PO_F32) {
+            if (sh.rows == 1) A3PO_BURST_LAUNCH(F32, true);
+            else A3PO_BURST_LAUNCH(F32, false);
+        } else {
+            if (sh.rows == 1) A3PO_BURST_LAUNCH(Bf16, true);
+            else A3PO_BURST_LAUNCH(Bf16, false);
+        }
+#undef A3PO_BURST_LAUNCH
+        return hipGetLastError();
+    }
     if (a.dt == A3PO_F32)
         hipLaunchKernelGGL((shard_bwd_rows_kernel<F32>), dim3(shard_grid(a.T)), dim3(kShardThreads), 0, s, a.z, a.dz,
                            a.T, a.V, a.ld, v0, a.ws_records, logp_theta, lse, a.current_version, a.clip_eps,

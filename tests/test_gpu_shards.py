@@ -111,13 +111,20 @@ def test_eight_even_shards_of_the_full_vocabulary_bf16(a3po):
     print(f"8 shards: N={st['n_tokens']} clipped={st['n_clipped']} excused={excused}")
 
 
-def test_uneven_shards_bf16(a3po):
+@pytest.mark.parametrize("bounds", [[0, 50000, 110008, 151936],     # 3 / 2 / 3 rows per burst
+                                    [0, 50004, 151936]])             # a partial last vector next to a neighbour's
+                                                                     # columns; the second base is only 8-byte aligned
+def test_uneven_shards_bf16(a3po, bounds):
     w = synth.WORKLOADS["1p5b"].scaled(S=8, L=4, G=8, len_lo=2, len_hi=4, noise_std=0.3)
     c = make_case(w)
-    bounds = [0, 50000, 110008, w.V]
+    c["chosen"][1] = bounds[1] - 1        # last column of the first shard
+    c["chosen"][2] = bounds[1]            # first column of the second
+    fwd = oracle.token_logprobs(c["z"], c["chosen"], V=w.V)
+    c["lb"] = synth.behav_from_target(fwd["logp"], c["tk"]["noise"][:c["T"]])
     res = run_sharded(a3po, c, bounds)
     check_partials(c, res, bounds)
     check_merged(a3po, c, res)
+    assert not (res["dlogits"].float() == 5.0).any(), "every column was written by exactly its own shard"
 
 
 @pytest.mark.parametrize("dtype,V,bounds", [
@@ -125,6 +132,8 @@ def test_uneven_shards_bf16(a3po):
     ("f32", 4099, [0, 1001, 2002, 4099]),            # odd widths: element-wise path
     ("bf16", 5001, [0, 3, 4, 2500, 5001]),           # tiny shards, one of a single column
     ("bf16", 70000, [0, 70000]),                     # a single shard is the whole vocabulary
+    ("f32", 70000, [0, 70000]),                      # 17,500 vectors per row: two column chunks per row
+    ("bf16", 163848, [0, 163848]),                   # 20,481 vectors per row: two chunks, the last vector whole
 ])
 def test_contiguous_shards(a3po, dtype, V, bounds):
     w = synth.WORKLOADS["tiny"].scaled(V=V, dtype=dtype, S=4, L=8, len_lo=4, len_hi=8, sigma=3.0, boost=6.0,
