@@ -20,9 +20,10 @@
  *  - Logits are row-major [T, V] with a row stride of `ld` elements (ld >= V), float32
  *    or bfloat16.  Row t pairs with chosen[t]; any next-token shift is the caller's.
  *    Base pointers of logits / dlogits must be aligned to their element size.  Rows whose base
- *    and byte stride are multiples of 16 and that fit on chip (V <= 163,840 bfloat16 / 81,920
- *    float32) take the single-pass kernels; everything else takes slower element-wise multi-pass
- *    kernels with identical results up to rounding order.
+ *    and byte stride are multiples of 16 take vectorised kernels: a single pass (each row read once
+ *    and written once) when the row fits on chip (V <= 163,840 bfloat16 / 81,920 float32), three
+ *    streaming passes (read, read, write) when it does not.  Everything else takes slower element-wise
+ *    multi-pass kernels.  Results are identical up to rounding order.
  */
 #ifndef A3PO_H
 #define A3PO_H

@@ -136,7 +136,6 @@ int a3po_loss_fwd_bwd_ex(const void *logits, a3po_dtype dt, int64_t T, int64_t V
     if (!aligned(workspace, 256)) return A3PO_E_ALIGN;
 
     hipStream_t s = static_cast<hipStream_t>(stream);
-    char *ws = static_cast<char *>(workspace);
     LossArgs a;
     a.z = logits;
     a.dz = dlogits;
@@ -163,11 +162,7 @@ int a3po_loss_fwd_bwd_ex(const void *logits, a3po_dtype dt, int64_t T, int64_t V
     a.clipped_out = o.clipped_out;
     a.denom_dev = o.denom_dev;
     a.accumulate = o.accumulate;
-    a.ws_header = ws;
-    a.ws_records = reinterpret_cast<TokenRecord *>(ws + lay.records);
-    a.ws_obj = reinterpret_cast<float *>(ws + lay.obj);
-    a.ws_iw = reinterpret_cast<float *>(ws + lay.iw);
-    a.ws_flags = reinterpret_cast<uint8_t *>(ws + lay.flags);
+    carve_loss_ws(a, workspace, T);
 
     if (launch_loss_prep(a, s) != hipSuccess) return A3PO_E_LAUNCH;
     if (o.event_before_rows && hipEventRecord(static_cast<hipEvent_t>(o.event_before_rows), s) != hipSuccess)
@@ -244,7 +239,7 @@ int a3po_shard_partials(const void *logits_shard, a3po_dtype dt, int64_t T, int6
     if (T == 0) return A3PO_OK;
     if (!chosen || !partial_out) return A3PO_E_NULL;
     if (!aligned(partial_out, 16)) return A3PO_E_ALIGN;
-    const hipError_t e = launch_shard_partials(logits_shard, (int)dt, T, Vs, ld, chosen, v0, partial_out,
+    const hipError_t e = launch_shard_partials(logits_shard, (int)dt, T, Vs, ld, chosen, v0, partial_out, nullptr,
                                                static_cast<hipStream_t>(stream));
     return e == hipSuccess ? A3PO_OK : A3PO_E_LAUNCH;
 }
@@ -256,7 +251,7 @@ int a3po_shard_combine(const a3po_shard_partial *partials, int32_t P, int64_t T,
     if (T == 0) return A3PO_OK;
     if (!partials || !chosen || !logp_out) return A3PO_E_NULL;
     if (!aligned(partials, 16)) return A3PO_E_ALIGN;
-    const hipError_t e = launch_shard_combine(partials, P, T, chosen, V, logp_out, lse_out, entropy_out,
+    const hipError_t e = launch_shard_combine(partials, P, T, chosen, V, logp_out, lse_out, entropy_out, nullptr,
                                               static_cast<hipStream_t>(stream));
     return e == hipSuccess ? A3PO_OK : A3PO_E_LAUNCH;
 }
@@ -286,7 +281,6 @@ int a3po_shard_loss_bwd(const void *logits_shard, a3po_dtype dt, int64_t T, int6
     if (!aligned(workspace, 256)) return A3PO_E_ALIGN;
 
     hipStream_t s = static_cast<hipStream_t>(stream);
-    char *ws = static_cast<char *>(workspace);
     LossArgs a;
     a.z = logits_shard;
     a.dz = dlogits_shard;
@@ -312,11 +306,7 @@ int a3po_shard_loss_bwd(const void *logits_shard, a3po_dtype dt, int64_t T, int6
     a.clipped_out = o.clipped_out;
     a.denom_dev = o.denom_dev;
     a.accumulate = o.accumulate;
-    a.ws_header = ws;
-    a.ws_records = reinterpret_cast<TokenRecord *>(ws + lay.records);
-    a.ws_obj = reinterpret_cast<float *>(ws + lay.obj);
-    a.ws_iw = reinterpret_cast<float *>(ws + lay.iw);
-    a.ws_flags = reinterpret_cast<uint8_t *>(ws + lay.flags);
+    carve_loss_ws(a, workspace, T);
     if (launch_loss_prep(a, s) != hipSuccess) return A3PO_E_LAUNCH;
     LossArgs b = a;
     b.V = Vs;  // the row kernel walks the shard's columns

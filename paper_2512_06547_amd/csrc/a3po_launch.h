@@ -40,11 +40,13 @@ struct LossArgs {
     float *ws_obj;
     float *ws_iw;
     uint8_t *ws_flags;
+    float *ws_lse;                  // [T], three-pass path only (rows too long for the registers)
+    a3po_shard_partial *ws_partial; // [T], three-pass path only
 };
 
-// Workspace of the loss path: header | TokenRecord[T] (16 bytes each) | obj[T] | iw[T] | flags[T]
+// Workspace of the loss path: header | TokenRecord[T] (16 bytes each) | obj[T] | iw[T] | flags[T] | lse[T] | partial[T]
 struct LossWsLayout {
-    size_t records, obj, iw, flags, total;
+    size_t records, obj, iw, flags, lse, partial, total;
 };
 inline LossWsLayout loss_ws_layout(int64_t T)
 {
@@ -55,8 +57,24 @@ inline LossWsLayout loss_ws_layout(int64_t T)
     l.obj = l.records + up(t * 16);
     l.iw = l.obj + up(t * sizeof(float));
     l.flags = l.iw + up(t * sizeof(float));
-    l.total = l.flags + up(t);
+    l.lse = l.flags + up(t);
+    l.partial = l.lse + up(t * sizeof(float));
+    l.total = l.partial + up(t * sizeof(a3po_shard_partial));
     return l;
+}
+
+// points the workspace fields of `a` into a workspace laid out for T tokens
+inline void carve_loss_ws(LossArgs &a, void *workspace, int64_t T)
+{
+    char *ws = static_cast<char *>(workspace);
+    const LossWsLayout lay = loss_ws_layout(T);
+    a.ws_header = ws;
+    a.ws_records = reinterpret_cast<TokenRecord *>(ws + lay.records);
+    a.ws_obj = reinterpret_cast<float *>(ws + lay.obj);
+    a.ws_iw = reinterpret_cast<float *>(ws + lay.iw);
+    a.ws_flags = reinterpret_cast<uint8_t *>(ws + lay.flags);
+    a.ws_lse = reinterpret_cast<float *>(ws + lay.lse);
+    a.ws_partial = reinterpret_cast<a3po_shard_partial *>(ws + lay.partial);
 }
 
 // true when the single-pass register-resident kernel can take these rows
@@ -76,10 +94,13 @@ hipError_t launch_proximal_interp(const float *lb, const float *lt, const int32_
 hipError_t launch_grpo_advantages(const float *rewards, int64_t S, int32_t G, float eps_adv, const int32_t *seq_id,
                                   int64_t T, float *adv, hipStream_t s);
 
+// records (nullable): rows whose record says "not counted" are skipped (partials) / get zeros (combine)
 hipError_t launch_shard_partials(const void *z, int dt, int64_t T, int64_t Vs, int64_t ld, const int32_t *chosen,
-                                 int64_t v0, a3po_shard_partial *out, hipStream_t s);
+                                 int64_t v0, a3po_shard_partial *out, const TokenRecord *records, hipStream_t s);
 hipError_t launch_shard_combine(const a3po_shard_partial *parts, int32_t P, int64_t T, const int32_t *chosen, int64_t V,
-                                float *logp, float *lse, float *ent, hipStream_t s);
+                                float *logp, float *lse, float *ent, const TokenRecord *records, hipStream_t s);
+// the loss rows in three streaming passes (partials, merge, gradient bursts) for rows that do not fit on chip
+hipError_t launch_loss_rows_three_pass(const LossArgs &a, hipStream_t s);
 // a.V is the shard width here; a.ws_records must come from a prep launch made with the full vocabulary size
 hipError_t launch_shard_bwd_rows(const LossArgs &a, int64_t v0, const float *logp_theta, const float *lse, hipStream_t s);
 

@@ -104,7 +104,6 @@ extern "C" int a3po_fused_lmhead_loss_fwd_bwd(const void *hidden, const void *we
     if (rocblas_set_pointer_mode(hd, rocblas_pointer_mode_host) != rocblas_status_success) return A3PO_E_LAUNCH;
 
     char *ws = static_cast<char *>(workspace);
-    const LossWsLayout lw = loss_ws_layout(T);
     uint16_t *zc = reinterpret_cast<uint16_t *>(ws + lay.zchunk);
     float *dwacc = reinterpret_cast<float *>(ws + lay.dwacc);
     const uint16_t *h = static_cast<const uint16_t *>(hidden);
@@ -129,11 +128,7 @@ extern "C" int a3po_fused_lmhead_loss_fwd_bwd(const void *hidden, const void *we
     a.prox_out = logp_prox_out;
     a.loss_out = loss_out;
     a.stats_out = stats_out;
-    a.ws_header = ws;
-    a.ws_records = reinterpret_cast<TokenRecord *>(ws + lw.records);
-    a.ws_obj = reinterpret_cast<float *>(ws + lw.obj);
-    a.ws_iw = reinterpret_cast<float *>(ws + lw.iw);
-    a.ws_flags = reinterpret_cast<uint8_t *>(ws + lw.flags);
+    carve_loss_ws(a, ws, T);
 
     // token count, 1/N and the per-token records for the whole batch
     if (launch_loss_prep(a, s) != hipSuccess) return A3PO_E_LAUNCH;
@@ -153,6 +148,8 @@ extern "C" int a3po_fused_lmhead_loss_fwd_bwd(const void *hidden, const void *we
         c.ws_obj = a.ws_obj + c0;
         c.ws_iw = a.ws_iw + c0;
         c.ws_flags = a.ws_flags + c0;
+        c.ws_lse = a.ws_lse + c0;
+        c.ws_partial = a.ws_partial + c0;
         if (c0 > 0 && launch_reset_row_queue(ws, s) != hipSuccess) return A3PO_E_LAUNCH;
         if (launch_loss_rows(c, s) != hipSuccess) return A3PO_E_LAUNCH;
         // dh_chunk^T [H, n] = W [H, V] dz^T [V, n]

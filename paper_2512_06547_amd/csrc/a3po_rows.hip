@@ -463,6 +463,8 @@ static hipError_t launch_loss_rows_t(const LossArgs &a, hipStream_t s)
     const int cus = device_cu_count();
     const unsigned grid = (unsigned)(a.T < (int64_t)cus ? a.T : (int64_t)cus);
     if (!rows_fit_on_chip(a.dt, a.V, a.ld, a.z, a.dz)) {
+        // aligned but too long for the registers: three vectorised streaming passes
+        if (aligned16(a.z) && aligned16(a.dz) && (a.ld * DT::kBytes) % 16 == 0) return launch_loss_rows_three_pass(a, s);
         hipLaunchKernelGGL((loss_rows_generic_kernel<DT>), dim3(grid * 2 > a.T ? (unsigned)a.T : grid * 2),
                            dim3(kRowThreads), 0, s, a);
         return hipGetLastError();

@@ -31,7 +31,8 @@ constexpr int kShardUnroll = A3PO_SHARD_UNROLL;  // 16-byte vectors in flight pe
 template <typename DT>
 __global__ __launch_bounds__(kShardThreads) void shard_partials_kernel(const void *z, int64_t T, int64_t Vs, int64_t ld,
                                                                       const int32_t *__restrict__ chosen, int64_t v0,
-                                                                      a3po_shard_partial *__restrict__ out, int vec)
+                                                                      a3po_shard_partial *__restrict__ out,
+                                                                      const TokenRecord *__restrict__ records, int vec)
 {
     constexpr int EPV = DT::kPerVec;
     __shared__ float red[3 * kShardWaves];
@@ -40,6 +41,7 @@ __global__ __launch_bounds__(kShardThreads) void shard_partials_kernel(const voi
     const size_t row_bytes = (size_t)ld * DT::kBytes;
 
     for (int64_t row = blockIdx.x; row < T; row += gridDim.x) {
+        if (records && records[row].y < 0) continue;  // not counted: the row is not read (uniform over the workgroup)
         const char *in_row = reinterpret_cast<const char *>(z) + (size_t)row * row_bytes;
         MaxSumU acc;
         seed(acc);
@@ -88,10 +90,16 @@ __global__ __launch_bounds__(kShardThreads) void shard_partials_kernel(const voi
 // the launch shape)
 __global__ void shard_combine_kernel(const a3po_shard_partial *__restrict__ parts, int32_t P, int64_t T,
                                      const int32_t *__restrict__ chosen, int64_t V, float *logp, float *lse_out,
-                                     float *ent_out)
+                                     float *ent_out, const TokenRecord *__restrict__ records)
 {
     const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (t >= T) return;
+    if (records && records[t].y < 0) {  // not counted: no partial was written
+        logp[t] = 0.0f;
+        if (lse_out) lse_out[t] = 0.0f;
+        if (ent_out) ent_out[t] = 0.0f;
+        return;
+    }
     MaxSumU tot;
     seed(tot);
     float zy = 0.0f;
@@ -363,26 +371,26 @@ static unsigned shard_grid(int64_t T)
 }
 
 hipError_t launch_shard_partials(const void *z, int dt, int64_t T, int64_t Vs, int64_t ld, const int32_t *chosen,
-                                 int64_t v0, a3po_shard_partial *out, hipStream_t s)
+                                 int64_t v0, a3po_shard_partial *out, const TokenRecord *records, hipStream_t s)
 {
     if (T == 0) return hipSuccess;
     const int64_t esz = dt == A3PO_F32 ? 4 : 2;
     const int vec = aligned16(z) && (ld * esz) % 16 == 0;
     if (dt == A3PO_F32)
         hipLaunchKernelGGL((shard_partials_kernel<F32>), dim3(shard_grid(T)), dim3(kShardThreads), 0, s, z, T, Vs, ld,
-                           chosen, v0, out, vec);
+                           chosen, v0, out, records, vec);
     else
         hipLaunchKernelGGL((shard_partials_kernel<Bf16>), dim3(shard_grid(T)), dim3(kShardThreads), 0, s, z, T, Vs, ld,
-                           chosen, v0, out, vec);
+                           chosen, v0, out, records, vec);
     return hipGetLastError();
 }
 
 hipError_t launch_shard_combine(const a3po_shard_partial *parts, int32_t P, int64_t T, const int32_t *chosen, int64_t V,
-                                float *logp, float *lse, float *ent, hipStream_t s)
+                                float *logp, float *lse, float *ent, const TokenRecord *records, hipStream_t s)
 {
     if (T == 0) return hipSuccess;
     hipLaunchKernelGGL(shard_combine_kernel, dim3((unsigned)((T + 255) / 256)), dim3(256), 0, s, parts, P, T, chosen, V,
-                       logp, lse, ent);
+                       logp, lse, ent, records);
     return hipGetLastError();
 }
 
@@ -442,6 +450,18 @@ hipError_t launch_shard_bwd_rows(const LossArgs &a, int64_t v0, const float *log
                            a.T, a.V, a.ld, v0, a.ws_records, logp_theta, lse, a.current_version, a.clip_eps,
                            a.prox_mode, hdr, out, vec);
     return hipGetLastError();
+}
+
+// Rows too long to stay in registers (but 16-byte aligned): the whole vocabulary as one shard - forward
+// partials of the counted rows, merge into log pi / lse / entropy, gradient in bursts.  Three passes over
+// a counted row (read, read, write) instead of two.
+hipError_t launch_loss_rows_three_pass(const LossArgs &a, hipStream_t s)
+{
+    hipError_t e = launch_shard_partials(a.z, a.dt, a.T, a.V, a.ld, a.chosen, 0, a.ws_partial, a.ws_records, s);
+    if (e != hipSuccess) return e;
+    e = launch_shard_combine(a.ws_partial, 1, a.T, a.chosen, a.V, a.logp_out, a.ws_lse, a.ent_out, a.ws_records, s);
+    if (e != hipSuccess) return e;
+    return launch_shard_bwd_rows(a, 0, a.logp_out, a.ws_lse, s);
 }
 
 }  // namespace a3po

@@ -182,11 +182,13 @@ def test_bf16_full_vocabulary_rows_every_element(a3po):
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("V,pad", [(1, 0), (7, 1), (8, 0), (1000, 0), (1001, 7), (4099, 5), (8192, 0), (8200, 8),
-                                   (32000, 0), (32768, 64), (50257, 0), (50257, 7), (65537, 15)])
+                                   (32000, 0), (32768, 64), (50257, 0), (50257, 7), (65537, 15),
+                                   (100000, 0), (170000, 8), (100001, 0)])
 def test_ragged_vocabularies_and_strides(a3po, dtype, V, pad):
     # covers: single partial sweep, exact sweep multiples, ragged tail vectors, padded strides
-    # (padding columns hold a 1e30 sentinel and must be neither read nor written), and strides
-    # whose byte size is not a multiple of 16 (multi-pass kernel).
+    # (padding columns hold a 1e30 sentinel and must be neither read nor written), strides
+    # whose byte size is not a multiple of 16 (element-wise multi-pass kernel), and rows too long for the
+    # registers (100,000 float32 / 170,000 bfloat16: three vectorised passes; 100,001: element-wise).
     w = synth.WORKLOADS["tiny"].scaled(V=V, dtype=dtype, S=4, L=6, len_lo=3, len_hi=6, sigma=3.0,
                                        boost=6.0, boost_prob=0.5, noise_std=0.15, stale_max=6)
     c = make_case(w, ld=V + pad)
