@@ -328,3 +328,63 @@ def test_grpo_advantages(a3po):
         _, ref = oracle.grpo_advantages(R, G, seq_id=sid)
         assert np.array_equal(adv, ref.astype(np.float32))
         assert not adv[:G * 7].any()
+
+
+# ------------------------------------------------------------------------------------------ streams, graphs
+
+def test_two_streams_with_their_own_workspaces(a3po):
+    # the library keeps no global state: calls on different streams with separate outputs and workspaces may overlap
+    c1 = make_case(synth.WORKLOADS["tiny"], T=512)
+    c2 = make_case(synth.WORKLOADS["tiny"].scaled(stream=9, V=8000, S=8, L=64, G=8, len_lo=16, len_hi=64))
+    ref1, ref2 = run_gpu(a3po, c1), run_gpu(a3po, c2)
+    ins = []
+    for c in (c1, c2):
+        ins.append(dict(z=dev_logits(c["z"]), y=torch.from_numpy(c["chosen"]).cuda(), lb=torch.from_numpy(c["lb"]).cuda(),
+                        ver=torch.from_numpy(c["versions"]).cuda(), adv=torch.from_numpy(c["adv"]).cuda(),
+                        m=torch.from_numpy(c["mask"]).cuda(), eps=c["w"].clip_eps))
+    torch.cuda.synchronize()
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    outs = [None, None]
+    for rep in range(3):
+        for i, (st, d) in enumerate(zip(streams, ins)):
+            with torch.cuda.stream(st):
+                outs[i] = a3po.loss_fwd_bwd(d["z"], d["y"], d["lb"], d["ver"], CUR, d["adv"], d["m"], d["eps"])
+    torch.cuda.synchronize()
+    for o, r in zip(outs, (ref1, ref2)):
+        for k in ("dlogits", "logp", "logp_prox", "loss", "stats"):
+            assert torch.equal(o[k].view(torch.uint8), r[k].view(torch.uint8)), k
+
+
+def test_graph_capture_and_replay(a3po):
+    # nothing in the call allocates or synchronises, so it can be recorded into a HIP graph; every replay must
+    # reproduce the eager result, also after the inputs changed in place between replays
+    c = make_case(synth.WORKLOADS["tiny"], T=384)
+    z = dev_logits(c["z"])
+    y, lb, ver = torch.from_numpy(c["chosen"]).cuda(), torch.from_numpy(c["lb"]).cuda(), torch.from_numpy(c["versions"]).cuda()
+    adv, m = torch.from_numpy(c["adv"]).cuda(), torch.from_numpy(c["mask"]).cuda()
+    dz = torch.empty_like(z)
+    ws = torch.empty(a3po.workspace_bytes(c["T"], c["w"].V), dtype=torch.uint8, device="cuda")
+    out = a3po.loss_fwd_bwd(z, y, lb, ver, CUR, adv, m, 0.2, dlogits=dz, workspace=ws, want_entropy=True)   # eager, allocates outputs
+    torch.cuda.synchronize()
+    eager1 = {k: out[k].clone() for k in ("dlogits", "logp", "loss", "stats", "entropy")}
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        a3po.loss_fwd_bwd(z, y, lb, ver, CUR, adv, m, 0.2, dlogits=dz, workspace=ws, out=out, want_entropy=True)
+    for rep in range(3):
+        for k in ("dlogits", "logp", "entropy"):
+            out[k].zero_()
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        for k, v in eager1.items():
+            assert torch.equal(out[k].view(torch.uint8), v.view(torch.uint8)), (rep, k)
+    # new inputs in the same buffers: the replay follows them
+    adv.mul_(-0.5)
+    torch.cuda.synchronize()
+    g.replay()
+    torch.cuda.synchronize()
+    replayed = {k: out[k].clone() for k in eager1}
+    fresh = a3po.loss_fwd_bwd(z, y, lb, ver, CUR, adv, m, 0.2, want_entropy=True)
+    torch.cuda.synchronize()
+    for k in eager1:
+        assert torch.equal(replayed[k].view(torch.uint8), fresh[k].view(torch.uint8)), k
