@@ -553,3 +553,20 @@ def test_given_prox_variant_reduces_to_the_interpolated_one_and_to_coupled_ppo()
     lp = lt + rng.standard_normal(n) * 0.05
     d = oracle.decoupled_clip(lt, lb, lp, A, m, 0.2)
     assert np.allclose(d["iw"] * d["r"], np.exp(lt - lb), rtol=1e-12)
+
+
+# ----------------------------------------------------------------------------- memory and arithmetic sanitizers
+
+def test_oracle_is_clean_under_address_and_undefined_behaviour_sanitizers(tmp_path):
+    """The oracle, built with -fsanitize=address,undefined, runs a driver over every entry point and the edge
+    cases (empty batch, single-entry vocabulary, ids out of range, extreme versions) without a report."""
+    import subprocess
+    here = os.path.dirname(os.path.abspath(__file__))
+    exe = str(tmp_path / "oracle_sanitize")
+    subprocess.check_call(["gcc", "-O1", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=undefined",
+                           "-fno-omit-frame-pointer", "-static-libasan", "-fopenmp", "-o", exe,
+                           os.path.join(here, "oracle_sanitize_driver.c"),
+                           os.path.join(os.path.dirname(here), "oracle", "a3po_oracle.c"), "-lm"])
+    res = subprocess.run([exe], capture_output=True, text=True, timeout=120)
+    assert res.returncode == 0, res.stderr[-2000:]
+    assert res.stdout.strip().endswith("ok") and "runtime error" not in res.stderr and "ERROR" not in res.stderr
