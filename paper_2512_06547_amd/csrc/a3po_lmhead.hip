@@ -136,39 +136,48 @@ __global__ __launch_bounds__(kLmThreads) void lmhead_lse_kernel(const uint16_t *
             run_s[tn] = 0.0f;
         }
 
-        for (int vt = nt; vt < nvt; vt += kLmVocabStrides) {
-            const int64_t v0 = (int64_t)vt * kLmTile;
-            const char *w_tile = reinterpret_cast<const char *>(W + v0 * H);
-            const int v_last = (int)(V - 1 - v0);
-            uint32_t aoff[4];  // rows past the vocabulary are clamped here and masked in the fold
+        // The ring runs through the whole sweep without a break: the refills of a tile's last stages already
+        // bring the next tile's first stages, so a tile's fold epilogue overlaps with their arrival and there
+        // is one prologue and one drain per sweep.  The refill cursor (r_*) names the stage the next refill
+        // loads; past the workgroup's last tile it stays on that tile's last stage (harmless reloads that
+        // keep the number of loads per stage, and with it the s_waitcnt arithmetic, constant).
+        if (nt < nvt) {  // uniform over the workgroup
+            const int last_vt = nt + ((nvt - 1 - nt) / kLmVocabStrides) * kLmVocabStrides;
+            uint32_t aoff_full[4], aoff_last[4];  // weight-row offsets; in the vocabulary's last tile rows past V are clamped
+            const int v_last_global = (int)(V - 1 - (int64_t)(nvt - 1) * kLmTile);
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
-                aoff[j] = (uint32_t)min((4 * j + wave) * 16 + drow, v_last) * (uint32_t)H * 2u + dpiece;
-            f32x16_t acc[4][4];
-#pragma unroll
-            for (int a = 0; a < 4; ++a)
-#pragma unroll
-                for (int b = 0; b < 4; ++b)
-#pragma unroll
-                    for (int e = 0; e < 16; ++e) acc[a][b][e] = 0.0f;
-
-            // the two direct loads number q (weight rows, hidden rows) of K-stage `st` (clamped to the last one)
-            // into ring slot `sl`; LDS destinations and the K offset are wave-uniform (scalar registers)
-            auto load_pair = [&](int st, int sl, int q) {
-                const uint32_t koff = (uint32_t)min(st, nstages - 1) * (uint32_t)kDmaRowBytes;
+            for (int j = 0; j < 4; ++j) {
+                const int r = (4 * j + wave) * 16 + drow;
+                aoff_full[j] = (uint32_t)r * (uint32_t)H * 2u + dpiece;
+                aoff_last[j] = (uint32_t)min(r, v_last_global) * (uint32_t)H * 2u + dpiece;
+            }
+            int r_vt = nt, r_k = 0;
+            const char *r_w = reinterpret_cast<const char *>(W + (int64_t)r_vt * kLmTile * H);
+            auto refill_pair = [&](int sl, int q) {  // direct loads number q (weight rows, hidden rows) of the cursor's stage
+                const uint32_t koff = (uint32_t)r_k * (uint32_t)kDmaRowBytes;
                 char *dst = lds + sl * kDmaStageBytes + wave_s * 1024 + q * 4096;
-                dma16(w_tile + koff + aoff[q], dst);
+                dma16(r_w + koff + (r_vt == nvt - 1 ? aoff_last[q] : aoff_full[q]), dst);
                 dma16(h_tile + koff + boff[q], dst + kDmaOperandBytes);
             };
+            auto advance = [&]() {
+                if (r_k + 1 < nstages) {
+                    ++r_k;
+                } else if (r_vt < last_vt) {
+                    r_k = 0;
+                    r_vt += kLmVocabStrides;
+                    r_w = reinterpret_cast<const char *>(W + (int64_t)r_vt * kLmTile * H);
+                }
+            };
 
-            // prologue: fill the whole ring, then wait for stage 0 and read its first fragments
+            // prologue: fill the whole ring, then wait for the first stage and read its first fragments
 #pragma unroll
             for (int st = 0; st < kDmaStages; ++st) {
 #pragma unroll
-                for (int q = 0; q < 4; ++q) load_pair(st, st, q);
+                for (int q = 0; q < 4; ++q) refill_pair(st, q);
+                advance();
             }
             {
-                constexpr int kAllow = 8 * (kDmaStages - 1);  // everything issued after stage 0
+                constexpr int kAllow = 8 * (kDmaStages - 1);  // everything issued after the first stage
                 __builtin_amdgcn_s_waitcnt(0x0F70 | (kAllow & 15) | ((kAllow >> 4) << 14));
             }
             __syncthreads();
@@ -179,70 +188,84 @@ __global__ __launch_bounds__(kLmThreads) void lmhead_lse_kernel(const uint16_t *
 #pragma unroll
             for (int b = 0; b < 4; ++b)
                 fb[0][b] = *reinterpret_cast<const bf16x8_t *>(lds + fb_base + b * 32 * kDmaRowBytes + fr0);
-
             int sl = 0;  // ring slot of the stage being computed
+
+            for (int vt = nt; vt < nvt; vt += kLmVocabStrides) {
+                const int64_t v0 = (int64_t)vt * kLmTile;
+                f32x16_t acc[4][4];
+#pragma unroll
+                for (int a = 0; a < 4; ++a)
+#pragma unroll
+                    for (int b = 0; b < 4; ++b)
+#pragma unroll
+                        for (int e = 0; e < 16; ++e) acc[a][b][e] = 0.0f;
+
 #pragma unroll 1
-            for (int i = 0; i < nstages; ++i) {
-                const char *cur = lds + sl * kDmaStageBytes;
-                const int nsl = sl + 1 == kDmaStages ? 0 : sl + 1;
-                const char *nxt = lds + nsl * kDmaStageBytes;
-                __builtin_amdgcn_sched_barrier(0);
-                // ---- first k-step; the second k-step's fragments are read meanwhile ----
+                for (int i = 0; i < nstages; ++i) {
+                    const char *cur = lds + sl * kDmaStageBytes;
+                    const int nsl = sl + 1 == kDmaStages ? 0 : sl + 1;
+                    const char *nxt = lds + nsl * kDmaStageBytes;
+                    __builtin_amdgcn_sched_barrier(0);
+                    // ---- first k-step; the second k-step's fragments are read meanwhile ----
 #pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    if (q < 2) {
+                    for (int q = 0; q < 4; ++q) {
+                        if (q < 2) {
 #pragma unroll
-                        for (int a = 2 * q; a < 2 * q + 2; ++a)
-                            fa[1][a] = *reinterpret_cast<const bf16x8_t *>(cur + fa_base + a * 32 * kDmaRowBytes + fr1);
-                    } else {
+                            for (int a = 2 * q; a < 2 * q + 2; ++a)
+                                fa[1][a] = *reinterpret_cast<const bf16x8_t *>(cur + fa_base + a * 32 * kDmaRowBytes + fr1);
+                        } else {
 #pragma unroll
-                        for (int b = 2 * q - 4; b < 2 * q - 2; ++b)
-                            fb[1][b] = *reinterpret_cast<const bf16x8_t *>(cur + fb_base + b * 32 * kDmaRowBytes + fr1);
+                            for (int b = 2 * q - 4; b < 2 * q - 2; ++b)
+                                fb[1][b] = *reinterpret_cast<const bf16x8_t *>(cur + fb_base + b * 32 * kDmaRowBytes + fr1);
+                        }
+#pragma unroll
+                        for (int b = 0; b < 4; ++b)
+                            acc[q][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[0][q], fb[0][b], acc[q][b], 0, 0, 0);
+                        __builtin_amdgcn_sched_barrier(0);
                     }
+                    // ---- the next stage has landed (own loads: the kDmaStages - 2 stages after it may still be
+                    // in flight), this stage is no longer read (own reads, lgkmcnt(0)): meet ----
+                    __builtin_amdgcn_s_waitcnt(0x0070 | (8 * (kDmaStages - 2) & 15) | ((8 * (kDmaStages - 2) >> 4) << 14));
+                    __syncthreads();
+                    __builtin_amdgcn_sched_barrier(0);
+                    // ---- second k-step; the first fragments of the next stage (the next tile's first stage, at
+                    // the end of a tile) are read and the freed slot is refilled meanwhile, two direct loads per
+                    // group of four MFMAs ----
 #pragma unroll
-                    for (int b = 0; b < 4; ++b)
-                        acc[q][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[0][q], fb[0][b], acc[q][b], 0, 0, 0);
+                    for (int q = 0; q < 4; ++q) {
+                        refill_pair(sl, q);
+                        if (q < 2) {
+#pragma unroll
+                            for (int a = 2 * q; a < 2 * q + 2; ++a)
+                                fa[0][a] = *reinterpret_cast<const bf16x8_t *>(nxt + fa_base + a * 32 * kDmaRowBytes + fr0);
+                        } else {
+#pragma unroll
+                            for (int b = 2 * q - 4; b < 2 * q - 2; ++b)
+                                fb[0][b] = *reinterpret_cast<const bf16x8_t *>(nxt + fb_base + b * 32 * kDmaRowBytes + fr0);
+                        }
+#pragma unroll
+                        for (int b = 0; b < 4; ++b)
+                            acc[q][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[1][q], fb[1][b], acc[q][b], 0, 0, 0);
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                    advance();
+                    sl = nsl;
+                }
+
+                // ---- fold the tile into the running (max, sum) of this lane's four token columns, while the
+                // next tile's first stages arrive ----
+                const bool ragged = v0 + kLmTile > V;
+                const int vlim = (int)(V - v0) - wm * 128 - (lane >> 5) * 4;
+#pragma unroll
+                for (int b = 0; b < 4; ++b) {
+                    if (ragged) fold_column<true>(acc, b, vlim, run_m[b], run_s[b]);
+                    else fold_column<false>(acc, b, vlim, run_m[b], run_s[b]);
                     __builtin_amdgcn_sched_barrier(0);
                 }
-                // ---- stage i+1 has landed (own loads: the kDmaStages - 2 stages after it may still be in
-                // flight), stage i is no longer read (own reads, lgkmcnt(0)): meet ----
-                __builtin_amdgcn_s_waitcnt(0x0070 | (8 * (kDmaStages - 2) & 15) | ((8 * (kDmaStages - 2) >> 4) << 14));
-                __syncthreads();
-                __builtin_amdgcn_sched_barrier(0);
-                // ---- second k-step; the first fragments of stage i+1 are read and the freed slot is refilled
-                // meanwhile, two direct loads per group of four MFMAs ----
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    load_pair(i + kDmaStages, sl, q);
-                    if (q < 2) {
-#pragma unroll
-                        for (int a = 2 * q; a < 2 * q + 2; ++a)
-                            fa[0][a] = *reinterpret_cast<const bf16x8_t *>(nxt + fa_base + a * 32 * kDmaRowBytes + fr0);
-                    } else {
-#pragma unroll
-                        for (int b = 2 * q - 4; b < 2 * q - 2; ++b)
-                            fb[0][b] = *reinterpret_cast<const bf16x8_t *>(nxt + fb_base + b * 32 * kDmaRowBytes + fr0);
-                    }
-#pragma unroll
-                    for (int b = 0; b < 4; ++b)
-                        acc[q][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[1][q], fb[1][b], acc[q][b], 0, 0, 0);
-                    __builtin_amdgcn_sched_barrier(0);
-                }
-                sl = nsl;
             }
-            // drain: the clamped loads past the last stage must have landed before the ring is refilled
+            // drain: the reloads past the last stage must have landed before the ring's memory is reused
             __builtin_amdgcn_s_waitcnt(0x0070);  // vmcnt(0) lgkmcnt(0)
             __syncthreads();
-
-            // ---- fold the tile into the running (max, sum) of this lane's four token columns ----
-            const bool ragged = v0 + kLmTile > V;
-            const int vlim = (int)(V - v0) - wm * 128 - (lane >> 5) * 4;
-#pragma unroll
-            for (int b = 0; b < 4; ++b) {
-                if (ragged) fold_column<true>(acc, b, vlim, run_m[b], run_s[b]);
-                else fold_column<false>(acc, b, vlim, run_m[b], run_s[b]);
-                __builtin_amdgcn_sched_barrier(0);
-            }
         }
 
         // ---- end of the sweep: merge the two lane halves, then the two vocabulary halves ----
