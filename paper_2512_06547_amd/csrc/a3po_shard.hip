@@ -4,15 +4,18 @@
 // and each shard then writes its own slice of the gradient from the merged values.  Between the two
 // vocabulary-wide kernels sits whatever exchanges the partials (nothing, on one GPU).
 //
-// Both kernels stream: a shard row is read once per kernel with 16-byte non-temporal accesses,
-// several vectors in flight per thread; nothing is kept between the two kernels except the merged
-// per-token scalars, so a shard row crosses HBM three times (read, read, write).
+// A shard row is read once per vocabulary-wide kernel with 16-byte non-temporal accesses (the forward
+// streams with several vectors in flight per thread, the backward works in bursts); nothing is kept
+// between the two except the merged per-token scalars, so a shard row crosses HBM three times (read,
+// read, write).  The same three kernels also serve the unsharded loss when a row is too long to stay
+// in registers (the whole vocabulary as one shard).
 #include "a3po_common.h"
 #include "a3po_launch.h"
 
 namespace a3po {
 
-// launch shape of the streaming kernels (overridable at build time for tuning sweeps)
+// launch shape of the streaming forward and of the element-wise backward (overridable at build time
+// for tuning sweeps)
 #ifndef A3PO_SHARD_THREADS
 #define A3PO_SHARD_THREADS 256
 #endif
