@@ -241,7 +241,8 @@ __global__ __launch_bounds__(kRowThreads) void loss_rows_kernel(
 
         // ---- backward: dz = g * (onehot(y) - softmax(z)), written over the same lanes ----
         // (with ENT a counted row whose g is 0 comes through here too and stores exact zeros)
-        const float neg_g = -g;
+        // (+0 rather than -0 when there is no gradient: the row is then stored as +0 bit for bit, as the zero path does)
+        const float neg_g = g != 0.0f ? -g : 0.0f;
         const float nlse = -lse * kLog2e;
         float pz = 0.0f;
 #pragma unroll

@@ -59,6 +59,10 @@ def test_entropy_in_the_loss_pass(a3po, dtype, V, pad):
                                        boost_prob=0.5, noise_std=0.2, stale_max=3)
     c = make_case(w, ld=V + pad)
     c["adv"][1] = 0.0                                   # a counted row with zero gradient still has an entropy
+    c["lb"][2] = c["lb"][2] - 1.0                       # ratio e: clipped if the advantage is positive
+    c["adv"][2] = 0.7
+    c["versions"][2] = CUR
+    c["mask"][:3] = 1
     plain = run_gpu(a3po, c)
     out = run_ex(a3po, c, want_entropy=True)
     # asking for the entropy changes nothing else
@@ -68,6 +72,7 @@ def test_entropy_in_the_loss_pass(a3po, dtype, V, pad):
             a, b = a[:, :V], b[:, :V]
         assert torch.equal(a.contiguous().view(torch.uint8), b.contiguous().view(torch.uint8)), k
     ref, st, _ = check_against_oracle(a3po, c, out)
+    assert ref["clipped"][2] == 1 and ref["g"][2] == 0
     H_ref = oracle.entropy(c["z"], V=V) * ref["eff_mask"]
     worst = assert_close_entropy(out["entropy"].cpu().numpy(), H_ref, ref["lse"], "entropy")
     assert (out["entropy"].cpu().numpy()[ref["eff_mask"] == 0] == 0).all()
