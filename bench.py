@@ -351,7 +351,7 @@ def main():
     ap.add_argument("--quiet", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1",
+        print("bench.py: the library runs on one GPU only (no sharding, no collectives); use --gpus 1",
               file=sys.stderr)
         sys.exit(2)
 

@@ -180,7 +180,7 @@ __global__ __launch_bounds__(kLmThreads) void lmhead_lse_kernel(const uint16_t *
                 constexpr int kAllow = 8 * (kDmaStages - 1);  // everything issued after the first stage
                 __builtin_amdgcn_s_waitcnt(0x0F70 | (kAllow & 15) | ((kAllow >> 4) << 14));
             }
-            __syncthreads();
+            __builtin_amdgcn_s_barrier();  // bare, as in the K loop: the rest of the ring stays in flight
             bf16x8_t fa[2][4], fb[2][4];
 #pragma unroll
             for (int a = 0; a < 4; ++a)
@@ -224,9 +224,11 @@ __global__ __launch_bounds__(kLmThreads) void lmhead_lse_kernel(const uint16_t *
                         __builtin_amdgcn_sched_barrier(0);
                     }
                     // ---- the next stage has landed (own loads: the kDmaStages - 2 stages after it may still be
-                    // in flight), this stage is no longer read (own reads, lgkmcnt(0)): meet ----
+                    // in flight), this stage is no longer read (own reads, lgkmcnt(0)): meet.  A bare barrier:
+                    // the fence that __syncthreads() carries makes the compiler drain every direct load it can
+                    // see in flight (vmcnt(0)), which would empty the ring at each stage ----
                     __builtin_amdgcn_s_waitcnt(0x0070 | (8 * (kDmaStages - 2) & 15) | ((8 * (kDmaStages - 2) >> 4) << 14));
-                    __syncthreads();
+                    __builtin_amdgcn_s_barrier();
                     __builtin_amdgcn_sched_barrier(0);
                     // ---- second k-step; the first fragments of the next stage (the next tile's first stage, at
                     // the end of a tile) are read and the freed slot is refilled meanwhile, two direct loads per
