@@ -287,7 +287,7 @@ int a3po_shard_loss_bwd(const void *logits_shard, a3po_dtype dt, int64_t T, int6
  * The [T, V] logits are never written to memory: each 256 x 256 tile is folded into a running
  * (max, sum) per token as it leaves the matrix cores.
  * hidden [T, H] and weight [V, H]: row-major, contiguous, bfloat16, 16-byte aligned; H must be a
- * positive multiple of 64.  chosen [T] int32; an id outside [0,V) gives logp 0 (lse still written).
+ * positive multiple of 64, at most 2^20 (A3PO_E_SIZE otherwise).  chosen [T] int32; an id outside [0,V) gives logp 0 (lse still written).
  * logp_out [T] float, lse_out [T] float (nullable).
  * workspace: a3po_workspace_bytes(A3PO_WS_FUSED_LMHEAD, T, V, H) bytes, 256-byte aligned.
  * The first call on a process raises the kernel's dynamic LDS limit (one hipFuncSetAttribute).
@@ -307,7 +307,7 @@ int a3po_fused_lmhead_logprob(const void *hidden, const void *weight, int64_t T,
  * GEMMs issued to rocBLAS (bfloat16 inputs, fp32 accumulation; dweight is accumulated over chunks
  * in fp32 and rounded to bfloat16 once); everything between them is this library's kernels.
  * hidden, dhidden [T, H]; weight, dweight [V, H]: row-major, contiguous, bfloat16, 16-byte
- * aligned; H % 8 == 0 and V % 8 == 0.  Per-token arguments and outputs as in a3po_loss_fwd_bwd.
+ * aligned; H % 8 == 0, H <= 2^20 and V % 8 == 0.  Per-token arguments and outputs as in a3po_loss_fwd_bwd.
  * workspace: a3po_workspace_bytes(A3PO_WS_FUSED_LMHEAD_LOSS, T, V, H) bytes, 256-byte aligned.
  * Unlike the other entry points this one keeps one process-wide rocBLAS handle, created on first
  * use (rocBLAS allocates its own scratch then); calls that share it must not overlap in time.

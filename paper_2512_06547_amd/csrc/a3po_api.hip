@@ -102,7 +102,8 @@ int a3po_fused_lmhead_logprob(const void *hidden, const void *weight, int64_t T,
                               const int32_t *chosen, float *logp_out, float *lse_out, void *workspace,
                               size_t workspace_bytes, void *stream)
 {
-    if (T < 0 || V <= 0 || H <= 0 || H % 64 != 0 || V > (int64_t)0x7FFFFFFF) return A3PO_E_SIZE;
+    // H <= 2^20 keeps the kernel's 32-bit byte offsets inside a 256-row tile (255 * 2 H + 64) far below 2^32
+    if (T < 0 || V <= 0 || H <= 0 || H % 64 != 0 || H > (1 << 20) || V > (int64_t)0x7FFFFFFF) return A3PO_E_SIZE;
     if (T == 0) return A3PO_OK;
     if (!hidden || !weight || !chosen || !logp_out) return A3PO_E_NULL;
     if (!aligned(hidden, 16) || !aligned(weight, 16)) return A3PO_E_ALIGN;

@@ -87,7 +87,8 @@ extern "C" int a3po_fused_lmhead_loss_fwd_bwd(const void *hidden, const void *we
                                               void *stream)
 {
     auto aligned = [](const void *p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; };
-    if (T < 0 || V <= 0 || H <= 0 || H % 8 != 0 || V % 8 != 0 || V > (int64_t)0x7FFFFFFF) return A3PO_E_SIZE;
+    if (T < 0 || V <= 0 || H <= 0 || H % 8 != 0 || H > (1 << 20) || V % 8 != 0 || V > (int64_t)0x7FFFFFFF)
+        return A3PO_E_SIZE;
     if (!(clip_eps >= 0.0f && clip_eps < 1.0f) || denom != denom) return A3PO_E_VALUE;
     if (!loss_out || !weight || !dweight) return A3PO_E_NULL;
     if (T > 0 && (!hidden || !dhidden || !chosen || !logp_behav || !versions || !advantages || !loss_mask || !logp_out))

@@ -93,6 +93,39 @@ def test_host_validation_rejects_bad_arguments_before_launch(lib):
     assert call(a1=2) == -3 and call(a4=32) == -2
 
 
+def test_lmhead_entry_points_validate_before_launch(lib):
+    fake, ws = ctypes.c_void_p(0x1000), ctypes.c_void_p(0x10000)
+    lp = lib.a3po_fused_lmhead_logprob
+    # (hidden, weight, T, H, V, chosen, logp, lse, workspace, bytes, stream)
+    assert lp(fake, fake, 0, 64, 8, None, None, None, None, 0, None) == 0                 # T == 0 is success
+    assert lp(fake, fake, 4, 96, 8, fake, fake, None, ws, 1 << 20, None) == -2            # H not a multiple of 64
+    assert lp(fake, fake, 4, (1 << 20) + 64, 8, fake, fake, None, ws, 1 << 20, None) == -2    # H above the limit
+    assert lp(fake, fake, 4, 64, 0, fake, fake, None, ws, 1 << 20, None) == -2
+    assert lp(fake, fake, 4, 64, 1 << 31, fake, fake, None, ws, 1 << 20, None) == -2      # ids are int32
+    assert lp(None, fake, 4, 64, 8, fake, fake, None, ws, 1 << 20, None) == -1
+    assert lp(fake, fake, 4, 64, 8, fake, None, None, ws, 1 << 20, None) == -1
+    assert lp(ctypes.c_void_p(0x1008), fake, 4, 64, 8, fake, fake, None, ws, 1 << 20, None) == -4
+    assert lp(fake, fake, 4, 64, 8, fake, fake, None, ws, 16, None) == -5
+    assert lp(fake, fake, 4, 64, 8, fake, fake, None, ctypes.c_void_p(0x10010), 1 << 20, None) == -4
+    lf = lib.a3po_fused_lmhead_loss_fwd_bwd
+    # (hidden, weight, T, H, V, chosen, logp_behav, versions, cur, adv, mask, eps, denom, dh, dW, logp, prox, loss,
+    #  stats, workspace, bytes, stream)
+    base = [fake, fake, 4, 64, 8, fake, fake, fake, 3, fake, fake, 0.2, 0.0, fake, fake, fake, None, fake, None,
+            ws, 16, None]
+
+    def call(**kw):
+        a = list(base)
+        for k, v in kw.items():
+            a[int(k[1:])] = v
+        return lf(*a)
+
+    assert call() == -5                                                                   # workspace too small
+    assert call(a3=12) == -2 and call(a4=12) == -2 and call(a3=(1 << 20) + 8) == -2        # H % 8, V % 8, H limit
+    assert call(a11=1.0) == -7 and call(a12=float("nan")) == -7
+    assert call(a17=None) == -1 and call(a1=None) == -1 and call(a14=None) == -1 and call(a5=None) == -1
+    assert call(a13=ctypes.c_void_p(0x1008)) == -4
+
+
 def test_ex_entry_point_validates_its_options_before_launch(lib):
     from paper_2512_06547_amd.binding import LossOptions
     fake = ctypes.c_void_p(0x1000)
