@@ -297,3 +297,30 @@ def plan_microbatches(seq_len, n_minibatches, max_tokens):
             tokens += n
     first.append(S)
     return first, owner
+
+
+def histogram(values, edges, select=None):
+    """Counts of a per-token quantity over bins with explicit edges (the distribution behind the
+    importance-weight extrema and clipped-token counts of Section 4.2.2).
+
+    ``edges`` is a non-decreasing array of nbins + 1 numbers.  Returns int64[nbins + 3]:
+    [0] selected values below edges[0]; [1 + k] values with edges[k] <= v < edges[k+1];
+    [nbins + 1] values >= edges[nbins]; [nbins + 2] NaNs.  ``select`` (optional) keeps token t only
+    when select[t] != 0.  Values and edges are compared as given (float32 compares are exact in any
+    wider type), so the counts are integers with no rounding question.
+    """
+    v = np.asarray(values, dtype=np.float64).ravel()
+    e = np.asarray(edges, dtype=np.float64).ravel()
+    if select is not None:
+        v = v[np.asarray(select).ravel() != 0]
+    nbins = len(e) - 1
+    counts = np.zeros(nbins + 3, dtype=np.int64)
+    for x in v:
+        if x != x:
+            counts[nbins + 2] += 1
+            continue
+        k = 0                              # number of edges that are <= x
+        while k <= nbins and e[k] <= x:
+            k += 1
+        counts[k] += 1
+    return counts

@@ -555,6 +555,45 @@ def test_given_prox_variant_reduces_to_the_interpolated_one_and_to_coupled_ppo()
     assert np.allclose(d["iw"] * d["r"], np.exp(lt - lb), rtol=1e-12)
 
 
+# ----------------------------------------------------------------------------- histograms (Section 4.2.2 statistics)
+
+def test_histogram_hand_example_numpy_and_invariants():
+    nan = float("nan")
+    # by hand: below 1.0 -> {0.5, -3}; [1, 1.5) -> {1.0, 1.0}; [1.5, 2) -> {1.7}; >= 2 -> {2.0, 5}; one NaN
+    v = np.array([0.5, 1.0, 1.0, 1.7, 2.0, -3.0, nan, 5.0], dtype=np.float32)
+    assert oracle.histogram(v, [1.0, 1.5, 2.0]).tolist() == [2, 2, 1, 2, 1]
+    # a selection: tokens 1, 3, 4, 6 only
+    sel = np.array([0, 1, 0, 1, 1, 0, 1, 0], dtype=np.uint8)
+    assert oracle.histogram(v, [1.0, 1.5, 2.0], sel).tolist() == [0, 1, 1, 1, 1]
+    # repeated edges make empty bins; a value equal to a repeated edge belongs to the bin after it
+    assert oracle.histogram([1.0, 2.0, 2.0, 3.0], [2.0, 2.0, 2.0, 3.0]).tolist() == [1, 0, 0, 2, 1, 0]
+    # an independent routine: numpy.histogram agrees on every half-open bin (its last bin is closed, so the
+    # edge value itself is kept out of the data), and everything is counted exactly once
+    x = (rng.standard_normal(5000) * 0.3).astype(np.float32)
+    w = np.exp(x).astype(np.float32)
+    edges = np.geomspace(0.25, 4.0, 33).astype(np.float32)
+    w = w[w != edges[-1]]
+    h = oracle.histogram(w, edges)
+    ref, _ = np.histogram(w.astype(np.float64), bins=edges.astype(np.float64))
+    assert np.array_equal(h[1:-2], ref)
+    assert h[0] == (w < edges[0]).sum() and h[-2] == (w >= edges[-1]).sum() and h[-1] == 0
+    assert h.sum() == len(w)
+    sel = (rng.random(len(w)) < 0.4).astype(np.uint8)
+    assert oracle.histogram(w, edges, sel).sum() == sel.sum()
+    assert np.array_equal(oracle.histogram(w, edges, sel) + oracle.histogram(w, edges, 1 - sel), h)
+    # importance weights of the surrogate: extrema reported by the statistics bracket the occupied bins
+    lt, lb = _random_logps(400)
+    m = (rng.random(400) < 0.7).astype(np.uint8)
+    ver = (30 - rng.integers(0, 9, 400)).astype(np.int32)
+    a = oracle.surrogate(lt, lb, ver, 30, rng.standard_normal(400), m, 0.2)
+    hw = oracle.histogram(a["iw"], edges, m)
+    occupied = np.nonzero(hw[1:-2])[0]
+    assert hw[0] == 0 and hw[-2] == 0
+    assert edges[occupied[0]] <= a["stats"]["iw_min"] < edges[occupied[0] + 1]
+    assert edges[occupied[-1]] <= a["stats"]["iw_max"] < edges[occupied[-1] + 1]
+    assert hw.sum() == a["stats"]["n_tokens"]
+
+
 # ----------------------------------------------------------------------------- memory and arithmetic sanitizers
 
 def test_oracle_is_clean_under_address_and_undefined_behaviour_sanitizers(tmp_path):
