@@ -202,6 +202,25 @@ int a3po_loss_fwd_bwd_ex(const void *logits, a3po_dtype dt, int64_t T, int64_t V
                          void *workspace, size_t workspace_bytes, void *stream,
                          const a3po_loss_options *opt);
 
+/*
+ * Histogram of a per-token quantity, for the distributions behind the stability statistics of
+ * Section 4.2.2 (Fig. 5 plots only the extrema of the importance weight, Fig. 6 only the number of
+ * clipped tokens): e.g. values = iw_out of a3po_loss_fwd_bwd_ex with select = loss_mask (all counted
+ * tokens) or select = clipped_out (the clipped ones), or values = entropy_out.
+ *   values [T] float, device.  select [T] uint8, device, nullable: token t is counted iff
+ *   select[t] != 0 (NULL: every token).  edges [nbins + 1] float, DEVICE, non-decreasing
+ *   (not checked; with unsorted edges every value still lands in some slot).
+ *   counts_out [nbins + 3] int64, device: [0] values below edges[0]; [1 + k] values with
+ *   edges[k] <= v < edges[k+1]; [nbins + 1] values >= edges[nbins]; [nbins + 2] NaNs.
+ *   accumulate = 0 overwrites counts_out, 1 adds to it (micro-batches of one update).
+ * Values are compared with the edges as stored, so the counts are exact integers.
+ * 1 <= nbins <= A3PO_HIST_MAX_BINS, else A3PO_E_SIZE; accumulate not 0 / 1: A3PO_E_VALUE.
+ * T == 0 is legal (counts_out is cleared unless accumulating).
+ */
+#define A3PO_HIST_MAX_BINS 1024
+int a3po_histogram(const float *values, const uint8_t *select, int64_t T, const float *edges, int32_t nbins,
+                   int32_t accumulate, int64_t *counts_out, void *stream);
+
 /* ---- mini-batches (Section 4.1: a training step makes 4 gradient updates, one per mini-batch, and a
  * forward/backward pass holds at most 10,240 tokens) -------------------------------------------------
  *

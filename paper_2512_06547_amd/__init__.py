@@ -16,6 +16,7 @@ from .binding import (  # noqa: F401
     fused_lmhead_loss_fwd_bwd,
     STATS_DTYPE,
     grpo_advantages,
+    histogram,
     lib,
     lib_path,
     loss_fwd_bwd,

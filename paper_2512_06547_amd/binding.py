@@ -51,6 +51,7 @@ _SIGNATURES = {
     "a3po_loss_fwd_bwd_ex": (ctypes.c_int, [_P, ctypes.c_int, _I64, _I64, _I64, _P, _P, _P, _I32, _P, _P, _F32,
                                             _F32, _P, _P, _P, _P, _P, _P, _SZ, _P, ctypes.POINTER(LossOptions)]),
     "a3po_count_tokens": (ctypes.c_int, [_P, _P, _I64, _I64, _P, _P, _P]),
+    "a3po_histogram": (ctypes.c_int, [_P, _P, _I64, _P, _I32, _I32, _P, _P]),
     "a3po_plan_microbatches": (ctypes.c_int, [_P, _I64, _I32, _I64, _P, _P, _I64, _P]),
     "a3po_shard_partials": (ctypes.c_int, [_P, ctypes.c_int, _I64, _I64, _I64, _P, _I64, _P, _P]),
     "a3po_shard_combine": (ctypes.c_int, [_P, _I32, _I64, _P, _I64, _P, _P, _P, _P]),
@@ -256,6 +257,26 @@ def count_tokens(chosen, loss_mask, V: int, want_count=False):
     _check(lib().a3po_count_tokens(_ptr(chosen), _ptr(loss_mask), T, int(V), _ptr(denom), _ptr(cnt), _stream()),
            "a3po_count_tokens")
     return (denom, cnt) if want_count else denom
+
+
+def histogram(values, edges, select=None, accumulate=False, out=None):
+    """a3po_histogram -> counts int64[nbins + 3] on the device (below, bins..., at-or-above, NaN)."""
+    torch = _torch()
+    T = values.numel()
+    _vec(values, torch.float32, T, "values")
+    if select is not None:
+        _vec(select, torch.uint8, T, "select")
+    nbins = edges.numel() - 1
+    _vec(edges, torch.float32, nbins + 1, "edges")
+    if out is None:
+        if accumulate:
+            raise ValueError("accumulate needs the counts of the earlier calls in `out`")
+        out = torch.empty(max(nbins, 0) + 3, dtype=torch.int64, device=values.device)
+    else:
+        _vec(out, torch.int64, nbins + 3, "out")
+    _check(lib().a3po_histogram(_ptr(values), _ptr(select), T, _ptr(edges), nbins, int(bool(accumulate)), _ptr(out),
+                                _stream()), "a3po_histogram")
+    return out
 
 
 def plan_microbatches(seq_len, n_minibatches: int, max_tokens: int, capacity=None):

@@ -196,6 +196,17 @@ int a3po_count_tokens(const int32_t *chosen, const uint8_t *loss_mask, int64_t T
     return e == hipSuccess ? A3PO_OK : A3PO_E_LAUNCH;
 }
 
+int a3po_histogram(const float *values, const uint8_t *select, int64_t T, const float *edges, int32_t nbins,
+                   int32_t accumulate, int64_t *counts_out, void *stream)
+{
+    if (T < 0 || nbins < 1 || nbins > A3PO_HIST_MAX_BINS) return A3PO_E_SIZE;
+    if (accumulate != 0 && accumulate != 1) return A3PO_E_VALUE;
+    if (!edges || !counts_out || (T > 0 && !values)) return A3PO_E_NULL;
+    const hipError_t e = launch_histogram(values, select, T, edges, nbins, accumulate == 1, counts_out,
+                                          static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? A3PO_OK : A3PO_E_LAUNCH;
+}
+
 int a3po_plan_microbatches(const int64_t *seq_len, int64_t S, int32_t n_minibatches, int64_t max_tokens,
                            int64_t *micro_first_seq, int32_t *micro_minibatch, int64_t capacity, int64_t *n_micro_out)
 {

@@ -85,6 +85,8 @@ hipError_t launch_loss_rows(const LossArgs &a, hipStream_t s);
 hipError_t launch_loss_finish(const LossArgs &a, hipStream_t s);
 hipError_t launch_count_tokens(const int32_t *chosen, const uint8_t *mask, int64_t T, int64_t V, float *denom_out,
                                int64_t *count_out, hipStream_t s);
+hipError_t launch_histogram(const float *values, const uint8_t *select, int64_t T, const float *edges, int nbins,
+                            bool accumulate, int64_t *counts, hipStream_t s);
 hipError_t launch_reset_row_queue(void *ws_header, hipStream_t s);  // before re-running the row kernel on one header
 
 hipError_t launch_token_logprobs(const void *z, int dt, int64_t T, int64_t V, int64_t ld, const int32_t *chosen,

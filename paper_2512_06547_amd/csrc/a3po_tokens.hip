@@ -1,5 +1,6 @@
 // Per-token kernels (O(T) work): mask count before the row kernel, fixed-order loss and
-// statistics reduction after it, the stand-alone proximal interpolation, GRPO advantages.
+// statistics reduction after it, the stand-alone proximal interpolation, GRPO advantages,
+// histograms of per-token quantities.
 #include "a3po_common.h"
 #include "a3po_launch.h"
 
@@ -170,6 +171,61 @@ __global__ __launch_bounds__(kTokThreads) void count_tokens_kernel(const int32_t
         *denom_out = (float)c;
         if (count_out) *count_out = c;
     }
+}
+
+// Histogram over explicit edges: slot k of a value = number of edges <= it (0: below the first edge,
+// nbins + 1: at or above the last), slot nbins + 2 for NaN.  Edges and per-workgroup counts live in LDS;
+// integer atomics only, so the result does not depend on the order of arrival.
+constexpr int kHistThreads = 256;
+constexpr int kHistMaxBlocks = 512;
+
+__global__ void histogram_clear_kernel(int64_t *counts, int n)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) counts[i] = 0;
+}
+
+__global__ __launch_bounds__(kHistThreads) void histogram_kernel(const float *__restrict__ values,
+                                                                 const uint8_t *__restrict__ select, int64_t T,
+                                                                 const float *__restrict__ edges, int nbins,
+                                                                 unsigned long long *__restrict__ counts)
+{
+    __shared__ float s_edge[A3PO_HIST_MAX_BINS + 1];
+    __shared__ unsigned long long s_cnt[A3PO_HIST_MAX_BINS + 3];
+    for (int i = threadIdx.x; i <= nbins; i += kHistThreads) s_edge[i] = edges[i];
+    for (int i = threadIdx.x; i < nbins + 3; i += kHistThreads) s_cnt[i] = 0ull;
+    __syncthreads();
+    const int64_t stride = (int64_t)gridDim.x * kHistThreads;
+    for (int64_t t = (int64_t)blockIdx.x * kHistThreads + threadIdx.x; t < T; t += stride) {
+        if (select && select[t] == 0) continue;
+        const float v = values[t];
+        int lo = 0, hi = nbins + 1;  // lo ends as the number of edges <= v
+        while (lo < hi) {
+            const int mid = (lo + hi) >> 1;
+            if (s_edge[mid] <= v) lo = mid + 1;
+            else hi = mid;
+        }
+        atomicAdd(&s_cnt[v != v ? nbins + 2 : lo], 1ull);
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < nbins + 3; i += kHistThreads)
+        if (s_cnt[i]) atomicAdd(&counts[i], s_cnt[i]);
+}
+
+hipError_t launch_histogram(const float *values, const uint8_t *select, int64_t T, const float *edges, int nbins,
+                            bool accumulate, int64_t *counts, hipStream_t s)
+{
+    if (!accumulate) {
+        hipLaunchKernelGGL(histogram_clear_kernel, dim3((nbins + 3 + 255) / 256), dim3(256), 0, s, counts, nbins + 3);
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    if (T == 0) return hipSuccess;
+    const int64_t want = (T + kHistThreads * 8 - 1) / (kHistThreads * 8);
+    const unsigned grid = (unsigned)(want < kHistMaxBlocks ? want : kHistMaxBlocks);
+    hipLaunchKernelGGL(histogram_kernel, dim3(grid), dim3(kHistThreads), 0, s, values, select, T, edges, nbins,
+                       reinterpret_cast<unsigned long long *>(counts));
+    return hipGetLastError();
 }
 
 // Eq. 3 with the coefficient of Eq. 4, element-wise.

@@ -126,6 +126,16 @@ def test_lmhead_entry_points_validate_before_launch(lib):
     assert call(a13=ctypes.c_void_p(0x1008)) == -4
 
 
+def test_histogram_validates_before_launch(lib):
+    fake = ctypes.c_void_p(0x1000)
+    hg = lib.a3po_histogram      # (values, select, T, edges, nbins, accumulate, counts_out, stream)
+    assert hg(fake, None, -1, fake, 8, 0, fake, None) == -2
+    assert hg(fake, None, 4, fake, 0, 0, fake, None) == -2 and hg(fake, None, 4, fake, 1025, 0, fake, None) == -2
+    assert hg(fake, None, 4, fake, 8, 2, fake, None) == -7
+    assert hg(None, None, 4, fake, 8, 0, fake, None) == -1 and hg(fake, None, 4, None, 8, 0, fake, None) == -1
+    assert hg(fake, None, 4, fake, 8, 0, None, None) == -1
+
+
 def test_ex_entry_point_validates_its_options_before_launch(lib):
     from paper_2512_06547_amd.binding import LossOptions
     fake = ctypes.c_void_p(0x1000)
