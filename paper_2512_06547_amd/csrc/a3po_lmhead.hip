@@ -37,29 +37,36 @@ typedef uint32_t lm_u32x4_t __attribute__((ext_vector_type(4)));
 // the lane's running (max, sum).  Row offset of acc[a][b][4 i + j] inside the lane's slice is
 // a 32 + 8 i + j; offsets >= vlim lie past the vocabulary (only in the last, ragged tile).
 // The accumulators are only read, never modified.
+// The scheduling fences after each MFMA tile keep the copies of the accumulators short-lived: without
+// them the register allocator spills across the K loop and a reload there waits for every direct load
+// in flight.
 template <bool RAGGED>
 __device__ __forceinline__ void fold_column(const f32x16_t (&acc)[4][4], int b, int vlim, float &run_m, float &run_s)
 {
     float mx = -INFINITY;
 #pragma unroll
-    for (int a = 0; a < 4; ++a)
+    for (int a = 0; a < 4; ++a) {
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
             float v = acc[a][b][e];
             if (RAGGED && a * 32 + (e >> 2) * 8 + (e & 3) >= vlim) v = -INFINITY;
             mx = fmaxf(mx, v);
         }
+        __builtin_amdgcn_sched_barrier(0);
+    }
     const float m_new = fmaxf(run_m, mx);
     const float nm = -m_new * kLog2e;
     float s = run_s * exp2_hw((run_m - m_new) * kLog2e);
 #pragma unroll
-    for (int a = 0; a < 4; ++a)
+    for (int a = 0; a < 4; ++a) {
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
             float v = acc[a][b][e];
             if (RAGGED && a * 32 + (e >> 2) * 8 + (e & 3) >= vlim) v = -INFINITY;
             s += exp2_hw(fmaf(v, kLog2e, nm));
         }
+        __builtin_amdgcn_sched_barrier(0);
+    }
     run_m = m_new;
     run_s = s;
 }
@@ -75,11 +82,13 @@ __device__ __forceinline__ void fold_column(const f32x16_t (&acc)[4][4], int b, 
 // at its physical position), so a fragment read - 16 consecutive rows, same logical piece - touches
 // 16 distinct bank groups.
 //
-// Schedule of stage i (two k-steps of 16 MFMAs): the first k-step runs while the second k-step's
-// fragments are read; then the wavefront waits for its own loads of stage i+1 and for its reads of
-// stage i, all wavefronts meet at one barrier (stage i+1 is now visible, the slot of stage i is
-// free), the loads of stage i + kDmaStages are issued into that slot, and the second k-step runs
-// while the first fragments of stage i+1 are read.
+// Schedule of stage i (two k-steps of 16 MFMAs).  A wavefront holds the fragments of a whole stage
+// in registers, twice (this stage and the next).  At the top of stage i it waits for its own loads
+// of stage i+1 and for its own fragment reads of stage i, and all wavefronts meet at one barrier:
+// stage i+1 is now visible and the slot of stage i is free (everybody has it in registers).  During
+// the 32 MFMAs of stage i the 16 fragments of stage i+1 are read and the 8 direct loads of stage
+// i + kDmaStages are issued into the freed slot, two reads and one load per group of four MFMAs, so
+// both streams are spread evenly over the stage.
 constexpr int kDmaStages = 4;
 constexpr int kDmaK = 32;                                  // K elements per stage
 constexpr int kDmaRowBytes = kDmaK * 2;                    // 64
@@ -94,6 +103,11 @@ __device__ __forceinline__ void dma16(const char *g, char *l)
     __builtin_amdgcn_global_load_lds(reinterpret_cast<const lm_u32x4_t *>(g), (lds_ptr_t)l, 16, 0, 0);
 }
 
+// QUAD: the hidden size is a multiple of kDmaStages stages.  Then every tile starts in ring slot 0,
+// the K loop is unrolled by the ring depth (all LDS addresses are constants) and the refill cursor
+// moves once per kDmaStages stages.  Otherwise the loop is unrolled by two (the fragment buffers
+// alternate; the number of stages is even) and slot and cursor are tracked per stage.
+template <bool QUAD>
 __global__ __launch_bounds__(kLmThreads) void lmhead_lse_kernel(const uint16_t *__restrict__ W,
                                                                     const uint16_t *__restrict__ h, int64_t T,
                                                                     int64_t H, int64_t V, float2 *__restrict__ partial)
@@ -114,8 +128,8 @@ __global__ __launch_bounds__(kLmThreads) void lmhead_lse_kernel(const uint16_t *
     const uint32_t dpiece = (uint32_t)((lane & 3) ^ ((lane >> 4) & 3)) * 16u;
     // fragment reads: row lane & 31 of a 32-row MFMA tile, k half lane >> 5 of k-step s: logical piece 2 s + (lane >> 5),
     // physical piece that ^ ((row >> 2) & 3) = that ^ ((lane >> 2) & 3)
-    const uint32_t fr0 = (uint32_t)(lane & 31) * kDmaRowBytes + (uint32_t)(((lane >> 5) ^ ((lane >> 2) & 3)) * 16);
-    const uint32_t fr1 = (uint32_t)(lane & 31) * kDmaRowBytes + (uint32_t)(((2 + (lane >> 5)) ^ ((lane >> 2) & 3)) * 16);
+    const uint32_t fr[2] = {(uint32_t)(lane & 31) * kDmaRowBytes + (uint32_t)(((lane >> 5) ^ ((lane >> 2) & 3)) * 16),
+                            (uint32_t)(lane & 31) * kDmaRowBytes + (uint32_t)(((2 + (lane >> 5)) ^ ((lane >> 2) & 3)) * 16)};
     const uint32_t fa_base = (uint32_t)(wm * 128) * kDmaRowBytes;
     const uint32_t fb_base = kDmaOperandBytes + (uint32_t)(wn * 128) * kDmaRowBytes;
 
@@ -139,56 +153,70 @@ __global__ __launch_bounds__(kLmThreads) void lmhead_lse_kernel(const uint16_t *
         // The ring runs through the whole sweep without a break: the refills of a tile's last stages already
         // bring the next tile's first stages, so a tile's fold epilogue overlaps with their arrival and there
         // is one prologue and one drain per sweep.  The refill cursor (r_*) names the stage the next refill
-        // loads; past the workgroup's last tile it stays on that tile's last stage (harmless reloads that
-        // keep the number of loads per stage, and with it the s_waitcnt arithmetic, constant).
+        // loads (QUAD: the first of a group of kDmaStages stages); past the workgroup's last tile it stays on
+        // that tile's last stage (group): reloads of bytes that are already there, which keep the number of
+        // loads per stage, and with it the s_waitcnt arithmetic, constant.
         if (nt < nvt) {  // uniform over the workgroup
             const int last_vt = nt + ((nvt - 1 - nt) / kLmVocabStrides) * kLmVocabStrides;
-            uint32_t aoff_full[4], aoff_last[4];  // weight-row offsets; in the vocabulary's last tile rows past V are clamped
+            // weight-row offsets; in the vocabulary's last tile rows past V are clamped
+            uint32_t aoff_last[4], aoff[4];
             const int v_last_global = (int)(V - 1 - (int64_t)(nvt - 1) * kLmTile);
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 const int r = (4 * j + wave) * 16 + drow;
-                aoff_full[j] = (uint32_t)r * (uint32_t)H * 2u + dpiece;
                 aoff_last[j] = (uint32_t)min(r, v_last_global) * (uint32_t)H * 2u + dpiece;
+                aoff[j] = nt == nvt - 1 ? aoff_last[j] : (uint32_t)r * (uint32_t)H * 2u + dpiece;
             }
             int r_vt = nt, r_k = 0;
             const char *r_w = reinterpret_cast<const char *>(W + (int64_t)r_vt * kLmTile * H);
-            auto refill_pair = [&](int sl, int q) {  // direct loads number q (weight rows, hidden rows) of the cursor's stage
-                const uint32_t koff = (uint32_t)r_k * (uint32_t)kDmaRowBytes;
+            // direct load number q of one operand (0: weight rows, 1: hidden rows) of stage r_k + u into ring slot sl
+            auto refill = [&](int sl, int q, int u, int operand) {
+                const uint32_t koff = (uint32_t)(r_k + u) * (uint32_t)kDmaRowBytes;
                 char *dst = lds + sl * kDmaStageBytes + wave_s * 1024 + q * 4096;
-                dma16(r_w + koff + (r_vt == nvt - 1 ? aoff_last[q] : aoff_full[q]), dst);
-                dma16(h_tile + koff + boff[q], dst + kDmaOperandBytes);
+                if (operand == 0) dma16(r_w + koff + aoff[q], dst);
+                else dma16(h_tile + koff + boff[q], dst + kDmaOperandBytes);
             };
-            auto advance = [&]() {
-                if (r_k + 1 < nstages) {
-                    ++r_k;
+            auto advance = [&](int step) {
+                if (r_k + step < nstages) {
+                    r_k += step;
                 } else if (r_vt < last_vt) {
                     r_k = 0;
                     r_vt += kLmVocabStrides;
                     r_w = reinterpret_cast<const char *>(W + (int64_t)r_vt * kLmTile * H);
+                    if (r_vt == nvt - 1) {
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) aoff[j] = aoff_last[j];
+                    }
                 }
             };
 
-            // prologue: fill the whole ring, then wait for the first stage and read its first fragments
+            // prologue: fill the whole ring, then wait for the first stage and read its fragments
 #pragma unroll
             for (int st = 0; st < kDmaStages; ++st) {
 #pragma unroll
-                for (int q = 0; q < 4; ++q) refill_pair(st, q);
-                advance();
+                for (int q = 0; q < 4; ++q) {
+                    refill(st, q, QUAD ? st : 0, 0);
+                    refill(st, q, QUAD ? st : 0, 1);
+                }
+                if (!QUAD) advance(1);
             }
+            if (QUAD) advance(kDmaStages);
             {
                 constexpr int kAllow = 8 * (kDmaStages - 1);  // everything issued after the first stage
                 __builtin_amdgcn_s_waitcnt(0x0F70 | (kAllow & 15) | ((kAllow >> 4) << 14));
             }
             __builtin_amdgcn_s_barrier();  // bare, as in the K loop: the rest of the ring stays in flight
-            bf16x8_t fa[2][4], fb[2][4];
+            bf16x8_t fa[2][2][4], fb[2][2][4];  // [buffer][k-step][MFMA tile]
 #pragma unroll
-            for (int a = 0; a < 4; ++a)
-                fa[0][a] = *reinterpret_cast<const bf16x8_t *>(lds + fa_base + a * 32 * kDmaRowBytes + fr0);
+            for (int ks = 0; ks < 2; ++ks) {
 #pragma unroll
-            for (int b = 0; b < 4; ++b)
-                fb[0][b] = *reinterpret_cast<const bf16x8_t *>(lds + fb_base + b * 32 * kDmaRowBytes + fr0);
-            int sl = 0;  // ring slot of the stage being computed
+                for (int a = 0; a < 4; ++a)
+                    fa[0][ks][a] = *reinterpret_cast<const bf16x8_t *>(lds + fa_base + a * 32 * kDmaRowBytes + fr[ks]);
+#pragma unroll
+                for (int b = 0; b < 4; ++b)
+                    fb[0][ks][b] = *reinterpret_cast<const bf16x8_t *>(lds + fb_base + b * 32 * kDmaRowBytes + fr[ks]);
+            }
+            int sl_dyn = 0;  // ring slot of the stage being computed (tracked only when !QUAD)
 
             for (int vt = nt; vt < nvt; vt += kLmVocabStrides) {
                 const int64_t v0 = (int64_t)vt * kLmTile;
@@ -200,58 +228,61 @@ __global__ __launch_bounds__(kLmThreads) void lmhead_lse_kernel(const uint16_t *
 #pragma unroll
                         for (int e = 0; e < 16; ++e) acc[a][b][e] = 0.0f;
 
-#pragma unroll 1
-                for (int i = 0; i < nstages; ++i) {
-                    const char *cur = lds + sl * kDmaStageBytes;
+                // One stage out of the fragments in buffer p (read from ring slot sl during the stage before);
+                // u: the stage's position in the cursor's group (0 when !QUAD).
+                auto stage = [&](const int sl, const int u, const int p) __attribute__((always_inline)) {
                     const int nsl = sl + 1 == kDmaStages ? 0 : sl + 1;
                     const char *nxt = lds + nsl * kDmaStageBytes;
                     __builtin_amdgcn_sched_barrier(0);
-                    // ---- first k-step; the second k-step's fragments are read meanwhile ----
-#pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        if (q < 2) {
-#pragma unroll
-                            for (int a = 2 * q; a < 2 * q + 2; ++a)
-                                fa[1][a] = *reinterpret_cast<const bf16x8_t *>(cur + fa_base + a * 32 * kDmaRowBytes + fr1);
-                        } else {
-#pragma unroll
-                            for (int b = 2 * q - 4; b < 2 * q - 2; ++b)
-                                fb[1][b] = *reinterpret_cast<const bf16x8_t *>(cur + fb_base + b * 32 * kDmaRowBytes + fr1);
-                        }
-#pragma unroll
-                        for (int b = 0; b < 4; ++b)
-                            acc[q][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[0][q], fb[0][b], acc[q][b], 0, 0, 0);
-                        __builtin_amdgcn_sched_barrier(0);
-                    }
-                    // ---- the next stage has landed (own loads: the kDmaStages - 2 stages after it may still be
-                    // in flight), this stage is no longer read (own reads, lgkmcnt(0)): meet.  A bare barrier:
-                    // the fence that __syncthreads() carries makes the compiler drain every direct load it can
-                    // see in flight (vmcnt(0)), which would empty the ring at each stage ----
+                    // The next stage has landed (own loads: the kDmaStages - 2 stages after it may still be in
+                    // flight) and this stage is in registers (own reads, lgkmcnt(0)): meet.  A bare barrier: the
+                    // fence that __syncthreads() carries makes the compiler drain every direct load it can see in
+                    // flight (vmcnt(0)), which would empty the ring at each stage.
                     __builtin_amdgcn_s_waitcnt(0x0070 | (8 * (kDmaStages - 2) & 15) | ((8 * (kDmaStages - 2) >> 4) << 14));
                     __builtin_amdgcn_s_barrier();
                     __builtin_amdgcn_sched_barrier(0);
-                    // ---- second k-step; the first fragments of the next stage (the next tile's first stage, at
-                    // the end of a tile) are read and the freed slot is refilled meanwhile, two direct loads per
-                    // group of four MFMAs ----
 #pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        refill_pair(sl, q);
+                    for (int grp = 0; grp < 8; ++grp) {   // k-step grp >> 2, vocabulary MFMA tile grp & 3
+                        const int ks = grp >> 2, q = grp & 3;
+                        // two fragments of the next stage (the next tile's first stage, at the end of a tile) ...
                         if (q < 2) {
 #pragma unroll
                             for (int a = 2 * q; a < 2 * q + 2; ++a)
-                                fa[0][a] = *reinterpret_cast<const bf16x8_t *>(nxt + fa_base + a * 32 * kDmaRowBytes + fr0);
+                                fa[p ^ 1][ks][a] = *reinterpret_cast<const bf16x8_t *>(nxt + fa_base + a * 32 * kDmaRowBytes + fr[ks]);
                         } else {
 #pragma unroll
                             for (int b = 2 * q - 4; b < 2 * q - 2; ++b)
-                                fb[0][b] = *reinterpret_cast<const bf16x8_t *>(nxt + fb_base + b * 32 * kDmaRowBytes + fr0);
+                                fb[p ^ 1][ks][b] = *reinterpret_cast<const bf16x8_t *>(nxt + fb_base + b * 32 * kDmaRowBytes + fr[ks]);
                         }
+                        // ... one direct load into the slot this stage came from ...
+                        refill(sl, grp >> 1, u, grp & 1);
+                        // ... and four MFMAs
 #pragma unroll
                         for (int b = 0; b < 4; ++b)
-                            acc[q][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[1][q], fb[1][b], acc[q][b], 0, 0, 0);
+                            acc[q][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[p][ks][q], fb[p][ks][b], acc[q][b], 0, 0, 0);
                         __builtin_amdgcn_sched_barrier(0);
                     }
-                    advance();
-                    sl = nsl;
+                };
+                if (QUAD) {
+                    static_assert(kDmaStages == 4, "the unrolled loop names the four ring slots");
+#pragma unroll 1
+                    for (int i = 0; i < nstages; i += kDmaStages) {
+                        stage(0, 0, 0);
+                        stage(1, 1, 1);
+                        stage(2, 2, 0);
+                        stage(3, 3, 1);
+                        advance(kDmaStages);
+                    }
+                } else {
+#pragma unroll 1
+                    for (int i = 0; i < nstages; i += 2) {  // H % 64 == 0: an even number of stages
+                        stage(sl_dyn, 0, 0);
+                        advance(1);
+                        sl_dyn = sl_dyn + 1 == kDmaStages ? 0 : sl_dyn + 1;
+                        stage(sl_dyn, 0, 1);
+                        advance(1);
+                        sl_dyn = sl_dyn + 1 == kDmaStages ? 0 : sl_dyn + 1;
+                    }
                 }
 
                 // ---- fold the tile into the running (max, sum) of this lane's four token columns, while the
@@ -337,15 +368,17 @@ hipError_t launch_fused_lmhead_logprob(const void *hidden, const void *weight, i
                                        const int32_t *chosen, float *logp, float *lse, void *workspace, hipStream_t s)
 {
     if (T == 0) return hipSuccess;
-    static bool attr_set = false;
-    if (!attr_set) {
-        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(lmhead_lse_kernel),
+    const bool quad = H % (kDmaK * kDmaStages) == 0;
+    auto *kernel = quad ? lmhead_lse_kernel<true> : lmhead_lse_kernel<false>;
+    static bool attr_set[2] = {false, false};
+    if (!attr_set[quad]) {
+        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
                                                  hipFuncAttributeMaxDynamicSharedMemorySize, kDmaLdsBytes);
         if (e != hipSuccess) return e;
-        attr_set = true;
+        attr_set[quad] = true;
     }
     float2 *partial = reinterpret_cast<float2 *>(workspace);
-    hipLaunchKernelGGL(lmhead_lse_kernel, dim3(256), dim3(kLmThreads), kDmaLdsBytes, s,
+    hipLaunchKernelGGL(kernel, dim3(256), dim3(kLmThreads), kDmaLdsBytes, s,
                        reinterpret_cast<const uint16_t *>(weight), reinterpret_cast<const uint16_t *>(hidden), T, H, V,
                        partial);
     hipError_t e = hipGetLastError();
