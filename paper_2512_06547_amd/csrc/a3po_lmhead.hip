@@ -15,7 +15,7 @@
 // Schedule.  256 persistent workgroups = 8 XCDs x 32.  Inside an XCD the 32 workgroups form a
 // 4 (token tiles) x 8 (vocabulary tiles) block that moves through the vocabulary together, so at
 // any time they share 4 hidden-state tiles and 8 weight tiles through that XCD's L2 instead of
-// each pulling its own 64 KiB per chunk from HBM.  A workgroup keeps one token tile for a whole
+// each pulling its own 32 KiB per stage from HBM.  A workgroup keeps one token tile for a whole
 // sweep over its vocabulary tiles (stride 8) and writes one partial (max, sum) per token at the
 // end; a small kernel merges the 8 partials per token, adds the chosen logit (a separate dot
 // product) and writes log pi.
