@@ -52,6 +52,13 @@ __global__ void f32_to_bf16_kernel(const float *__restrict__ src, uint16_t *__re
     }
 }
 
+// (a fill kernel rather than hipMemsetAsync, so that the call can be captured into a HIP graph)
+__global__ void zero_bf16_kernel(uint16_t *__restrict__ dst, size_t n)
+{
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) dst[i] = 0;
+}
+
 static rocblas_handle blas_handle()
 {
     static rocblas_handle handle = nullptr;
@@ -165,7 +172,9 @@ extern "C" int a3po_fused_lmhead_loss_fwd_bwd(const void *hidden, const void *we
     if (launch_loss_finish(a, s) != hipSuccess) return A3PO_E_LAUNCH;
     const size_t nw = (size_t)V * (size_t)H;
     if (T == 0) {
-        if (hipMemsetAsync(dweight, 0, nw * 2, s) != hipSuccess) return A3PO_E_LAUNCH;
+        hipLaunchKernelGGL(zero_bf16_kernel, dim3((unsigned)((nw + 255) / 256)), dim3(256), 0, s,
+                           static_cast<uint16_t *>(dweight), nw);
+        if (hipGetLastError() != hipSuccess) return A3PO_E_LAUNCH;
     } else {
         hipLaunchKernelGGL(f32_to_bf16_kernel, dim3((unsigned)((nw / 2 + 255) / 256)), dim3(256), 0, s, dwacc,
                            static_cast<uint16_t *>(dweight), nw);

@@ -151,3 +151,18 @@ def test_fused_lmhead_loss_fwd_bwd(a3po, T, H, V):
     if not near.any():
         assert not bad_w.any(), f"dW: {bad_w.sum()} elements off"
     assert np.abs(dh_ref).max() > 0 and np.abs(dw_ref).max() > 0
+
+
+def test_fused_lmhead_loss_fwd_bwd_empty_batch(a3po):
+    """T == 0: loss 0, no counted tokens, an all-zero weight gradient (the buffer is written, not left as found)."""
+    H, V = 64, 24
+    W = torch.randn((V, H), device="cuda").bfloat16()
+    h = torch.empty((0, H), dtype=torch.bfloat16, device="cuda")
+    i32 = torch.empty(0, dtype=torch.int32, device="cuda")
+    f32 = torch.empty(0, dtype=torch.float32, device="cuda")
+    out = a3po.fused_lmhead_loss_fwd_bwd(h, W, i32, f32, i32, 3, f32, torch.empty(0, dtype=torch.uint8, device="cuda"), 0.2)
+    torch.cuda.synchronize()
+    assert float(out["loss"].cpu()[0]) == 0.0
+    assert a3po.stats_to_dict(out["stats"])["n_tokens"] == 0
+    assert out["dweight"].shape == (V, H) and not out["dweight"].any()
+    assert out["dhidden"].numel() == 0
