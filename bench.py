@@ -341,7 +341,7 @@ def main():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="1p5b")
-    ap.add_argument("--cpu-rows", type=int, default=16384, help="rows of the oracle baseline sample (0 = skip)")
+    ap.add_argument("--cpu-rows", type=int, default=32768, help="rows of the oracle baseline sample (0 = skip)")
     ap.add_argument("--phase", default="both", choices=["both", "ragged", "ones"],
                     help="time the workload's own mask, an all-ones mask, or both (default)")
     ap.add_argument("--entropy", action="store_true",
