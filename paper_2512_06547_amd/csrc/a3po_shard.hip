@@ -28,6 +28,7 @@ namespace a3po {
 constexpr int kShardThreads = A3PO_SHARD_THREADS;
 constexpr int kShardWaves = kShardThreads / kWave;
 constexpr int kShardUnroll = A3PO_SHARD_UNROLL;  // 16-byte vectors in flight per thread
+constexpr int64_t kShardWaveRowBytes = 65536;     // forward: rows up to this size always go one wavefront per row
 
 // ---------------------------------------------------------------------------------------
 // partial (max, sum exp, chosen logit if owned, sum exp * z) of one shard, one workgroup per row
@@ -46,25 +47,25 @@ __global__ __launch_bounds__(kShardThreads) void shard_partials_kernel(const voi
     for (int64_t row = blockIdx.x; row < T; row += gridDim.x) {
         if (records && records[row].y < 0) continue;  // not counted: the row is not read (uniform over the workgroup)
         const char *in_row = reinterpret_cast<const char *>(z) + (size_t)row * row_bytes;
+        const int64_t yl = (int64_t)chosen[row] - v0;  // asked for first: its latency hides behind the row's loads
         MaxSumU acc;
         seed(acc);
         if (vec) {
-            int idx = tid;
-            for (; idx + (kShardUnroll - 1) * kShardThreads < nfull; idx += kShardUnroll * kShardThreads) {
+            // every pass issues up to kShardUnroll loads per thread before the first fold, the ragged last
+            // pass included (a shard row is often little more than one pass long)
+            for (int idx = tid; idx < nfull; idx += kShardUnroll * kShardThreads) {
                 uint4 v[kShardUnroll];
 #pragma unroll
-                for (int u = 0; u < kShardUnroll; ++u) v[u] = stream_load(in_row + (size_t)(idx + u * kShardThreads) * 16);
+                for (int u = 0; u < kShardUnroll; ++u)
+                    if (idx + u * kShardThreads < nfull) v[u] = stream_load(in_row + (size_t)(idx + u * kShardThreads) * 16);
 #pragma unroll
                 for (int u = 0; u < kShardUnroll; ++u) {
-                    float f[EPV];
-                    unpack<DT>(v[u], f);
-                    fold<EPV>(acc, f);
+                    if (idx + u * kShardThreads < nfull) {
+                        float f[EPV];
+                        unpack<DT>(v[u], f);
+                        fold<EPV>(acc, f);
+                    }
                 }
-            }
-            for (; idx < nfull; idx += kShardThreads) {
-                float f[EPV];
-                unpack<DT>(stream_load(in_row + (size_t)idx * 16), f);
-                fold<EPV>(acc, f);
             }
             for (int64_t j = (int64_t)nfull * EPV + tid; j < Vs; j += kShardThreads) {
                 float f[1] = {load_elem<DT>(in_row, j)};
@@ -76,13 +77,67 @@ __global__ __launch_bounds__(kShardThreads) void shard_partials_kernel(const voi
                 fold<1>(acc, f);
             }
         }
+        // the gather is issued before the reduction's barriers, not after them
+        const float zy = (tid == 0 && yl >= 0 && yl < Vs) ? load_elem<DT>(in_row, yl) : 0.0f;
         const MaxSumU tot = block_allreduce<kShardWaves>(acc, red);
         if (tid == 0) {
-            const int64_t yl = (int64_t)chosen[row] - v0;
             a3po_shard_partial p;
             p.max = tot.m;
             p.sum_exp = tot.s;
-            p.chosen_logit = (yl >= 0 && yl < Vs) ? load_elem<DT>(in_row, yl) : 0.0f;
+            p.chosen_logit = zy;
+            p.sum_exp_z = tot.u;
+            out[row] = p;
+        }
+    }
+}
+
+// The same, one wavefront per row: for narrow shards (a row is a few passes of one wavefront) there is no
+// barrier and no LDS in the row's path, and the 32 wavefronts of a compute unit run independently.
+// Vector path only (16-byte aligned base and stride).
+template <typename DT>
+__global__ __launch_bounds__(kShardThreads) void shard_partials_wave_kernel(const void *z, int64_t T, int64_t Vs,
+                                                                           int64_t ld,
+                                                                           const int32_t *__restrict__ chosen,
+                                                                           int64_t v0,
+                                                                           a3po_shard_partial *__restrict__ out,
+                                                                           const TokenRecord *__restrict__ records)
+{
+    constexpr int EPV = DT::kPerVec;
+    const int lane = threadIdx.x & (kWave - 1);
+    const int nfull = (int)(Vs / EPV);
+    const size_t row_bytes = (size_t)ld * DT::kBytes;
+    const int64_t nwaves = (int64_t)gridDim.x * kShardWaves;
+    for (int64_t row = (int64_t)blockIdx.x * kShardWaves + threadIdx.x / kWave; row < T; row += nwaves) {
+        if (records && records[row].y < 0) continue;  // uniform over the wavefront
+        const char *in_row = reinterpret_cast<const char *>(z) + (size_t)row * row_bytes;
+        const int64_t yl = (int64_t)chosen[row] - v0;
+        MaxSumU acc;
+        seed(acc);
+        for (int idx = lane; idx < nfull; idx += kShardUnroll * kWave) {
+            uint4 v[kShardUnroll];
+#pragma unroll
+            for (int u = 0; u < kShardUnroll; ++u)
+                if (idx + u * kWave < nfull) v[u] = stream_load(in_row + (size_t)(idx + u * kWave) * 16);
+#pragma unroll
+            for (int u = 0; u < kShardUnroll; ++u) {
+                if (idx + u * kWave < nfull) {
+                    float f[EPV];
+                    unpack<DT>(v[u], f);
+                    fold<EPV>(acc, f);
+                }
+            }
+        }
+        for (int64_t j = (int64_t)nfull * EPV + lane; j < Vs; j += kWave) {
+            float f[1] = {load_elem<DT>(in_row, j)};
+            fold<1>(acc, f);
+        }
+        const float zy = (lane == 0 && yl >= 0 && yl < Vs) ? load_elem<DT>(in_row, yl) : 0.0f;
+        const MaxSumU tot = wave_reduce(acc);
+        if (lane == 0) {
+            a3po_shard_partial p;
+            p.max = tot.m;
+            p.sum_exp = tot.s;
+            p.chosen_logit = zy;
             p.sum_exp_z = tot.u;
             out[row] = p;
         }
@@ -228,7 +283,7 @@ __global__ __launch_bounds__(kShardThreads) void shard_bwd_rows_kernel(
 // evaluated by the first threads and handed over through LDS (double-buffered by item parity, so one
 // barrier per item suffices); the chosen column's +g is added in registers by the thread that holds
 // that element.  Items come from the workspace's queue counter.
-constexpr int kBurstThreads = 1024;
+constexpr int kBurstThreads = 1024;  // one workgroup per compute unit: halves and quarters (more, smaller bursts) are 6-8 % slower
 template <typename DT> struct BurstVec { static constexpr int value = 19; };  // vectors per thread and item
 template <> struct BurstVec<F32> { static constexpr int value = 16; };  // (what fits in 128 registers)
 
@@ -379,6 +434,20 @@ hipError_t launch_shard_partials(const void *z, int dt, int64_t T, int64_t Vs, i
     if (T == 0) return hipSuccess;
     const int64_t esz = dt == A3PO_F32 ? 4 : 2;
     const int vec = aligned16(z) && (ld * esz) % 16 == 0;
+    const unsigned cap = shard_grid(T);
+    // one wavefront per row for narrow rows, and for any rows when there are enough of them to give every
+    // resident wavefront its own; one workgroup per row otherwise (few long rows)
+    if (vec && (Vs * esz <= kShardWaveRowBytes || T >= (int64_t)cap * kShardWaves)) {
+        const int64_t blocks = (T + kShardWaves - 1) / kShardWaves;
+        const unsigned grid = (unsigned)(blocks < (int64_t)cap ? blocks : cap);
+        if (dt == A3PO_F32)
+            hipLaunchKernelGGL((shard_partials_wave_kernel<F32>), dim3(grid), dim3(kShardThreads), 0, s, z, T, Vs, ld,
+                               chosen, v0, out, records);
+        else
+            hipLaunchKernelGGL((shard_partials_wave_kernel<Bf16>), dim3(grid), dim3(kShardThreads), 0, s, z, T, Vs, ld,
+                               chosen, v0, out, records);
+        return hipGetLastError();
+    }
     if (dt == A3PO_F32)
         hipLaunchKernelGGL((shard_partials_kernel<F32>), dim3(shard_grid(T)), dim3(kShardThreads), 0, s, z, T, Vs, ld,
                            chosen, v0, out, records, vec);
