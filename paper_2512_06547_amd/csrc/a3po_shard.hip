@@ -396,9 +396,12 @@ __global__ __launch_bounds__(kBurstThreads) void shard_bwd_burst_kernel(
                 unpack<DT>(v[k], f);
                 const int ye = s_ycol[par][r] - c * EPV;  // the chosen column's place in this vector
 #pragma unroll
-                for (int e = 0; e < EPV; ++e) {
-                    f[e] = neg_g * exp2_hw(fmaf(f[e], kLog2e, nlse));
-                    if (e == ye) f[e] -= neg_g;  // + g
+                for (int e = 0; e < EPV; ++e) f[e] = neg_g * exp2_hw(fmaf(f[e], kLog2e, nlse));
+                if ((unsigned)ye < (unsigned)EPV) {  // one vector per row: a real branch, not eight selects per vector
+                    asm volatile("" ::: "memory");
+#pragma unroll
+                    for (int e = 0; e < EPV; ++e)
+                        if (e == ye) f[e] -= neg_g;  // + g
                 }
             } else {
 #pragma unroll
