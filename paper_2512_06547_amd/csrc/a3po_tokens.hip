@@ -76,18 +76,38 @@ __global__ __launch_bounds__(kTokThreads) void loss_finish_kernel(const float *o
     double sum = 0.0, esum = 0.0;
     long long clip = 0, neg = 0;
     float lo = INFINITY, hi = -INFINITY;
-    for (int64_t t = threadIdx.x; t < T; t += kTokThreads) {
-        const uint8_t f = flags[t];
-        if (iw_out) iw_out[t] = (f & kFlagCounted) ? iw[t] : 0.0f;
-        if (clipped_out) clipped_out[t] = (f & kFlagClipped) ? 1 : 0;
-        if (f & kFlagCounted) {
-            sum += (double)obj[t];
-            if (ent) esum += (double)ent[t];
-            clip += (f & kFlagClipped) ? 1 : 0;
-            neg += (f & kFlagNegStale) ? 1 : 0;
-            const float w = iw[t];
-            lo = fminf(lo, w);
-            hi = fmaxf(hi, w);
+    // kFinishUnroll tokens' loads are in flight before the first is used (one workgroup: latency, not bandwidth);
+    // the order of a thread's additions is that of its tokens, whatever the unroll
+    constexpr int kFinishUnroll = 8;
+    for (int64_t t0 = threadIdx.x; t0 < T; t0 += (int64_t)kFinishUnroll * kTokThreads) {
+        uint8_t f[kFinishUnroll];
+        float o[kFinishUnroll], w[kFinishUnroll], h[kFinishUnroll];
+#pragma unroll
+        for (int u = 0; u < kFinishUnroll; ++u) {
+            const int64_t t = t0 + (int64_t)u * kTokThreads;
+            f[u] = 0;
+            o[u] = w[u] = h[u] = 0.0f;
+            if (t < T) {
+                f[u] = flags[t];
+                o[u] = obj[t];
+                w[u] = iw[t];
+                if (ent) h[u] = ent[t];
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < kFinishUnroll; ++u) {
+            const int64_t t = t0 + (int64_t)u * kTokThreads;
+            if (t >= T) continue;
+            if (iw_out) iw_out[t] = (f[u] & kFlagCounted) ? w[u] : 0.0f;
+            if (clipped_out) clipped_out[t] = (f[u] & kFlagClipped) ? 1 : 0;
+            if (f[u] & kFlagCounted) {
+                sum += (double)o[u];
+                if (ent) esum += (double)h[u];
+                clip += (f[u] & kFlagClipped) ? 1 : 0;
+                neg += (f[u] & kFlagNegStale) ? 1 : 0;
+                lo = fminf(lo, w[u]);
+                hi = fmaxf(hi, w[u]);
+            }
         }
     }
 #pragma unroll
