@@ -483,7 +483,7 @@ static BurstShape burst_shape(int64_t T, int64_t Vs, int64_t esz)
         sh.chunks = (int)((sh.nvec_row + cap - 1) / cap);
         sh.chunk_vec = (sh.nvec_row + sh.chunks - 1) / sh.chunks;
     }
-    sh.magic = (uint32_t)((1ull << 32) / (uint64_t)sh.nvec_row + 1);  // used only when rows > 1 (then cw == nvec_row)
+    sh.magic = (uint32_t)((1ull << 32) / (uint64_t)sh.nvec_row + 1);  // nvec_row >= 2; used only when rows > 1 (then cw == nvec_row)
     sh.items = ((T + sh.rows - 1) / sh.rows) * sh.chunks;
     return sh;
 }
@@ -495,7 +495,9 @@ hipError_t launch_shard_bwd_rows(const LossArgs &a, int64_t v0, const float *log
     const int vec = aligned16(a.z) && aligned16(a.dz) && (a.ld * esz) % 16 == 0;
     const RowOutputs out = {nullptr, a.prox_out, a.ws_obj, a.ws_iw, nullptr, a.ws_flags};
     const WsHeader *hdr = reinterpret_cast<const WsHeader *>(a.ws_header);
-    if (vec) {  // bursts; the queue counter in the workspace header was zeroed by the prep kernel
+    // bursts for rows of at least two vectors (the reciprocal that stands in for the division by the row
+    // length does not exist for 1); the queue counter in the workspace header was zeroed by the prep kernel
+    if (vec && a.V * esz > 16) {
         const BurstShape sh = burst_shape(a.T, a.V, esz);
         int dev = 0, cus = 0;
         if (hipGetDevice(&dev) != hipSuccess ||

@@ -134,6 +134,8 @@ def test_uneven_shards_bf16(a3po, bounds):
     ("bf16", 70000, [0, 70000]),                     # a single shard is the whole vocabulary
     ("f32", 70000, [0, 70000]),                      # 17,500 vectors per row: two column chunks per row
     ("bf16", 163848, [0, 163848]),                   # 20,481 vectors per row: two chunks, the last vector whole
+    ("bf16", 45, [0, 21, 30, 37, 45]),               # a shard of exactly one 16-byte vector per row (8 columns)
+    ("f32", 20, [0, 4, 8, 20]),                      # the same in fp32 (4 columns), next to a three-vector shard
 ])
 def test_contiguous_shards(a3po, dtype, V, bounds):
     w = synth.WORKLOADS["tiny"].scaled(V=V, dtype=dtype, S=4, L=8, len_lo=4, len_hi=8, sigma=3.0, boost=6.0,
