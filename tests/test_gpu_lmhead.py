@@ -101,13 +101,26 @@ def _bf16_round(x):
     return bits, synth.bf16_bits_to_f64(bits)
 
 
-@pytest.mark.parametrize("T,H,V", [(300, 64, 1000), (1, 8, 8), (8192 + 300, 64, 512)])
+def _bf16_ulp(x):
+    """spacing of bfloat16 at |x| (8 significant bits)"""
+    a = np.maximum(np.abs(x), 2.0 ** -126)
+    return 2.0 ** (np.floor(np.log2(a)) - 7)
+
+
+@pytest.mark.parametrize("T,H,V", [(300, 64, 1000), (1, 8, 8), (8192 + 300, 64, 512), (467, 224, 1344)])
 def test_fused_lmhead_loss_fwd_bwd(a3po, T, H, V):
     """The oracle follows the same staging as the GPU path (logits rounded once to bfloat16, gradient
-    rows rounded to bfloat16 before the two contractions), in fp64 otherwise.  Tolerances:
-    log-probs one bfloat16 ulp of the chosen logit (a rounding tie may fall the other way after fp32
-    accumulation) - in practice they agree to 1e-5; dh, dW: 2^-7 |ref| + 2^-9 sum |dz| |operand|
-    (bfloat16 output rounding plus fp32 accumulation of bfloat16 products)."""
+    rows rounded to bfloat16 before the two contractions), in fp64 otherwise.  What the two cannot
+    share is the side of a rounding tie: the GPU rounds an fp32-accumulated logit, the oracle an fp64
+    one, so a logit within the fp32 accumulation error (H u sum_k |h||W|, u = 2^-24) of a bfloat16
+    rounding boundary may come out one ulp apart ("tie" below).  Error model, per element:
+      log-probs  1e-5-ish, plus for a tied chosen logit its ulp, plus the shift of lse a tied logit causes
+                 (p ulp): dev_t.  A clip decision is compared only when log r is further than 1e-3 + dev_t
+                 from both clip bounds; rows of such tokens are left out of dh, and dW is then not compared.
+      dh, dW     2^-7 |ref|                      bfloat16 rounding of the output
+               + 2^-8 sum |dz| |operand|         every gradient entry may round the other way (fp32 vs fp64 value)
+               + sum over tied (t, v) of |g_t| p ulp(z) |operand|      the entry of a tied logit itself
+               + sum_t dev_t |dz| |operand|      every entry of a row whose lse moved."""
     r = np.random.default_rng(T + 7 * V)
     cur = 50
     h = bf16_bits(r.standard_normal((T, H)))
@@ -126,31 +139,43 @@ def test_fused_lmhead_loss_fwd_bwd(a3po, T, H, V):
     dh_ref, dw_ref = oracle.lmhead_backward(dzr, h, W)
     dh_abs, dw_abs = oracle.lmhead_backward(np.abs(dzr), h & 0x7FFF, W & 0x7FFF)
 
-    dev = lambda a: torch.from_numpy(a).cuda()
-    out = a3po.fused_lmhead_loss_fwd_bwd(dev(h).view(torch.bfloat16), dev(W).view(torch.bfloat16), dev(y), dev(lb),
-                                         dev(ver), cur, dev(adv), dev(mask), 0.2)
+    # logits the two roundings may disagree on, and what that does to each row
+    z_abs = oracle.lmhead_logits(h & 0x7FFF, W & 0x7FFF)
+    ulp = _bf16_ulp(z)
+    tie = np.abs(np.abs(z - zr) - 0.5 * ulp) <= H * 2.0 ** -24 * z_abs + 1e-300
+    p = np.exp(zr - ref["lse"][:, None])
+    dev = (tie * p * ulp).sum(axis=1) + tie[np.arange(T), y] * ulp[np.arange(T), y]     # |delta log pi| per token
+    direct = tie * np.abs(ref["g"])[:, None] * p * ulp                                    # |delta dz| of the tied entries
+    dh_tie, dw_tie = oracle.lmhead_backward(direct + dev[:, None] * np.abs(dzr), h & 0x7FFF, W & 0x7FFF)
+
+    dev_ = lambda a: torch.from_numpy(a).cuda()
+    out = a3po.fused_lmhead_loss_fwd_bwd(dev_(h).view(torch.bfloat16), dev_(W).view(torch.bfloat16), dev_(y), dev_(lb),
+                                         dev_(ver), cur, dev_(adv), dev_(mask), 0.2)
     torch.cuda.synchronize()
     st = a3po.stats_to_dict(out["stats"])
     assert st["n_tokens"] == ref["stats"]["n_tokens"]
     logp = out["logp"].cpu().numpy().astype(np.float64)
-    zy = np.abs(zr[np.arange(T), y])
-    assert (np.abs(logp - ref["logp"]) <= 2.0 ** -7 * np.maximum(1.0, zy) * (mask == 1) + 1e-30).all()
+    assert (np.abs(logp - ref["logp"]) <= (2e-5 + 1e-5 * np.abs(ref["logp"]) + dev) * (mask == 1) + 1e-30).all()
     assert np.quantile(np.abs(logp - ref["logp"]), 0.99) < 2e-5
     N = max(1, st["n_tokens"])
     loss = float(out["loss"].cpu()[0])
     sur = oracle.surrogate(ref["logp"], lb, ver, cur, adv, ref["eff_mask"], 0.2)
+    near = ((np.abs(np.log(sur["r"]) - np.log(1.2)) < 1e-3 + dev) |
+            (np.abs(np.log(sur["r"]) - np.log(0.8)) < 1e-3 + dev)) & (ref["eff_mask"] == 1)
     scale = (np.abs(sur["obj"]) * ref["eff_mask"]).sum() / N
-    assert abs(loss - ref["loss"]) <= 1e-4 * scale + 1e-6, (loss, ref["loss"])
+    slack = (np.abs(sur["obj"]) * (dev + near * 0.5)).sum() / N       # a token's objective moves with its log-prob
+    assert abs(loss - ref["loss"]) <= 1e-4 * scale + slack + 1e-6, (loss, ref["loss"])
     dh = out["dhidden"].float().cpu().numpy().astype(np.float64)
     dw = out["dweight"].float().cpu().numpy().astype(np.float64)
-    bad_h = np.abs(dh - dh_ref) > 2.0 ** -7 * np.abs(dh_ref) + 2.0 ** -9 * dh_abs + 1e-30
-    bad_w = np.abs(dw - dw_ref) > 2.0 ** -7 * np.abs(dw_ref) + 2.0 ** -9 * dw_abs + 1e-30
-    # a clip decision within the boundary band may differ for a token: allow those rows of dh to differ
-    near = (np.abs(sur["r"] - 1.2) < 1e-3) | (np.abs(sur["r"] - 0.8) < 1e-3)
-    assert not bad_h[~near].any(), f"dh: {bad_h.sum()} elements off"
+    bad_h = np.abs(dh - dh_ref) > 2.0 ** -7 * np.abs(dh_ref) + 2.0 ** -8 * dh_abs + dh_tie + 1e-30
+    bad_w = np.abs(dw - dw_ref) > 2.0 ** -7 * np.abs(dw_ref) + 2.0 ** -8 * dw_abs + dw_tie + 1e-30
+    assert not bad_h[~near].any(), f"dh: {bad_h[~near].sum()} elements off"
     if not near.any():
         assert not bad_w.any(), f"dW: {bad_w.sum()} elements off"
     assert np.abs(dh_ref).max() > 0 and np.abs(dw_ref).max() > 0
+    # the model stays sharp: what the ties add (many of them at logits near zero, whose ulp is tiny) is small beside
+    # the rounding terms
+    assert np.median(dw_tie / (2.0 ** -8 * dw_abs + 1e-300)) < 1.0 and np.median(dh_tie / (2.0 ** -8 * dh_abs + 1e-300)) < 1.0
 
 
 def test_fused_lmhead_loss_fwd_bwd_empty_batch(a3po):
