@@ -130,6 +130,8 @@ int a3po_token_logprobs_entropy(const void *logits, a3po_dtype dt, int64_t T, in
  * current version):
  *   d = current_version - versions[t];  alpha = 1/d if d >= 1 else 1;
  *   logp_prox_out[t] = alpha * logp_behav[t] + (1 - alpha) * logp_theta[t]     (fp32)
+ * d is the exact integer difference (any int32 versions, so up to 2^32 - 1), converted to fp32 once:
+ * alpha is the correctly rounded 1/d for d <= 2^24 and within one fp32 ulp of it beyond.
  * alpha_out (nullable) [T] float.  All arrays [T].
  */
 int a3po_proximal_interp(const float *logp_behav, const float *logp_theta,

@@ -316,6 +316,19 @@ def test_proximal_interp(a3po):
     lo, hi = np.minimum(lb, lt), np.maximum(lb, lt)                # sandwich property on device outputs
     slack = 4 * np.spacing(np.maximum(np.abs(lb), np.abs(lt)))
     assert (lp >= lo - slack).all() and (lp <= hi + slack).all()
+    # versions anywhere in int32: the staleness is an exact integer difference (up to 2^32 - 1), converted to
+    # fp32 once, so alpha is the correctly rounded 1/d up to d = 2^24 and within one fp32 ulp of it beyond
+    ver = r.integers(-2 ** 31, 2 ** 31, n).astype(np.int32)
+    for cur in (2 ** 31 - 1, 0, -2 ** 31):
+        lp, al = a3po.proximal_interp(torch.from_numpy(lb).cuda(), torch.from_numpy(lt).cuda(),
+                                      torch.from_numpy(ver).cuda(), cur)
+        ref_lp, ref_al = oracle.proximal_interp(lb, lt, ver, cur)
+        al = al.cpu().numpy()
+        d = np.int64(cur) - ver.astype(np.int64)
+        small = d <= (1 << 24)
+        assert np.array_equal(al[small], ref_al.astype(np.float32)[small])
+        assert (np.abs(al[~small] - ref_al[~small]) <= 1.2e-7 * ref_al[~small]).all()
+        assert (np.abs(lp.cpu().numpy() - ref_lp) <= 1e-5 * np.abs(ref_lp) + 1e-6).all()
 
 
 def test_grpo_advantages(a3po):
