@@ -109,6 +109,9 @@ const char *a3po_strerror(int code);
  * lse_out (nullable) [T] float.  chosen_logit_out (nullable) [T] elements of dtype `dt`:
  * the stored z[t,y_t] copied bit for bit.  A chosen id outside [0,V) gives logp 0 and a
  * zero chosen logit; lse is still written.  Reads T*V elements once.
+ * Logits may be -inf (entries that cannot be sampled: probability exactly 0).  Accuracy of lse and
+ * logp: 1e-5 (1 + |value|) + 1.2e-7 max_j |z[t,j]| - the last term is below 1e-5 for logits within
+ * +-80, the range language models produce, and grows with the magnitude of the largest logit.
  */
 int a3po_token_logprobs(const void *logits, a3po_dtype dt, int64_t T, int64_t V, int64_t ld,
                         const int32_t *chosen, float *logp_out, float *lse_out,

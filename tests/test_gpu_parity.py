@@ -401,3 +401,51 @@ def test_graph_capture_and_replay(a3po):
     torch.cuda.synchronize()
     for k in eager1:
         assert torch.equal(replayed[k].view(torch.uint8), fresh[k].view(torch.uint8)), k
+
+
+# ------------------------------------------------------------------------------------------ large logits
+
+@pytest.mark.parametrize("dtype,V,sigma,offset", [("f32", 4099, 300.0, 0.0), ("f32", 32000, 1e4, 0.0), ("bf16", 8192, 30.0, 1e3),
+                                                  ("f32", 1000, 1.0, -1e6), ("bf16", 151936, 3000.0, 0.0), ("f32", 64, 1.0, 1e8)])
+def test_large_logits(a3po, dtype, V, sigma, offset):
+    """Beyond the magnitudes language models produce the bars widen by 1.2e-7 max|z| (the common shift that the
+    rounding of m log2e gives every exponent of a row); nothing overflows, a third of the entries are -inf."""
+    r = np.random.default_rng(int(V + sigma))
+    T = 12
+    z = (r.standard_normal((T, V)) * sigma + offset).astype(np.float32)
+    z[r.random((T, V)) < 0.3] = -np.inf
+    y = np.array([r.choice(np.nonzero(np.isfinite(z[t]))[0]) for t in range(T)], dtype=np.int32)
+    if dtype == "bf16":
+        u = z.view(np.uint32).astype(np.uint64)
+        z = ((u + 0x7FFF + ((u >> 16) & 1)) >> 16).astype(np.uint16)
+        z64 = synth.bf16_bits_to_f64(z)
+    else:
+        z64 = z.astype(np.float64)
+    big = 1.2e-7 * np.abs(np.where(np.isfinite(z64), z64, 0.0)).max(axis=1)
+
+    def close(gpu, ref, what):
+        err = np.abs(np.asarray(gpu, dtype=np.float64) - ref)
+        assert (err <= 1e-5 * np.abs(ref) + 1e-5 + big).all(), f"{what}: max err {err.max():.3e}"
+
+    ref = oracle.token_logprobs(z, y)
+    logp, lse, _ = a3po.token_logprobs(dev_logits(z), torch.from_numpy(y).cuda())
+    close(lse.cpu().numpy(), ref["lse"], "lse")
+    close(logp.cpu().numpy(), ref["logp"], "logp")
+    lb = np.minimum(0.0, ref["logp"] + r.standard_normal(T) * 0.2).astype(np.float32)
+    ver = (CUR - r.integers(0, 6, T)).astype(np.int32)
+    adv = r.standard_normal(T).astype(np.float32)
+    m = np.ones(T, dtype=np.uint8)
+    out = a3po.loss_fwd_bwd(dev_logits(z), torch.from_numpy(y).cuda(), torch.from_numpy(lb).cuda(),
+                            torch.from_numpy(ver).cuda(), CUR, torch.from_numpy(adv).cuda(), torch.from_numpy(m).cuda(), 0.2)
+    torch.cuda.synchronize()
+    full = oracle.loss_fwd_bwd(z, y, lb, ver, CUR, adv, m, 0.2, want_dz=True)
+    close(out["logp"].cpu().numpy(), full["logp"], "fused logp")
+    sur = oracle.surrogate(full["logp"], lb, ver, CUR, adv, full["eff_mask"], 0.2)
+    tau = (1e-4 if dtype == "f32" else 1e-3) + 3 * big          # the clip ratio inherits the log-prob's bar
+    ok = (np.abs(np.log(sur["r"]) - np.log(1.2)) > tau) & (np.abs(np.log(sur["r"]) - np.log(0.8)) > tau)
+    dz = host_rows(out["dlogits"])
+    assert np.isfinite(dz).all() and not dz[~np.isfinite(z64)].any()
+    rel = (2e-5 if dtype == "f32" else 2.0 ** -8) + 2 * big[:, None]
+    err = np.abs(dz - full["dz"])
+    bound = rel * np.abs(full["dz"]) + (1e-5 + big[:, None]) * np.abs(full["g"])[:, None]
+    assert (err[ok] <= bound[ok]).all(), f"dlogits: max err {err[ok].max():.3e}"
