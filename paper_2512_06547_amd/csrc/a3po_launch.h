@@ -42,12 +42,20 @@ struct LossArgs {
     uint8_t *ws_flags;
     float *ws_lse;                  // [T], three-pass path only (rows too long for the registers)
     a3po_shard_partial *ws_partial; // [T], three-pass path only
+    void *ws_scratch;               // kLossScratchBytes: per-workgroup partials of the prep and finish kernels
 };
 
-// Workspace of the loss path: header | TokenRecord[T] (16 bytes each) | obj[T] | iw[T] | flags[T] | lse[T] | partial[T]
+// Workspace of the loss path: header | TokenRecord[T] (16 bytes each) | obj[T] | iw[T] | flags[T] | lse[T] | partial[T] |
+// scratch
 struct LossWsLayout {
-    size_t records, obj, iw, flags, lse, partial, total;
+    size_t records, obj, iw, flags, lse, partial, scratch, total;
 };
+
+// The O(T) kernels before and after the row kernel run on up to kTokMaxBlocks workgroups of kTokBlockTokens tokens
+// each (one workgroup for short batches); each leaves a partial of at most 64 bytes in the scratch area.
+constexpr int kTokMaxBlocks = 256;
+constexpr int kTokBlockTokens = 2048;
+constexpr size_t kLossScratchBytes = (size_t)kTokMaxBlocks * 64;
 inline LossWsLayout loss_ws_layout(int64_t T)
 {
     auto up = [](size_t x) { return (x + 255) / 256 * 256; };
@@ -59,7 +67,8 @@ inline LossWsLayout loss_ws_layout(int64_t T)
     l.flags = l.iw + up(t * sizeof(float));
     l.lse = l.flags + up(t);
     l.partial = l.lse + up(t * sizeof(float));
-    l.total = l.partial + up(t * sizeof(a3po_shard_partial));
+    l.scratch = l.partial + up(t * sizeof(a3po_shard_partial));
+    l.total = l.scratch + kLossScratchBytes;
     return l;
 }
 
@@ -75,6 +84,7 @@ inline void carve_loss_ws(LossArgs &a, void *workspace, int64_t T)
     a.ws_flags = reinterpret_cast<uint8_t *>(ws + lay.flags);
     a.ws_lse = reinterpret_cast<float *>(ws + lay.lse);
     a.ws_partial = reinterpret_cast<a3po_shard_partial *>(ws + lay.partial);
+    a.ws_scratch = ws + lay.scratch;
 }
 
 // true when the single-pass register-resident kernel can take these rows

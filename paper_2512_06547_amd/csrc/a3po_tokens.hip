@@ -61,15 +61,149 @@ __global__ __launch_bounds__(kTokThreads) void loss_prep_kernel(const int32_t *c
     }
 }
 
+// The same for long batches, on several workgroups: workgroup b packs the records of tokens
+// [b, b+1) * per_block and leaves its two counts in the scratch area; a one-workgroup kernel adds the
+// counts (integers: any order) and writes the header.
+struct PrepPartial {
+    long long cnt, bad;
+};
+
+__global__ __launch_bounds__(kTokThreads) void loss_prep_records_kernel(const int32_t *chosen, const uint8_t *mask,
+                                                                        const float *lb, const int32_t *versions,
+                                                                        const float *adv, const float *prox_in,
+                                                                        int64_t T, int64_t V, TokenRecord *records,
+                                                                        PrepPartial *partial, int64_t per_block)
+{
+    __shared__ long long s_cnt[kTokWaves], s_bad[kTokWaves];
+    long long cnt = 0, bad = 0;
+    const int64_t t_end = min(T, ((int64_t)blockIdx.x + 1) * per_block);
+    for (int64_t t = (int64_t)blockIdx.x * per_block + threadIdx.x; t < t_end; t += kTokThreads) {
+        const bool m = mask[t] != 0;
+        const int32_t y = chosen[t];
+        const bool ok = y >= 0 && (int64_t)y < V;
+        cnt += (m && ok) ? 1 : 0;
+        bad += (m && !ok) ? 1 : 0;
+        TokenRecord r;
+        r.y = (m && ok) ? y : -1;
+        r.ver = prox_in ? __float_as_int(prox_in[t]) : (versions ? versions[t] : 0);
+        r.lb = lb[t];
+        r.A = adv[t];
+        records[t] = r;
+    }
+#pragma unroll
+    for (int off = kWave / 2; off > 0; off >>= 1) {
+        cnt += __shfl_xor(cnt, off, kWave);
+        bad += __shfl_xor(bad, off, kWave);
+    }
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+    if (lane == 0) {
+        s_cnt[wave] = cnt;
+        s_bad[wave] = bad;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        PrepPartial p = {0, 0};
+        for (int w = 0; w < kTokWaves; ++w) {
+            p.cnt += s_cnt[w];
+            p.bad += s_bad[w];
+        }
+        partial[blockIdx.x] = p;
+    }
+}
+
+__global__ __launch_bounds__(kTokMaxBlocks) void loss_prep_header_kernel(const PrepPartial *partial, int nblocks,
+                                                                        float denom, const float *denom_dev,
+                                                                        WsHeader *hdr)
+{
+    if (denom_dev) denom = *denom_dev;
+    __shared__ long long s_cnt[kTokMaxBlocks / kWave], s_bad[kTokMaxBlocks / kWave];
+    long long cnt = 0, bad = 0;
+    if ((int)threadIdx.x < nblocks) {
+        cnt = partial[threadIdx.x].cnt;
+        bad = partial[threadIdx.x].bad;
+    }
+#pragma unroll
+    for (int off = kWave / 2; off > 0; off >>= 1) {
+        cnt += __shfl_xor(cnt, off, kWave);
+        bad += __shfl_xor(bad, off, kWave);
+    }
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+    if (lane == 0) {
+        s_cnt[wave] = cnt;
+        s_bad[wave] = bad;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        long long c = 0, b = 0;
+        for (int w = 0; w < kTokMaxBlocks / kWave; ++w) {
+            c += s_cnt[w];
+            b += s_bad[w];
+        }
+        const float n = denom > 0.0f ? denom : (float)c;
+        hdr->inv_n = n > 0.0f ? 1.0f / n : 0.0f;
+        hdr->n_as_float = n;
+        hdr->n_counted = c;
+        hdr->n_bad = b;
+        *row_queue_of(hdr) = 0u;  // the row kernel's work queue starts empty
+    }
+}
+
+// Totals of the finish pass over a range of tokens.
+struct FinishTotals {
+    double sum, esum;     // sum of obj and of the entropies over counted tokens
+    long long clip, neg;  // clipped tokens, tokens with negative staleness
+    float lo, hi;         // extrema of the importance weight
+};
+
+static_assert(sizeof(FinishTotals) <= 64 && sizeof(PrepPartial) <= 64, "a partial is at most 64 bytes of the scratch area");
+
+// loss_out / stats_out from the totals of the whole call (overwritten, or merged into what earlier micro-batches of
+// the same update left there)
+__device__ __forceinline__ void write_loss_and_stats(const FinishTotals &tot, bool have_entropy, const WsHeader *hdr,
+                                                     float *loss_out, a3po_stats *stats, int accumulate)
+{
+    const float share = (float)(-(tot.sum * (double)hdr->inv_n));
+    *loss_out = accumulate ? *loss_out + share : share;
+    if (!stats) return;
+    a3po_stats o;
+    o.n_tokens = hdr->n_counted;
+    o.n_clipped = tot.clip;
+    o.n_bad_index = hdr->n_bad;
+    o.n_negative_staleness = tot.neg;
+    o.iw_min = tot.lo;
+    o.iw_max = tot.hi;
+    o.entropy_mean = (have_entropy && hdr->n_counted > 0) ? (float)(tot.esum / (double)hdr->n_counted) : 0.0f;
+    o.reserved = 0.0f;
+    if (accumulate) {
+        const a3po_stats p = *stats;
+        const long long n = p.n_tokens + o.n_tokens;
+        o.entropy_mean = (have_entropy && n > 0)
+                             ? (float)(((double)p.entropy_mean * (double)p.n_tokens + tot.esum) / (double)n)
+                             : 0.0f;
+        o.n_tokens = n;
+        o.n_clipped += p.n_clipped;
+        o.n_bad_index += p.n_bad_index;
+        o.n_negative_staleness += p.n_negative_staleness;
+        o.iw_min = fminf(o.iw_min, p.iw_min);
+        o.iw_max = fmaxf(o.iw_max, p.iw_max);
+    }
+    *stats = o;
+}
+
 // loss = -(1/N) sum over counted tokens of obj, accumulated in double in a fixed order
 // (thread-strided partials, then a fixed tree), so repeated runs agree bit for bit.
 // ent (nullable): per-token entropies the row kernel wrote; their mean over counted tokens goes to
 // the statistics.  iw_out / clipped_out (nullable): per-token copies for the caller.
+// partial == nullptr: one workgroup covers all T tokens and writes loss and statistics itself.  Otherwise workgroup b
+// covers tokens [b, b+1) * per_block and leaves its totals in partial[b] for loss_finish_final_kernel.
 __global__ __launch_bounds__(kTokThreads) void loss_finish_kernel(const float *obj, const float *iw, const uint8_t *flags,
                                                                   const float *ent, int64_t T, const WsHeader *hdr,
                                                                   float *loss_out, a3po_stats *stats, float *iw_out,
-                                                                  uint8_t *clipped_out, int accumulate)
+                                                                  uint8_t *clipped_out, int accumulate,
+                                                                  FinishTotals *partial, int64_t per_block)
 {
+    const int64_t t_begin = partial ? (int64_t)blockIdx.x * per_block : 0;
+    const int64_t t_end = partial ? min(T, t_begin + per_block) : T;
     __shared__ double s_sum[kTokWaves], s_ent[kTokWaves];
     __shared__ long long s_clip[kTokWaves], s_neg[kTokWaves];
     __shared__ float s_min[kTokWaves], s_max[kTokWaves];
@@ -79,7 +213,7 @@ __global__ __launch_bounds__(kTokThreads) void loss_finish_kernel(const float *o
     // kFinishUnroll tokens' loads are in flight before the first is used (one workgroup: latency, not bandwidth);
     // the order of a thread's additions is that of its tokens, whatever the unroll
     constexpr int kFinishUnroll = 8;
-    for (int64_t t0 = threadIdx.x; t0 < T; t0 += (int64_t)kFinishUnroll * kTokThreads) {
+    for (int64_t t0 = t_begin + threadIdx.x; t0 < t_end; t0 += (int64_t)kFinishUnroll * kTokThreads) {
         uint8_t f[kFinishUnroll];
         float o[kFinishUnroll], w[kFinishUnroll], h[kFinishUnroll];
 #pragma unroll
@@ -87,7 +221,7 @@ __global__ __launch_bounds__(kTokThreads) void loss_finish_kernel(const float *o
             const int64_t t = t0 + (int64_t)u * kTokThreads;
             f[u] = 0;
             o[u] = w[u] = h[u] = 0.0f;
-            if (t < T) {
+            if (t < t_end) {
                 f[u] = flags[t];
                 o[u] = obj[t];
                 w[u] = iw[t];
@@ -97,7 +231,7 @@ __global__ __launch_bounds__(kTokThreads) void loss_finish_kernel(const float *o
 #pragma unroll
         for (int u = 0; u < kFinishUnroll; ++u) {
             const int64_t t = t0 + (int64_t)u * kTokThreads;
-            if (t >= T) continue;
+            if (t >= t_end) continue;
             if (iw_out) iw_out[t] = (f[u] & kFlagCounted) ? w[u] : 0.0f;
             if (clipped_out) clipped_out[t] = (f[u] & kFlagClipped) ? 1 : 0;
             if (f[u] & kFlagCounted) {
@@ -130,44 +264,52 @@ __global__ __launch_bounds__(kTokThreads) void loss_finish_kernel(const float *o
     }
     __syncthreads();
     if (threadIdx.x == 0) {
-        double S = 0.0, E = 0.0;
-        long long c = 0, n = 0;
-        float mn = INFINITY, mx = -INFINITY;
+        FinishTotals tot = {0.0, 0.0, 0, 0, INFINITY, -INFINITY};
         for (int w = 0; w < kTokWaves; ++w) {
-            S += s_sum[w];
-            E += s_ent[w];
-            c += s_clip[w];
-            n += s_neg[w];
-            mn = fminf(mn, s_min[w]);
-            mx = fmaxf(mx, s_max[w]);
+            tot.sum += s_sum[w];
+            tot.esum += s_ent[w];
+            tot.clip += s_clip[w];
+            tot.neg += s_neg[w];
+            tot.lo = fminf(tot.lo, s_min[w]);
+            tot.hi = fmaxf(tot.hi, s_max[w]);
         }
-        const float share = (float)(-(S * (double)hdr->inv_n));
-        *loss_out = accumulate ? *loss_out + share : share;
-        if (stats) {
-            a3po_stats o;
-            o.n_tokens = hdr->n_counted;
-            o.n_clipped = c;
-            o.n_bad_index = hdr->n_bad;
-            o.n_negative_staleness = n;
-            o.iw_min = mn;
-            o.iw_max = mx;
-            o.entropy_mean = (ent && hdr->n_counted > 0) ? (float)(E / (double)hdr->n_counted) : 0.0f;
-            o.reserved = 0.0f;
-            if (accumulate) {  // merge with what earlier micro-batches of the same update left
-                const a3po_stats p = *stats;
-                const long long tot = p.n_tokens + o.n_tokens;
-                o.entropy_mean = (ent && tot > 0)
-                                     ? (float)(((double)p.entropy_mean * (double)p.n_tokens + E) / (double)tot)
-                                     : 0.0f;
-                o.n_tokens = tot;
-                o.n_clipped += p.n_clipped;
-                o.n_bad_index += p.n_bad_index;
-                o.n_negative_staleness += p.n_negative_staleness;
-                o.iw_min = fminf(o.iw_min, p.iw_min);
-                o.iw_max = fmaxf(o.iw_max, p.iw_max);
-            }
-            *stats = o;
+        if (partial) partial[blockIdx.x] = tot;
+        else write_loss_and_stats(tot, ent != nullptr, hdr, loss_out, stats, accumulate);
+    }
+}
+
+// Long batches: the kernel above runs on several workgroups (workgroup b over tokens [b, b+1) * per_block,
+// totals to the scratch area); this one adds the workgroups' totals in a fixed tree and writes loss and statistics.
+__global__ __launch_bounds__(kTokMaxBlocks) void loss_finish_final_kernel(const FinishTotals *partial, int nblocks,
+                                                                         int have_entropy, const WsHeader *hdr,
+                                                                         float *loss_out, a3po_stats *stats,
+                                                                         int accumulate)
+{
+    __shared__ FinishTotals s_tot[kTokMaxBlocks / kWave];
+    FinishTotals t = {0.0, 0.0, 0, 0, INFINITY, -INFINITY};
+    if ((int)threadIdx.x < nblocks) t = partial[threadIdx.x];
+#pragma unroll
+    for (int off = kWave / 2; off > 0; off >>= 1) {
+        t.sum += __shfl_xor(t.sum, off, kWave);
+        t.esum += __shfl_xor(t.esum, off, kWave);
+        t.clip += __shfl_xor(t.clip, off, kWave);
+        t.neg += __shfl_xor(t.neg, off, kWave);
+        t.lo = fminf(t.lo, __shfl_xor(t.lo, off, kWave));
+        t.hi = fmaxf(t.hi, __shfl_xor(t.hi, off, kWave));
+    }
+    if ((threadIdx.x & (kWave - 1)) == 0) s_tot[threadIdx.x / kWave] = t;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        FinishTotals tot = {0.0, 0.0, 0, 0, INFINITY, -INFINITY};
+        for (int w = 0; w < kTokMaxBlocks / kWave; ++w) {
+            tot.sum += s_tot[w].sum;
+            tot.esum += s_tot[w].esum;
+            tot.clip += s_tot[w].clip;
+            tot.neg += s_tot[w].neg;
+            tot.lo = fminf(tot.lo, s_tot[w].lo);
+            tot.hi = fmaxf(tot.hi, s_tot[w].hi);
         }
+        write_loss_and_stats(tot, have_entropy != 0, hdr, loss_out, stats, accumulate);
     }
 }
 
@@ -284,12 +426,39 @@ __global__ void grpo_advantages_kernel(const float *rewards, int64_t S, int32_t 
     adv[t] = (float)(((double)rewards[s] - mu) / (sqrt(var) + (double)eps_adv));
 }
 
+// Workgroups of the O(T) kernels and the tokens each takes: one workgroup up to kTokBlockTokens tokens, else one per
+// kTokBlockTokens up to the kTokMaxBlocks partials the scratch area holds, beyond that equal shares of the batch.
+struct TokSplit {
+    int blocks;
+    int64_t per_block;
+};
+static TokSplit tok_split(int64_t T)
+{
+    const int64_t want = (T + kTokBlockTokens - 1) / kTokBlockTokens;
+    TokSplit sp;
+    sp.blocks = (int)(want < 1 ? 1 : (want > kTokMaxBlocks ? kTokMaxBlocks : want));
+    sp.per_block = T > 0 ? (T + sp.blocks - 1) / sp.blocks : 1;
+    return sp;
+}
+
 hipError_t launch_loss_prep(const LossArgs &a, hipStream_t s)
 {
-    hipLaunchKernelGGL(loss_prep_kernel, dim3(1), dim3(kTokThreads), 0, s, a.chosen, a.mask, a.lb,
-                       a.prox_mode == A3PO_PROX_INTERP ? a.versions : nullptr, a.adv,
-                       a.prox_mode == A3PO_PROX_GIVEN ? a.prox_in : nullptr, a.T, a.V, a.denom, a.denom_dev,
-                       reinterpret_cast<WsHeader *>(a.ws_header), a.ws_records);
+    const int32_t *ver = a.prox_mode == A3PO_PROX_INTERP ? a.versions : nullptr;
+    const float *prox = a.prox_mode == A3PO_PROX_GIVEN ? a.prox_in : nullptr;
+    const TokSplit sp = tok_split(a.T);
+    const int nb = sp.blocks;
+    if (nb == 1) {
+        hipLaunchKernelGGL(loss_prep_kernel, dim3(1), dim3(kTokThreads), 0, s, a.chosen, a.mask, a.lb, ver, a.adv, prox,
+                           a.T, a.V, a.denom, a.denom_dev, reinterpret_cast<WsHeader *>(a.ws_header), a.ws_records);
+        return hipGetLastError();
+    }
+    PrepPartial *part = reinterpret_cast<PrepPartial *>(a.ws_scratch);
+    hipLaunchKernelGGL(loss_prep_records_kernel, dim3(nb), dim3(kTokThreads), 0, s, a.chosen, a.mask, a.lb, ver, a.adv,
+                       prox, a.T, a.V, a.ws_records, part, sp.per_block);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(loss_prep_header_kernel, dim3(1), dim3(kTokMaxBlocks), 0, s, part, nb, a.denom, a.denom_dev,
+                       reinterpret_cast<WsHeader *>(a.ws_header));
     return hipGetLastError();
 }
 
@@ -310,9 +479,16 @@ hipError_t launch_reset_row_queue(void *ws_header, hipStream_t s)
 
 hipError_t launch_loss_finish(const LossArgs &a, hipStream_t s)
 {
-    hipLaunchKernelGGL(loss_finish_kernel, dim3(1), dim3(kTokThreads), 0, s, a.ws_obj, a.ws_iw, a.ws_flags, a.ent_out,
-                       a.T, reinterpret_cast<const WsHeader *>(a.ws_header), a.loss_out, a.stats_out, a.iw_out,
-                       a.clipped_out, a.accumulate);
+    const WsHeader *hdr = reinterpret_cast<const WsHeader *>(a.ws_header);
+    const TokSplit sp = tok_split(a.T);
+    const int nb = sp.blocks;
+    FinishTotals *part = nb == 1 ? nullptr : reinterpret_cast<FinishTotals *>(a.ws_scratch);
+    hipLaunchKernelGGL(loss_finish_kernel, dim3(nb), dim3(kTokThreads), 0, s, a.ws_obj, a.ws_iw, a.ws_flags, a.ent_out,
+                       a.T, hdr, a.loss_out, a.stats_out, a.iw_out, a.clipped_out, a.accumulate, part, sp.per_block);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || nb == 1) return e;
+    hipLaunchKernelGGL(loss_finish_final_kernel, dim3(1), dim3(kTokMaxBlocks), 0, s, part, nb, a.ent_out != nullptr, hdr,
+                       a.loss_out, a.stats_out, a.accumulate);
     return hipGetLastError();
 }
 

@@ -229,3 +229,40 @@ def test_ex_host_validation(a3po):
     with pytest.raises(a3po.A3poError) as e:
         run_ex(a3po, c, no_versions=True, want_iw=True)            # interpolation needs versions
     assert e.value.code == -1
+
+
+# ---------------------------------------------------------------------------- batches of many tokens
+
+@pytest.mark.parametrize("S,L", [(4, 512), (3, 683), (4, 2500), (60, 1001), (200, 3001)])
+def test_long_batches_of_short_rows(a3po, S, L):
+    """The per-token kernels before and after the row pass split a long batch over several workgroups
+    (one up to 2048 tokens, one per 2048 up to 256 of them, equal shares beyond): token counts, statistics,
+    per-token outputs and the loss must not depend on where the cuts fall.  Rows are short so that the oracle
+    covers every token; the last case has more than 256 * 2048 tokens."""
+    w = synth.WORKLOADS["tiny"].scaled(V=48, S=S, L=L, G=3 if S == 3 else 4, len_lo=max(1, L // 3), len_hi=L,
+                                       noise_std=0.3, stale_max=6)
+    c = make_case(w)
+    T = c["T"]
+    assert T == S * L
+    c["chosen"][[0, T // 2, T - 1]] = [-1, w.V, w.V + 7]           # bad ids in the first, a middle and the last cut
+    c["mask"][[0, T // 2, T - 1]] = 1
+    c["versions"][[1, T - 2]] = CUR + 2                               # negative staleness at both ends
+    c["mask"][[1, T - 2]] = 1
+    out = run_ex(a3po, c, want_entropy=True, want_iw=True, want_clipped=True)
+    ref, st, _ = check_against_oracle(a3po, c, out, rows=np.r_[0:8, T // 2 - 4:T // 2 + 4, T - 8:T])
+    assert st["n_bad_index"] == 3 and st["n_negative_staleness"] >= 2
+    sur = oracle.surrogate(ref["logp"], c["lb"], c["versions"], CUR, c["adv"], ref["eff_mask"], w.clip_eps)
+    counted = ref["eff_mask"] == 1
+    iw = out["iw"].cpu().numpy()
+    assert (iw[~counted] == 0).all()
+    assert (np.abs(iw[counted] - sur["iw"][counted]) <= 1e-5 * sur["iw"][counted] + 1e-6).all()
+    clipped = out["clipped"].cpu().numpy()
+    assert int(clipped.sum()) == st["n_clipped"] and not clipped[~counted].any()
+    band = (np.abs(sur["r"] - 1.2) < 1e-4) | (np.abs(sur["r"] - 0.8) < 1e-4)
+    assert np.array_equal(clipped[counted & ~band], (sur["clipped"][counted & ~band] != 0).astype(np.uint8))
+    H_ref = oracle.entropy(c["z"], V=w.V) * ref["eff_mask"]
+    n = max(1, int(counted.sum()))
+    assert abs(st["entropy_mean"] - H_ref.sum() / n) <= 1e-5 * H_ref.sum() / n + 2e-5 * (1 + np.abs(ref["lse"]).max())
+    # fixed summation order within and across workgroups: a second run gives the same bits
+    again = run_ex(a3po, c, want_entropy=True)
+    assert torch.equal(again["loss"], out["loss"])
