@@ -297,12 +297,22 @@ __device__ __forceinline__ int opaque(int x)
 
 struct BurstShape {
     int nvec_row;    // 16-byte vectors per shard row (the last one may be partial)
+    int align;       // 1: a row's slots start at the 128-byte line that holds its first vector (see below)
+    int slots_row;   // slots per row: nvec_row, or with align nvec_row + 7 rounded up to a multiple of 8
     int rows;        // rows per item (1 when a row is cut into chunks)
     int chunks;      // column chunks per row
-    int chunk_vec;   // vectors per chunk
-    uint32_t magic;  // floor(2^32 / nvec_row) + 1: i / nvec_row == umulhi(i, magic) for i, nvec_row < 2^16
+    int chunk_vec;   // slots per chunk (a multiple of 8 with align)
+    uint32_t magic;  // floor(2^32 / slots_row) + 1: i / slots_row == umulhi(i, magic) for i, slots_row < 2^16
     int64_t items;
 };
+// Slots and alignment.  A thread's k-th vector is slot k * 1024 + tid of the item, so a wavefront's store covers 64
+// consecutive slots.  A column slice of a wider matrix starts where its column offset puts it - for a 1/8 shard of
+// 151,936 bf16 columns at a multiple of 32 bytes only - and stores that straddle 128-byte lines cost 7 % of the
+// bandwidth.  With `align`, slot 0 of a row is the vector at the start of the line that holds the row's first
+// vector: up to 7 leading slots (the row's phase, from the gradient's address) and the slots past the row's end are
+// idle, and every wavefront's 64 slots cover whole lines.  Narrow rows, where idle slots would outnumber the gain,
+// keep slot = vector.
+constexpr int kBurstAlignMinVec = 128;
 
 // SINGLE: an item is one row (or one column chunk of a row): no index divisions in the bursts.
 template <typename DT, bool SINGLE>
@@ -320,16 +330,24 @@ __global__ __launch_bounds__(kBurstThreads) void shard_bwd_burst_kernel(
     const size_t row_bytes = (size_t)ld * DT::kBytes;
     const float inv_n = hdr->inv_n;
     const int rem = (int)(Vs % EPV);  // elements of the partial last vector of a row (0 = none)
+    // phase of row r, in vectors: ((address of the gradient's row r) / 16) mod 8 = (phase_base + r * phase_step) mod 8
+    const int phase_base = sh.align ? (int)((reinterpret_cast<uintptr_t>(dz) >> 4) & 7) : 0;
+    const int phase_step = sh.align ? (int)((row_bytes >> 4) & 7) : 0;
     int par = 0;
 
     int64_t item = blockIdx.x;
     while (item < sh.items) {
         const int64_t r0 = (item / sh.chunks) * sh.rows;
         const int chunk = (int)(item % sh.chunks);
-        const int c0 = chunk * sh.chunk_vec;                          // first vector column of the item
-        const int cw = min(sh.chunk_vec, sh.nvec_row - c0);           // vector columns of the item
+        const int c0 = chunk * sh.chunk_vec;                          // first slot column of the item
+        const int cw = min(sh.chunk_vec, sh.slots_row - c0);          // slot columns of the item
         const int nrows = (int)min((int64_t)sh.rows, T - r0);
         const int nvec = nrows * cw;
+        const int phase0 = (phase_base + (int)(r0 & 7) * phase_step) & 7;
+        // slot i of the item -> row r (relative) and vector column c of that row (outside [0, nvec_row): idle)
+#define A3PO_BURST_SLOT(i, r, c)                                              \
+    const int r = SINGLE ? 0 : (int)__umulhi((uint32_t)(i), sh.magic);          \
+    const int c = c0 + ((i) - r * cw) - ((phase0 + r * phase_step) & 7)
         if (tid == 0) s_next[par] = atomicAdd(queue, 1u);
         if (tid < nrows) {
             const int64_t row = r0 + tid;
@@ -366,8 +384,9 @@ __global__ __launch_bounds__(kBurstThreads) void shard_bwd_burst_kernel(
         uint32_t live = 0;
 #pragma unroll
         for (int k = 0; k < kBurstVec; ++k) {
-            const int i = k * kBurstThreads + tid;
-            if (i < nvec && s_negg[par][SINGLE ? 0 : (int)__umulhi((uint32_t)i, sh.magic)] != 0.0f) live |= 1u << k;
+            const int i = opaque(k * kBurstThreads + tid);
+            A3PO_BURST_SLOT(i, r, c);
+            if (i < nvec && (unsigned)c < (unsigned)sh.nvec_row && s_negg[par][r] != 0.0f) live |= 1u << k;
         }
         // ---- the read burst (row and column of a vector are recomputed rather than kept in registers) ----
         uint4 v[kBurstVec];
@@ -375,7 +394,7 @@ __global__ __launch_bounds__(kBurstThreads) void shard_bwd_burst_kernel(
         for (int k = 0; k < kBurstVec; ++k) {
             if (live >> k & 1u) {
                 const int i = opaque(k * kBurstThreads + tid);
-                const int r = SINGLE ? 0 : (int)__umulhi((uint32_t)i, sh.magic), c = c0 + (i - r * cw);
+                A3PO_BURST_SLOT(i, r, c);
                 v[k] = stream_load(reinterpret_cast<const char *>(z) + (size_t)(r0 + r) * row_bytes + (size_t)c * 16);
             }
         }
@@ -387,7 +406,8 @@ __global__ __launch_bounds__(kBurstThreads) void shard_bwd_burst_kernel(
         for (int k = 0; k < kBurstVec; ++k) {
             const int i = opaque(k * kBurstThreads + tid);
             if (i >= nvec) continue;
-            const int r = SINGLE ? 0 : (int)__umulhi((uint32_t)i, sh.magic), c = c0 + (i - r * cw);
+            A3PO_BURST_SLOT(i, r, c);
+            if ((unsigned)c >= (unsigned)sh.nvec_row) continue;
             const float neg_g = s_negg[par][r];
             char *dst = reinterpret_cast<char *>(dz) + (size_t)(r0 + r) * row_bytes + (size_t)c * 16;
             float f[EPV];
@@ -413,6 +433,7 @@ __global__ __launch_bounds__(kBurstThreads) void shard_bwd_burst_kernel(
                 stream_store(dst, pack<DT>(f));
             }
         }
+#undef A3PO_BURST_SLOT
         par ^= 1;
         item = next;
     }
@@ -474,16 +495,19 @@ static BurstShape burst_shape(int64_t T, int64_t Vs, int64_t esz)
     const int64_t cap = (int64_t)(esz == 4 ? BurstVec<F32>::value : BurstVec<Bf16>::value) * kBurstThreads;
     BurstShape sh;
     sh.nvec_row = (int)((Vs * esz + 15) / 16);
-    if (sh.nvec_row <= cap) {
-        sh.rows = (int)(cap / sh.nvec_row < kBurstThreads ? cap / sh.nvec_row : kBurstThreads);
+    sh.align = sh.nvec_row >= kBurstAlignMinVec;
+    sh.slots_row = sh.align ? (sh.nvec_row + 7 + 7) / 8 * 8 : sh.nvec_row;
+    if (sh.slots_row <= cap) {
+        sh.rows = (int)(cap / sh.slots_row < kBurstThreads ? cap / sh.slots_row : kBurstThreads);
         sh.chunks = 1;
-        sh.chunk_vec = sh.nvec_row;
-    } else {
+        sh.chunk_vec = sh.slots_row;
+    } else {  // (only rows wide enough to be aligned get here)
         sh.rows = 1;
-        sh.chunks = (int)((sh.nvec_row + cap - 1) / cap);
-        sh.chunk_vec = (sh.nvec_row + sh.chunks - 1) / sh.chunks;
+        const int chunks = (int)((sh.slots_row + cap - 1) / cap);
+        sh.chunk_vec = ((sh.slots_row + chunks - 1) / chunks + 7) / 8 * 8;  // <= cap: cap is a multiple of 8
+        sh.chunks = (sh.slots_row + sh.chunk_vec - 1) / sh.chunk_vec;
     }
-    sh.magic = (uint32_t)((1ull << 32) / (uint64_t)sh.nvec_row + 1);  // nvec_row >= 2; used only when rows > 1 (then cw == nvec_row)
+    sh.magic = (uint32_t)((1ull << 32) / (uint64_t)sh.slots_row + 1);  // slots_row >= 2; used only when rows > 1 (then cw == slots_row)
     sh.items = ((T + sh.rows - 1) / sh.rows) * sh.chunks;
     return sh;
 }

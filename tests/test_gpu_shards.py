@@ -150,6 +150,56 @@ def test_contiguous_shards(a3po, dtype, V, bounds):
     check_merged(a3po, c, res)
 
 
+@pytest.mark.parametrize("dtype,V,pad,bounds", [
+    # column offsets at every kind of position inside a 128-byte line, a row stride that is not a multiple of
+    # 128 bytes (the position changes from row to row), a partial last vector
+    ("bf16", 9003, 5, [0, 1032, 3120, 5208, 9003]),
+    ("f32", 5000, 4, [0, 516, 1100, 5000]),
+    # a row of two column chunks that starts one vector into a line, next to a shard of one vector
+    ("bf16", 163856, 0, [0, 8, 163856]),
+    # row stride a multiple of 128 bytes: the same position in every row
+    ("bf16", 8192, 0, [0, 1096, 4112, 8192]),
+])
+def test_column_views_at_any_position_inside_a_cache_line(a3po, dtype, V, pad, bounds):
+    """The backward maps a wavefront's stores onto whole 128-byte lines of the gradient, whatever the column
+    offset and row stride of the view (shards of at least 128 vectors per row): every column must still be
+    written exactly once by its own shard, and nothing outside the view."""
+    w = synth.WORKLOADS["tiny"].scaled(V=V, dtype=dtype, S=4, L=40, len_lo=20, len_hi=40, sigma=3.0, boost=6.0,
+                                       boost_prob=0.5, noise_std=0.2, stale_max=5)
+    c = make_case(w, ld=V + pad)
+    T = c["T"]
+    c["chosen"][2] = bounds[1]
+    c["chosen"][3] = bounds[1] - 1
+    c["chosen"][4] = V - 1
+    fwd = oracle.token_logprobs(c["z"], c["chosen"], V=V)
+    c["lb"] = synth.behav_from_target(fwd["logp"], c["tk"]["noise"][:T])
+    z_buf = dev_logits(c["z"])                                   # [T, V + pad]
+    dz_buf = torch.full_like(z_buf, 5.0)
+    y = cu(c["chosen"])
+    P = len(bounds) - 1
+    parts = torch.empty((P, T, 4), dtype=torch.float32, device="cuda")
+    for p in range(P):
+        a3po.shard_partials(z_buf[:, bounds[p]:bounds[p + 1]], y, bounds[p], out=parts[p])
+    logp, lse, ent = a3po.shard_combine(parts, y, V, want_entropy=True)
+    outs = [a3po.shard_loss_bwd(z_buf[:, bounds[p]:bounds[p + 1]], bounds[p], V, y, logp, lse, cu(c["lb"]),
+                                cu(c["versions"]), CUR, cu(c["adv"]), cu(c["mask"]), w.clip_eps,
+                                dlogits=dz_buf[:, bounds[p]:bounds[p + 1]]) for p in range(P)]
+    torch.cuda.synchronize()
+    assert (dz_buf[:, V:].float() == 5.0).all(), "padding columns are not the library's to write"
+    assert not (dz_buf[:, :V].float() == 5.0).any()
+    res = dict(parts=parts, logp=logp, lse=lse, entropy=ent, outs=outs, dlogits=dz_buf[:, :V])
+    check_merged(a3po, c, res)
+    # one shard alone, into a buffer of its own: the neighbours' columns stay as they were
+    for p in range(P):
+        alone = torch.full_like(z_buf, 7.0)
+        a3po.shard_loss_bwd(z_buf[:, bounds[p]:bounds[p + 1]], bounds[p], V, y, logp, lse, cu(c["lb"]),
+                            cu(c["versions"]), CUR, cu(c["adv"]), cu(c["mask"]), w.clip_eps,
+                            dlogits=alone[:, bounds[p]:bounds[p + 1]])
+        torch.cuda.synchronize()
+        assert (alone[:, :bounds[p]].float() == 7.0).all() and (alone[:, bounds[p + 1]:].float() == 7.0).all()
+        assert torch.equal(alone[:, bounds[p]:bounds[p + 1]], dz_buf[:, bounds[p]:bounds[p + 1]])
+
+
 def test_in_place_and_bad_ids_and_variants(a3po):
     w = synth.WORKLOADS["tiny"].scaled(V=32000, S=4, L=16, len_lo=8, len_hi=16, noise_std=0.3)
     c = make_case(w, T=48)
