@@ -44,11 +44,13 @@ def packed_case(w, n_prompt=3):
                 seq_len=np.asarray(seq_len, dtype=np.int64), off=off, T=len(rows))
 
 
-@pytest.mark.parametrize("dtype,V,budget,n_mb", [("f32", 8000, 160, 4), ("bf16", 151936, 24, 2), ("f32", 1001, 50, 3)])
-def test_microbatches_add_up_to_the_minibatch(a3po, dtype, V, budget, n_mb):
-    big = V > 100000
-    w = synth.WORKLOADS["tiny"].scaled(V=V, dtype=dtype, S=16, L=12 if big else 64, G=4, len_lo=4 if big else 10,
-                                       len_hi=12 if big else 64, noise_std=0.3, sigma=3.0, stale_max=6)
+@pytest.mark.parametrize("dtype,V,budget,n_mb,L", [
+    ("f32", 8000, 160, 4, 64), ("bf16", 151936, 24, 2, 12), ("f32", 1001, 50, 3, 64),
+    ("f32", 64, 5000, 2, 1500),     # micro-batches of several thousand tokens: the per-token kernels run on several workgroups
+])
+def test_microbatches_add_up_to_the_minibatch(a3po, dtype, V, budget, n_mb, L):
+    w = synth.WORKLOADS["tiny"].scaled(V=V, dtype=dtype, S=16, L=L, G=4, len_lo=max(4, L // 6), len_hi=L,
+                                       noise_std=0.3, sigma=3.0, stale_max=6)
     c = packed_case(w)
     first, owner = a3po.plan_microbatches(c["seq_len"], n_mb, budget)
     assert len(owner) > n_mb, "the case must actually split mini-batches into several micro-batches"
