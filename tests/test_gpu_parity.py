@@ -368,10 +368,12 @@ def test_two_streams_with_their_own_workspaces(a3po):
             assert torch.equal(o[k].view(torch.uint8), r[k].view(torch.uint8)), k
 
 
-def test_graph_capture_and_replay(a3po):
+@pytest.mark.parametrize("V,L,T", [(32000, 256, 384),
+                                   (512, 1500, 6000)])   # the per-token kernels on several workgroups
+def test_graph_capture_and_replay(a3po, V, L, T):
     # nothing in the call allocates or synchronises, so it can be recorded into a HIP graph; every replay must
     # reproduce the eager result, also after the inputs changed in place between replays
-    c = make_case(synth.WORKLOADS["tiny"], T=384)
+    c = make_case(synth.WORKLOADS["tiny"].scaled(V=V, L=L, len_lo=L // 4, len_hi=L), T=T)
     z = dev_logits(c["z"])
     y, lb, ver = torch.from_numpy(c["chosen"]).cuda(), torch.from_numpy(c["lb"]).cuda(), torch.from_numpy(c["versions"]).cuda()
     adv, m = torch.from_numpy(c["adv"]).cuda(), torch.from_numpy(c["mask"]).cuda()
