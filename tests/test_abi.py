@@ -209,3 +209,67 @@ def test_microbatch_planner_against_reference_and_invariants(lib):
             a3po.plan_microbatches([1, 2], **bad)
     with pytest.raises(a3po.A3poError):
         a3po.plan_microbatches([1, -2], 1, 5)
+
+
+C_PROGRAM = r"""
+#include <stddef.h>
+#include <stdio.h>
+#include <string.h>
+#include "a3po.h"
+
+int main(void)
+{
+    /* host-only entry points: nothing here touches a GPU */
+    const int64_t seq_len[5] = {7, 3, 9, 0, 4};
+    int64_t first[8];
+    int32_t owner[7];
+    int64_t n = -1;
+    a3po_loss_options opt;
+    a3po_stats st;
+    memset(&opt, 0, sizeof opt);
+    memset(&st, 0, sizeof st);
+    if (a3po_plan_microbatches(seq_len, 5, 2, 10, first, owner, 7, &n) != A3PO_OK) return 1;
+    printf("micro %lld:", (long long)n);
+    for (int64_t i = 0; i <= n; ++i) printf(" %lld", (long long)first[i]);
+    printf("\n");
+    printf("ws %zu\n", a3po_workspace_bytes(A3PO_WS_LOSS_FWD_BWD, 1000, 32000, 0));
+    printf("err %s\n", a3po_strerror(A3PO_E_WORKSPACE));
+    /* a null logits pointer is refused on the host, before any launch */
+    printf("null %d\n", a3po_token_logprobs(NULL, A3PO_BF16, 4, 64, 64, NULL, NULL, NULL, NULL, NULL));
+    printf("sizes %zu %zu %zu\n", sizeof(a3po_stats), sizeof(a3po_shard_partial), sizeof(a3po_loss_options));
+    printf("offsets %zu %zu %zu %zu\n", offsetof(a3po_stats, iw_min), offsetof(a3po_stats, entropy_mean),
+           offsetof(a3po_loss_options, logp_prox_in), offsetof(a3po_loss_options, denom_dev));
+    return (int)(opt.accumulate + st.n_tokens);
+}
+"""
+
+
+def test_header_is_plain_c_and_the_library_links_from_c(lib, tmp_path):
+    """include/a3po.h compiles as strict C99 and a C program linked against the library gets the same answers
+    as the Python binding (planner, workspace size, error strings, host-side validation)."""
+    import shutil
+    import subprocess
+
+    import numpy as np
+    import paper_2512_06547_amd as a3po
+    cc = shutil.which("gcc") or shutil.which("cc")
+    if cc is None:
+        pytest.skip("no C compiler")
+    src = tmp_path / "use_a3po.c"
+    src.write_text(C_PROGRAM)
+    exe = tmp_path / "use_a3po"
+    libdir = os.path.dirname(a3po.lib_path())
+    subprocess.run([cc, "-std=c99", "-pedantic", "-Wall", "-Wextra", "-Werror", "-I", os.path.join(ROOT, "include"),
+                    str(src), "-o", str(exe), "-L", libdir, "-la3po", f"-Wl,-rpath,{libdir}", "-Wl,-rpath,/opt/rocm/lib"],
+                   check=True, capture_output=True, text=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True, timeout=120).stdout.splitlines()
+    first, owner = a3po.plan_microbatches(np.array([7, 3, 9, 0, 4], dtype=np.int64), 2, 10)
+    assert out[0] == f"micro {len(owner)}: " + " ".join(str(int(x)) for x in first)
+    assert out[1] == f"ws {a3po.workspace_bytes(1000, 32000)}"
+    assert out[2] == "err " + lib.a3po_strerror(-5).decode()
+    assert out[3] == "null -1"
+    # struct layouts as the binding mirrors them
+    B = a3po.binding
+    assert out[4] == f"sizes {B.STATS_DTYPE.itemsize} 16 {ctypes.sizeof(B.LossOptions)}"
+    assert out[5] == (f"offsets {B.STATS_DTYPE.fields['iw_min'][1]} {B.STATS_DTYPE.fields['entropy_mean'][1]} "
+                      f"{B.LossOptions.logp_prox_in.offset} {B.LossOptions.denom_dev.offset}")
