@@ -9,19 +9,21 @@ namespace a3po {
 constexpr int kTokThreads = 1024;
 constexpr int kTokWaves = kTokThreads / kWave;
 
-// N = number of tokens with mask != 0 and a valid chosen id; header gets 1/N (or 1/denom).
-// Also packs each token's inputs into one 16-byte record for the row kernel (y = -1 when the
-// token does not enter the loss).
-__global__ __launch_bounds__(kTokThreads) void loss_prep_kernel(const int32_t *chosen, const uint8_t *mask,
-                                                                const float *lb, const int32_t *versions,
-                                                                const float *adv, const float *prox_in, int64_t T,
-                                                                int64_t V, float denom, const float *denom_dev,
-                                                                WsHeader *hdr, TokenRecord *records)
+// Counts of a range of tokens: those that enter the loss (mask != 0 and a valid chosen id), and those with
+// mask != 0 and an id outside [0, V).
+struct PrepPartial {
+    long long cnt, bad;
+};
+
+// Packs the inputs of tokens [t_begin, t_end) into one 16-byte record each for the row kernel (y = -1 when the
+// token does not enter the loss) and counts them; the totals of the workgroup are returned to thread 0.
+__device__ __forceinline__ PrepPartial pack_records(const int32_t *chosen, const uint8_t *mask, const float *lb,
+                                                    const int32_t *versions, const float *adv, const float *prox_in,
+                                                    int64_t t_begin, int64_t t_end, int64_t V, TokenRecord *records)
 {
-    if (denom_dev) denom = *denom_dev;
     __shared__ long long s_cnt[kTokWaves], s_bad[kTokWaves];
     long long cnt = 0, bad = 0;
-    for (int64_t t = threadIdx.x; t < T; t += kTokThreads) {
+    for (int64_t t = t_begin + threadIdx.x; t < t_end; t += kTokThreads) {
         const bool m = mask[t] != 0;
         const int32_t y = chosen[t];
         const bool ok = y >= 0 && (int64_t)y < V;
@@ -46,76 +48,57 @@ __global__ __launch_bounds__(kTokThreads) void loss_prep_kernel(const int32_t *c
         s_bad[wave] = bad;
     }
     __syncthreads();
+    PrepPartial p = {0, 0};
     if (threadIdx.x == 0) {
-        long long c = 0, b = 0;
         for (int w = 0; w < kTokWaves; ++w) {
-            c += s_cnt[w];
-            b += s_bad[w];
+            p.cnt += s_cnt[w];
+            p.bad += s_bad[w];
         }
-        const float n = denom > 0.0f ? denom : (float)c;
-        hdr->inv_n = n > 0.0f ? 1.0f / n : 0.0f;
-        hdr->n_as_float = n;
-        hdr->n_counted = c;
-        hdr->n_bad = b;
-        *row_queue_of(hdr) = 0u;  // the row kernel's work queue starts empty
     }
+    return p;
 }
 
-// The same for long batches, on several workgroups: workgroup b packs the records of tokens
-// [b, b+1) * per_block and leaves its two counts in the scratch area; a one-workgroup kernel adds the
-// counts (integers: any order) and writes the header.
-struct PrepPartial {
-    long long cnt, bad;
-};
+// Header of a call: 1/N with N the number of counted tokens, or the caller's denominator when it is positive;
+// the counts for the statistics; the row kernel's work queue starts empty.
+__device__ __forceinline__ void write_header(PrepPartial total, float denom, WsHeader *hdr)
+{
+    const float n = denom > 0.0f ? denom : (float)total.cnt;
+    hdr->inv_n = n > 0.0f ? 1.0f / n : 0.0f;
+    hdr->n_as_float = n;
+    hdr->n_counted = total.cnt;
+    hdr->n_bad = total.bad;
+    *row_queue_of(hdr) = 0u;
+}
 
+// One workgroup does both (batches of up to kTokBlockTokens tokens).
+__global__ __launch_bounds__(kTokThreads) void loss_prep_kernel(const int32_t *chosen, const uint8_t *mask,
+                                                                const float *lb, const int32_t *versions,
+                                                                const float *adv, const float *prox_in, int64_t T,
+                                                                int64_t V, float denom, const float *denom_dev,
+                                                                WsHeader *hdr, TokenRecord *records)
+{
+    const PrepPartial total = pack_records(chosen, mask, lb, versions, adv, prox_in, 0, T, V, records);
+    if (threadIdx.x == 0) write_header(total, denom_dev ? *denom_dev : denom, hdr);
+}
+
+// Long batches: workgroup b packs the records of tokens [b, b+1) * per_block and leaves its counts in the
+// scratch area; a one-workgroup kernel adds the counts (integers: any order) and writes the header.
 __global__ __launch_bounds__(kTokThreads) void loss_prep_records_kernel(const int32_t *chosen, const uint8_t *mask,
                                                                         const float *lb, const int32_t *versions,
                                                                         const float *adv, const float *prox_in,
                                                                         int64_t T, int64_t V, TokenRecord *records,
                                                                         PrepPartial *partial, int64_t per_block)
 {
-    __shared__ long long s_cnt[kTokWaves], s_bad[kTokWaves];
-    long long cnt = 0, bad = 0;
-    const int64_t t_end = min(T, ((int64_t)blockIdx.x + 1) * per_block);
-    for (int64_t t = (int64_t)blockIdx.x * per_block + threadIdx.x; t < t_end; t += kTokThreads) {
-        const bool m = mask[t] != 0;
-        const int32_t y = chosen[t];
-        const bool ok = y >= 0 && (int64_t)y < V;
-        cnt += (m && ok) ? 1 : 0;
-        bad += (m && !ok) ? 1 : 0;
-        TokenRecord r;
-        r.y = (m && ok) ? y : -1;
-        r.ver = prox_in ? __float_as_int(prox_in[t]) : (versions ? versions[t] : 0);
-        r.lb = lb[t];
-        r.A = adv[t];
-        records[t] = r;
-    }
-#pragma unroll
-    for (int off = kWave / 2; off > 0; off >>= 1) {
-        cnt += __shfl_xor(cnt, off, kWave);
-        bad += __shfl_xor(bad, off, kWave);
-    }
-    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
-    if (lane == 0) {
-        s_cnt[wave] = cnt;
-        s_bad[wave] = bad;
-    }
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        PrepPartial p = {0, 0};
-        for (int w = 0; w < kTokWaves; ++w) {
-            p.cnt += s_cnt[w];
-            p.bad += s_bad[w];
-        }
-        partial[blockIdx.x] = p;
-    }
+    const int64_t t_begin = (int64_t)blockIdx.x * per_block;
+    const PrepPartial p =
+        pack_records(chosen, mask, lb, versions, adv, prox_in, t_begin, min(T, t_begin + per_block), V, records);
+    if (threadIdx.x == 0) partial[blockIdx.x] = p;
 }
 
 __global__ __launch_bounds__(kTokMaxBlocks) void loss_prep_header_kernel(const PrepPartial *partial, int nblocks,
                                                                         float denom, const float *denom_dev,
                                                                         WsHeader *hdr)
 {
-    if (denom_dev) denom = *denom_dev;
     __shared__ long long s_cnt[kTokMaxBlocks / kWave], s_bad[kTokMaxBlocks / kWave];
     long long cnt = 0, bad = 0;
     if ((int)threadIdx.x < nblocks) {
@@ -134,17 +117,12 @@ __global__ __launch_bounds__(kTokMaxBlocks) void loss_prep_header_kernel(const P
     }
     __syncthreads();
     if (threadIdx.x == 0) {
-        long long c = 0, b = 0;
+        PrepPartial total = {0, 0};
         for (int w = 0; w < kTokMaxBlocks / kWave; ++w) {
-            c += s_cnt[w];
-            b += s_bad[w];
+            total.cnt += s_cnt[w];
+            total.bad += s_bad[w];
         }
-        const float n = denom > 0.0f ? denom : (float)c;
-        hdr->inv_n = n > 0.0f ? 1.0f / n : 0.0f;
-        hdr->n_as_float = n;
-        hdr->n_counted = c;
-        hdr->n_bad = b;
-        *row_queue_of(hdr) = 0u;  // the row kernel's work queue starts empty
+        write_header(total, denom_dev ? *denom_dev : denom, hdr);
     }
 }
 
