@@ -1,7 +1,10 @@
 """GPU parity at the full sizes of the named workloads (32,768 and 131,072 rows of 151,936 bf16
 logits), in the launch configuration the benchmark times: every token's log-prob, the loss, the
 statistics, and a sample of gradient rows are compared with the CPU oracle; rows are generated
-chunk by chunk (counter-based generator), so the host never holds the whole matrix.
+chunk by chunk (counter-based generator), so the host never holds the whole matrix.  Two of the
+workloads then go through the vocabulary-sharded entry points as eight column views of the same matrix:
+merged log-probs, loss and the sampled rows against the oracle, every gradient element against the fused
+kernel's.
 
 Tolerances are those of test_gpu_parity.py.
 """
@@ -26,7 +29,7 @@ def a3po():
     return lib
 
 
-def _run_full(a3po, name, n_sample, inplace):
+def _run_full(a3po, name, n_sample, inplace, shards=0):
     w = synth.WORKLOADS[name]
     tk = synth.token_arrays(w)
     T, V = w.T, w.V
@@ -92,12 +95,51 @@ def _run_full(a3po, name, n_sample, inplace):
     assert dead.any() and (~dead).any()
     print(f"{name}: T={T} counted={N} clipped={st['n_clipped']} (oracle {sur['stats']['n_clipped']}, "
           f"{int(near.sum())} in the boundary band) loss={loss:.6f} oracle={sur['loss']:.6f} rows checked={len(rows)}")
+    if shards:
+        # the same matrix as `shards` column views through the vocabulary-sharded entry points: merged log-probs
+        # against the oracle, the sampled gradient rows against the oracle, and EVERY gradient element against the
+        # fused kernel's (two bf16 roundings of fp32 values that differ in their last bits: one bf16 ulp apart at most)
+        assert not inplace and V % (8 * shards) == 0
+        Vs = V // shards
+        y_d, lb_d, ver_d, m_d = dev(tk["chosen"]), dev(lb), dev(tk["versions"]), dev(tk["mask"])
+        parts = torch.empty((shards, T, 4), dtype=torch.float32, device="cuda")
+        for p in range(shards):
+            a3po.shard_partials(z_d[:, p * Vs:(p + 1) * Vs], y_d, p * Vs, out=parts[p])
+        logp_s, lse_s, _ = a3po.shard_combine(parts, y_d, V)
+        dz_s = torch.full_like(z_d, 3.0)
+        ws = None
+        for p in range(shards):
+            o = a3po.shard_loss_bwd(z_d[:, p * Vs:(p + 1) * Vs], p * Vs, V, y_d, logp_s, lse_s, lb_d, ver_d, CUR, adv_d,
+                                    m_d, w.clip_eps, dlogits=dz_s[:, p * Vs:(p + 1) * Vs], workspace=ws)
+            ws = o["workspace"]
+        torch.cuda.synchronize()
+        err = np.abs(logp_s.cpu().numpy().astype(np.float64) - logp_ref)
+        assert (err <= 1e-5 * np.abs(logp_ref) + 1e-5).all(), err.max()
+        assert a3po.stats_to_dict(o["stats"])["n_tokens"] == N
+        loss_s = float(o["loss"].cpu()[0])
+        assert abs(loss_s - sur["loss"]) <= 1e-5 * abs(sur["loss"]) + 1e-5 * scale + slack, (loss_s, sur["loss"])
+        got_s = dz_s[torch.from_numpy(rows).cuda()].float().cpu().numpy().astype(np.float64)
+        e = np.abs(got_s - ref)
+        assert (e <= 2.0 ** -8 * np.abs(ref) + 1e-5 * gs + 1e-37).all(), "sharded gradient beyond one bf16 rounding"
+        # rows whose clip decision sits in the boundary band may take different branches on the two paths
+        g_abs = torch.from_numpy(np.where(near, np.inf, np.abs(sur["g"])).astype(np.float32)).cuda()
+        worst = 0.0
+        for r0 in range(0, T, 2048):
+            a = dz_s[r0:r0 + 2048].float()
+            b = out["dlogits"][r0:r0 + 2048].float()
+            bound = 2.0 ** -7 * b.abs() + (1e-5 * g_abs[r0:r0 + 2048]).unsqueeze(1)
+            bound = torch.nan_to_num(bound, nan=float("inf"))
+            excess = ((a - b).abs() - bound).max().item()
+            worst = max(worst, excess)
+        assert worst <= 0.0, f"sharded and fused gradients differ by more than one bf16 ulp somewhere ({worst:.3e})"
+        print(f"{name}: {shards} column views agree with the fused kernel on all {T}x{V} gradient elements")
+        del dz_s, parts
     del out, z_d
     torch.cuda.empty_cache()
 
 
 def test_1p5b_shape_full_size(a3po):
-    _run_full(a3po, "1p5b", 48, inplace=False)
+    _run_full(a3po, "1p5b", 48, inplace=False, shards=8)
 
 
 def test_8b_shape_full_size_in_place(a3po):
@@ -105,4 +147,4 @@ def test_8b_shape_full_size_in_place(a3po):
 
 
 def test_long_response_high_staleness_full_size(a3po):
-    _run_full(a3po, "long", 32, inplace=False)
+    _run_full(a3po, "long", 32, inplace=False, shards=8)
