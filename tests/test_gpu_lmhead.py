@@ -191,3 +191,98 @@ def test_fused_lmhead_loss_fwd_bwd_empty_batch(a3po):
     assert a3po.stats_to_dict(out["stats"])["n_tokens"] == 0
     assert out["dweight"].shape == (V, H) and not out["dweight"].any()
     assert out["dhidden"].numel() == 0
+
+
+def test_fused_lmhead_loss_fwd_bwd_full_size(a3po):
+    """The whole path from hidden states at the benchmark's size (65,536 tokens x hidden 4,096 x vocabulary
+    151,936, eight chunks of 8,192 tokens).  The oracle cannot run the projection for every token, so the case
+    is built to be checkable in full: every token is counted (the denominator is the whole batch), but only 24
+    tokens, three in each chunk, have a non-zero advantage.  Every other token then contributes exactly nothing to
+    the loss and to the gradients, whatever its log-prob is, and the oracle evaluates the 24 rows completely:
+    their log-probs, the loss, their rows of dh, and ALL of dW; the other 65,512 rows of dh must be exactly zero.
+    Error model as in test_fused_lmhead_loss_fwd_bwd."""
+    lw = synth.LMHEAD_WORKLOADS["lmhead8b"]
+    T, H, V = lw.tokens.T, lw.H, lw.tokens.V
+    assert (T, H, V) == (65536, 4096, 151936)
+    tk = synth.token_arrays(lw.tokens)
+    cur = synth.CURRENT_VERSION
+    h = synth.hidden_rows(lw, 0, T)
+    W = np.empty((V, H), dtype=np.uint16)
+    W_d = torch.empty((V, H), dtype=torch.bfloat16, device="cuda")
+    for v0 in range(0, V, 16384):
+        n = min(16384, V - v0)
+        W[v0:v0 + n] = synth.weight_rows(lw, v0, n)
+        W_d[v0:v0 + n].copy_(torch.from_numpy(W[v0:v0 + n]).view(torch.bfloat16))
+    r = np.random.default_rng(2512)
+    rows = np.sort(np.concatenate([c * 8192 + r.choice(8192, 3, replace=False) for c in range(8)]))
+    rows[0], rows[-1] = 0, T - 1
+    y = tk["chosen"].copy()
+    mask = np.ones(T, dtype=np.uint8)
+    ver = tk["versions"].copy()
+    adv = np.zeros(T, dtype=np.float32)
+    adv[rows] = r.choice([-1.0, 1.0], len(rows)) * (0.5 + r.random(len(rows)))
+
+    # oracle on the 24 rows, with the GPU path's staging (logits and gradient entries rounded once to bfloat16)
+    hs = h[rows]
+    z = oracle.lmhead_logits(hs, W)
+    zb, zr = _bf16_round(z)
+    fwd = oracle.token_logprobs(zb, y[rows].copy())
+    lb = np.full(T, -12.0, dtype=np.float32)
+    lb[rows] = synth.behav_from_target(fwd["logp"], (r.standard_normal(len(rows)) * 0.15).astype(np.float32))
+    ref = oracle.loss_fwd_bwd(zb, y[rows].copy(), lb[rows], ver[rows], cur, adv[rows], np.ones(len(rows), dtype=np.uint8),
+                              0.2, denom=float(T))
+    dzb, dzr = _bf16_round(ref["dz"])
+    z_abs = oracle.lmhead_logits(hs & 0x7FFF, W & 0x7FFF)
+    ulp = _bf16_ulp(z)
+    tie = np.abs(np.abs(z - zr) - 0.5 * ulp) <= H * 2.0 ** -24 * z_abs + 1e-300
+    p = np.exp(zr - ref["lse"][:, None])
+    k = np.arange(len(rows))
+    dev = (tie * p * ulp).sum(axis=1) + tie[k, y[rows]] * ulp[k, y[rows]]
+    direct = tie * np.abs(ref["g"])[:, None] * p * ulp
+    extra = direct + dev[:, None] * np.abs(dzr)
+    sur = oracle.surrogate(ref["logp"], lb[rows], ver[rows], cur, adv[rows], np.ones(len(rows), dtype=np.uint8), 0.2,
+                           float(T))
+    near = (np.abs(np.log(sur["r"]) - np.log(1.2)) < 1e-3 + dev) | (np.abs(np.log(sur["r"]) - np.log(0.8)) < 1e-3 + dev)
+    assert not near.all() and (ref["g"] != 0).any()
+
+    dev_ = lambda a: torch.from_numpy(a).cuda()
+    out = a3po.fused_lmhead_loss_fwd_bwd(dev_(h).view(torch.bfloat16), W_d, dev_(y), dev_(lb), dev_(ver), cur, dev_(adv),
+                                         dev_(mask), 0.2)
+    torch.cuda.synchronize()
+    st = a3po.stats_to_dict(out["stats"])
+    assert st["n_tokens"] == T and st["n_bad_index"] == 0
+    logp = out["logp"].cpu().numpy().astype(np.float64)
+    assert (np.abs(logp[rows] - ref["logp"]) <= 2e-5 + 1e-5 * np.abs(ref["logp"]) + dev).all()
+    assert np.isfinite(logp).all() and (logp <= 0).all()
+    loss = float(out["loss"].cpu()[0])
+    scale = np.abs(sur["obj"]).sum() / T
+    slack = (np.abs(sur["obj"]) * (dev + near * 0.5)).sum() / T
+    assert abs(loss - ref["loss"]) <= 1e-4 * scale + slack + 1e-9, (loss, ref["loss"])
+    assert abs(st["n_clipped"] - int(ref["stats"]["n_clipped"])) <= int(near.sum())
+
+    dh = out["dhidden"]
+    others = torch.ones(T, dtype=torch.bool, device="cuda")
+    others[dev_(rows)] = False
+    assert not dh[others].any(), "a token without advantage must leave its row of dh exactly zero"
+    hf, ha = synth.bf16_bits_to_f64(hs), synth.bf16_bits_to_f64(hs & 0x7FFF)
+    dh_ref, dh_abs, dh_tie = np.zeros((len(rows), H)), np.zeros((len(rows), H)), np.zeros((len(rows), H))
+    bad_w = 0
+    ok = ~near
+    for v0 in range(0, V, 16384):
+        v1 = min(V, v0 + 16384)
+        Wf, Wa = synth.bf16_bits_to_f64(W[v0:v1]), synth.bf16_bits_to_f64(W[v0:v1] & 0x7FFF)
+        dh_ref += dzr[:, v0:v1] @ Wf
+        dh_abs += np.abs(dzr[:, v0:v1]) @ Wa
+        dh_tie += extra[:, v0:v1] @ Wa
+        if ok.all():
+            dw_ref = dzr[:, v0:v1].T @ hf
+            bound = 2.0 ** -7 * np.abs(dw_ref) + 2.0 ** -8 * (np.abs(dzr[:, v0:v1]).T @ ha) + extra[:, v0:v1].T @ ha + 1e-30
+            dw = out["dweight"][v0:v1].float().cpu().numpy().astype(np.float64)
+            bad_w += int((np.abs(dw - dw_ref) > bound).sum())
+    got = dh[dev_(rows)].float().cpu().numpy().astype(np.float64)
+    bad_h = np.abs(got - dh_ref) > 2.0 ** -7 * np.abs(dh_ref) + 2.0 ** -8 * dh_abs + dh_tie + 1e-30
+    assert not bad_h[ok].any(), f"dh: {bad_h[ok].sum()} elements off"
+    assert bad_w == 0, f"dW: {bad_w} elements off"
+    assert np.abs(dh_ref).max() > 0
+    print(f"lmhead8b full size: loss {loss:.6e} (oracle {ref['loss']:.6e}), {int(near.sum())} of {len(rows)} sampled tokens "
+          f"in the clip band, dW compared on {'all' if ok.all() else 'no'} elements")
