@@ -284,5 +284,13 @@ def test_fused_lmhead_loss_fwd_bwd_full_size(a3po):
     assert not bad_h[ok].any(), f"dh: {bad_h[ok].sum()} elements off"
     assert bad_w == 0, f"dW: {bad_w} elements off"
     assert np.abs(dh_ref).max() > 0
+    # the forward-only kernel at the same size: fp32 logits on chip, so the 24 rows are compared with the
+    # un-rounded fp64 products; every other token must agree with the chunked path up to its bf16 staging
+    logp_f, lse_f = a3po.fused_lmhead_logprob(dev_(h).view(torch.bfloat16), W_d, dev_(y))
+    torch.cuda.synchronize()
+    exact = oracle.token_logprobs(z, y[rows].copy())
+    close(lse_f.cpu().numpy()[rows], exact["lse"], "lse (forward only, full size)")
+    close(logp_f.cpu().numpy()[rows], exact["logp"], "logp (forward only, full size)")
+    assert (logp_f - out["logp"]).abs().max().item() < 5e-2
     print(f"lmhead8b full size: loss {loss:.6e} (oracle {ref['loss']:.6e}), {int(near.sum())} of {len(rows)} sampled tokens "
           f"in the clip band, dW compared on {'all' if ok.all() else 'no'} elements")
