@@ -70,7 +70,7 @@ __device__ __forceinline__ void write_header(PrepPartial total, float denom, WsH
     *row_queue_of(hdr) = 0u;
 }
 
-// One workgroup does both (batches of up to kTokBlockTokens tokens).
+// One workgroup does both (short batches).
 __global__ __launch_bounds__(kTokThreads) void loss_prep_kernel(const int32_t *chosen, const uint8_t *mask,
                                                                 const float *lb, const int32_t *versions,
                                                                 const float *adv, const float *prox_in, int64_t T,
@@ -404,17 +404,20 @@ __global__ void grpo_advantages_kernel(const float *rewards, int64_t S, int32_t 
     adv[t] = (float)(((double)rewards[s] - mu) / (sqrt(var) + (double)eps_adv));
 }
 
-// Workgroups of the O(T) kernels and the tokens each takes: one workgroup up to kTokBlockTokens tokens, else one per
-// kTokBlockTokens up to the kTokMaxBlocks partials the scratch area holds, beyond that equal shares of the batch.
+// Workgroups of the O(T) kernels and the tokens each takes: one workgroup up to kTokSingleMax tokens (a second
+// launch for the partials costs more than it saves there: one workgroup takes about 4 us + 0.4 us per 1,000
+// tokens, the split pair about 11 us), else one per kTokBlockTokens up to the kTokMaxBlocks partials the scratch
+// area holds, beyond that equal shares of the batch.
+constexpr int64_t kTokSingleMax = 16384;
 struct TokSplit {
     int blocks;
     int64_t per_block;
 };
 static TokSplit tok_split(int64_t T)
 {
-    const int64_t want = (T + kTokBlockTokens - 1) / kTokBlockTokens;
+    const int64_t want = T <= kTokSingleMax ? 1 : (T + kTokBlockTokens - 1) / kTokBlockTokens;
     TokSplit sp;
-    sp.blocks = (int)(want < 1 ? 1 : (want > kTokMaxBlocks ? kTokMaxBlocks : want));
+    sp.blocks = (int)(want > kTokMaxBlocks ? kTokMaxBlocks : want);
     sp.per_block = T > 0 ? (T + sp.blocks - 1) / sp.blocks : 1;
     return sp;
 }

@@ -46,7 +46,7 @@ def packed_case(w, n_prompt=3):
 
 @pytest.mark.parametrize("dtype,V,budget,n_mb,L", [
     ("f32", 8000, 160, 4, 64), ("bf16", 151936, 24, 2, 12), ("f32", 1001, 50, 3, 64),
-    ("f32", 64, 5000, 2, 1500),     # micro-batches of several thousand tokens: the per-token kernels run on several workgroups
+    ("f32", 64, 20000, 2, 6000),    # micro-batches beyond 16,384 tokens: the per-token kernels run on several workgroups
 ])
 def test_microbatches_add_up_to_the_minibatch(a3po, dtype, V, budget, n_mb, L):
     w = synth.WORKLOADS["tiny"].scaled(V=V, dtype=dtype, S=16, L=L, G=4, len_lo=max(4, L // 6), len_hi=L,

@@ -233,13 +233,13 @@ def test_ex_host_validation(a3po):
 
 # ---------------------------------------------------------------------------- batches of many tokens
 
-@pytest.mark.parametrize("S,L", [(4, 512), (3, 683), (4, 2500), (60, 1001), (200, 3001)])
+@pytest.mark.parametrize("S,L", [(4, 512), (4, 4096), (5, 3277), (60, 1001), (200, 3001)])
 def test_long_batches_of_short_rows(a3po, S, L):
     """The per-token kernels before and after the row pass split a long batch over several workgroups
-    (one up to 2048 tokens, one per 2048 up to 256 of them, equal shares beyond): token counts, statistics,
+    (one up to 16,384 tokens, one per 2048 up to 256 of them, equal shares beyond): token counts, statistics,
     per-token outputs and the loss must not depend on where the cuts fall.  Rows are short so that the oracle
     covers every token; the last case has more than 256 * 2048 tokens."""
-    w = synth.WORKLOADS["tiny"].scaled(V=48, S=S, L=L, G=3 if S == 3 else 4, len_lo=max(1, L // 3), len_hi=L,
+    w = synth.WORKLOADS["tiny"].scaled(V=48, S=S, L=L, G=5 if S == 5 else 4, len_lo=max(1, L // 3), len_hi=L,
                                        noise_std=0.3, stale_max=6)
     c = make_case(w)
     T = c["T"]
