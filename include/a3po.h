@@ -294,7 +294,9 @@ int a3po_shard_combine(const a3po_shard_partial *partials, int32_t P, int64_t T,
 /* Loss and this shard's gradient slice from the merged log pi_theta and lse (both [T], as written by
  * a3po_shard_combine):  dlogits_shard[t, j] = g_t ([v0 + j == chosen[t]] - exp(z[t, j] - lse[t])).
  * Per-token arguments, loss_out, stats_out, workspace (A3PO_WS_LOSS_FWD_BWD size) and error codes as in
- * a3po_loss_fwd_bwd; dlogits_shard may alias logits_shard exactly.  opt (nullable): prox_mode,
+ * a3po_loss_fwd_bwd; dlogits_shard may alias logits_shard exactly.  Exactly the T x Vs elements of the
+ * slice are written: when the slice is a column range of a wider matrix, its neighbours' columns and the
+ * padding of the rows stay as they are.  opt (nullable): prox_mode,
  * logp_prox_in, iw_out and clipped_out are honoured; entropy_out and the events are ignored. */
 int a3po_shard_loss_bwd(const void *logits_shard, a3po_dtype dt, int64_t T, int64_t Vs, int64_t ld, int64_t v0,
                         int64_t V, const int32_t *chosen, const float *logp_theta, const float *lse,
