@@ -235,6 +235,28 @@ def test_infinite_staleness_limit_never_clips():
     assert o["stats"]["n_clipped"] == 0 and not o["clipped"].any()
 
 
+def test_contraction_of_the_ratio_with_staleness():
+    """Appendix A, contractive stability: r = w^alpha lies between 1 and w, so (r - 1)^2 <= (w - 1)^2 token by
+    token (the dominating function of the proof); on a fixed batch the second moment of r - 1 and the number
+    of clipped tokens do not grow with the staleness (Section 3.1), and both vanish in the limit."""
+    n = 4000
+    lt, lb = _random_logps(n)
+    A = rng.standard_normal(n)
+    w = np.exp(lt - lb)
+    ones = np.ones(n, np.uint8)
+    spread, clipped = [], []
+    for d in (1, 2, 3, 4, 8, 16, 64, 1024, 2 ** 20):
+        o = oracle.surrogate(lt, lb, np.full(n, 100 - d, dtype=np.int32), 100, A, ones, 0.2)
+        r = o["r"]
+        assert (np.minimum(1.0, w) * (1 - 1e-12) <= r).all() and (r <= np.maximum(1.0, w) * (1 + 1e-12)).all()
+        assert ((r - 1) ** 2 <= (w - 1) ** 2 * (1 + 1e-9) + 1e-15).all()
+        spread.append(((r - 1) ** 2).mean())
+        clipped.append(o["stats"]["n_clipped"])
+    assert spread[0] == pytest.approx(((w - 1) ** 2).mean(), rel=1e-12)      # d = 1: r = w
+    assert all(a >= b for a, b in zip(spread, spread[1:])) and spread[-1] < 1e-9
+    assert all(a >= b for a, b in zip(clipped, clipped[1:])) and clipped[0] > 0 and clipped[-1] == 0
+
+
 # ----------------------------------------------------------------------------- loss (Eq. 2) and stats
 
 def test_worked_tokens_of_eq2():
