@@ -176,6 +176,10 @@ def secondary_kernels(a3po, torch, w, b, adv, dz, ws, log, reps=10, shards=8):
         return e0.elapsed_time(e1) / reps
 
     res = {}
+    # the stand-alone interpolation of Eq. 3 / Eq. 4 on its own (the step the paper times, Section 4.2.1): O(T)
+    lt = a3po.token_logprobs(b["z"], b["chosen"], want_lse=False, want_chosen_logit=False)[0]
+    ms = timed(lambda: a3po.proximal_interp(b["lb"], lt, b["versions"], b["cur"], want_alpha=False))
+    res["proximal_interp"] = {"ms": ms, "tokens_per_s": T / ms * 1e3}
     ms = timed(lambda: a3po.token_logprobs(b["z"], b["chosen"], want_chosen_logit=False))
     res["token_logprobs"] = {"ms": ms, "gbs": T * row / ms / 1e6, "frac": T * row / ms / 1e6 / HBM_PEAK_GBS}
     ms = timed(lambda: a3po.token_logprobs(b["z"], b["chosen"], want_chosen_logit=False, want_entropy=True))
@@ -235,7 +239,7 @@ def secondary_kernels(a3po, torch, w, b, adv, dz, ws, log, reps=10, shards=8):
     res["minibatched_step"] = {"ms": ms, "calls": len(spans), "minibatches": len(mb_rows), "token_budget": 10240,
                                "tokens_per_s": T / ms * 1e3}
     for k, v in res.items():
-        log(f"{k}: {v['ms']:.3f} ms" + (f", {v['gbs']:.0f} GB/s" if "gbs" in v else f", {v['tokens_per_s'] / 1e6:.2f} M tokens/s"))
+        log(f"{k}: {v['ms']:.4f} ms" + (f", {v['gbs']:.0f} GB/s" if "gbs" in v else f", {v['tokens_per_s'] / 1e6:.2f} M tokens/s"))
     return res
 
 
