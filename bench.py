@@ -406,7 +406,7 @@ def main():
     dt, kavg, bytes_cfg, ach, st = head["dt"], head["kavg"], head["bytes"], head["gbs"], head["st"]
 
     # context only: a plain device copy of the same matrix (read + write), the practical ceiling
-    # of a mixed read/write stream on this box
+    # of a mixed read/write stream on this machine
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     for _ in range(3):
         dz.copy_(b["z"])
