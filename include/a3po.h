@@ -35,7 +35,12 @@
 extern "C" {
 #endif
 
-typedef enum { A3PO_F32 = 0, A3PO_BF16 = 1 } a3po_dtype;
+typedef enum {
+    A3PO_F32 = 0,
+    A3PO_BF16 = 1,
+    A3PO_DTYPE_INT_RANGE_ = 0x7fffffff /* not a dtype: makes every int a value of the type, so that an */
+                                       /* unknown code reaches the library's own check (A3PO_E_DTYPE) */
+} a3po_dtype;
 
 enum {
     A3PO_OK = 0,
