@@ -273,3 +273,35 @@ def test_header_is_plain_c_and_the_library_links_from_c(lib, tmp_path):
     assert out[4] == f"sizes {B.STATS_DTYPE.itemsize} 16 {ctypes.sizeof(B.LossOptions)}"
     assert out[5] == (f"offsets {B.STATS_DTYPE.fields['iw_min'][1]} {B.STATS_DTYPE.fields['entropy_mean'][1]} "
                       f"{B.LossOptions.logp_prox_in.offset} {B.LossOptions.denom_dev.offset}")
+
+
+def test_host_code_is_clean_under_address_and_undefined_behaviour_sanitizers(lib, tmp_path):
+    """The translation unit that holds the library's host logic (planner, workspace sizes, validation of every
+    entry point) is rebuilt with -fsanitize=address,undefined on the host side and linked with the other objects
+    as built; a driver compiled the same way runs 100,000 random plans into exactly-sized arrays and every
+    refusal path.  Device code is untouched (sanitizers are host-only here)."""
+    import glob
+    import subprocess
+    from paper_2512_06547_amd import build
+    clang = os.path.join(os.path.dirname(os.path.dirname(os.path.realpath(build.HIPCC))), "llvm", "bin", "clang")
+    others = [o for o in glob.glob(os.path.join(build.OBJ, "*.hip.o")) if not o.endswith("a3po_api.hip.o")]
+    if not os.path.exists(clang) or len(others) != len(build.SOURCES) - 1:
+        pytest.skip("needs ROCm's clang and the objects of an in-tree build")
+    san = ["-fsanitize=address", "-fsanitize=undefined", "-fno-omit-frame-pointer"]
+    host_san = [x for f in san for x in ("-Xarch_host", f)]
+    flags = [f for f in build.FLAGS if f != "-O3"] + ["-O1", "-g"]
+    api_o = str(tmp_path / "a3po_api.san.o")
+    subprocess.run([build.HIPCC, *flags, *host_san, "-c", os.path.join(build.CSRC, "a3po_api.hip"), "-o", api_o],
+                   check=True, capture_output=True)
+    rocm_lib = os.path.join(os.path.dirname(os.path.dirname(os.path.realpath(build.HIPCC))), "lib")
+    so = str(tmp_path / "liba3po.so")
+    subprocess.run([build.HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", *san[:2], "-o", so, api_o, *others,
+                    "-L", rocm_lib, "-lrocblas", f"-Wl,-rpath,{rocm_lib}"], check=True, capture_output=True)
+    exe = str(tmp_path / "host_sanitize")
+    subprocess.run([clang, "-std=c99", "-g", *san, "-I", os.path.join(ROOT, "include"),
+                    os.path.join(ROOT, "tests", "a3po_host_sanitize_driver.c"), "-o", exe, "-L", str(tmp_path), "-la3po",
+                    f"-Wl,-rpath,{tmp_path}", f"-Wl,-rpath,{rocm_lib}"], check=True, capture_output=True)
+    env = dict(os.environ, ASAN_OPTIONS="detect_leaks=0")      # the GPU runtime's own start-up allocations are not ours
+    res = subprocess.run([exe], capture_output=True, text=True, timeout=300, env=env)
+    assert res.returncode == 0, (res.stdout[-500:], res.stderr[-2000:])
+    assert res.stdout.strip().endswith("ok") and "runtime error" not in res.stderr and "ERROR" not in res.stderr
