@@ -339,7 +339,8 @@ int a3po_fused_lmhead_logprob(const void *hidden, const void *weight, int64_t T,
  * in fp32 and rounded to bfloat16 once); everything between them is this library's kernels.
  * hidden, dhidden [T, H]; weight, dweight [V, H]: row-major, contiguous, bfloat16, 16-byte
  * aligned; H % 8 == 0, H <= 2^20 and V % 8 == 0.  Per-token arguments and outputs as in a3po_loss_fwd_bwd.
- * workspace: a3po_workspace_bytes(A3PO_WS_FUSED_LMHEAD_LOSS, T, V, H) bytes, 256-byte aligned.
+ * workspace: a3po_workspace_bytes(A3PO_WS_FUSED_LMHEAD_LOSS, T, V, H) bytes, 256-byte aligned (the fp32
+ * accumulator of dweight, a chunk of logits and its transpose: about 4 V H + 4 * 8192 V bytes).
  * Unlike the other entry points this one keeps one process-wide rocBLAS handle, created on first
  * use (rocBLAS allocates its own scratch then); calls that share it must not overlap in time.
  */

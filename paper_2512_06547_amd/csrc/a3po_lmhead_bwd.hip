@@ -9,6 +9,12 @@
 // The three contractions are plain GEMMs and go to rocBLAS (bfloat16 in, fp32 accumulate); dW is
 // accumulated across chunks in fp32 and rounded to bfloat16 once at the end.  Everything between
 // the GEMMs is this library's own kernels.
+//
+// dW = dz^T h contracts over the tokens, which is the slow dimension of both dz [n, V] and h [n, H] as they
+// lie in memory; the matrix cores want the contracted index contiguous.  The gradient chunk and the hidden
+// chunk are therefore transposed once (dzT [V, n], hT [H, n]; one more read and write of the chunk) and the
+// product runs in the form with both operands contiguous along the tokens: 8.05 against 9.93 ms per chunk
+// for the GEMM at the 8B shape, about 1 ms for the two transposes.
 #include <mutex>
 
 #include <rocblas/rocblas.h>
@@ -24,8 +30,9 @@ namespace a3po {
 constexpr int64_t kLmBwdChunk = A3PO_LM_BWD_CHUNK;  // tokens whose logits live in HBM at a time
 
 struct LmBwdLayout {
-    size_t loss_ws, zchunk, dwacc, total;
+    size_t loss_ws, zchunk, dzt, ht, dwacc, total;
     int64_t chunk;
+    int64_t ldt;  // row stride of the transposed chunks: the chunk length rounded up to 8 tokens (16 bytes)
 };
 
 static LmBwdLayout lmhead_bwd_layout(int64_t T, int64_t V, int64_t H)
@@ -34,8 +41,11 @@ static LmBwdLayout lmhead_bwd_layout(int64_t T, int64_t V, int64_t H)
     LmBwdLayout l;
     l.chunk = T < kLmBwdChunk ? (T > 0 ? T : 1) : kLmBwdChunk;
     l.loss_ws = 0;
+    l.ldt = (l.chunk + 7) / 8 * 8;
     l.zchunk = up(loss_ws_layout(T).total);
-    l.dwacc = l.zchunk + up((size_t)l.chunk * (size_t)V * 2);
+    l.dzt = l.zchunk + up((size_t)l.chunk * (size_t)V * 2);
+    l.ht = l.dzt + up((size_t)V * (size_t)l.ldt * 2);
+    l.dwacc = l.ht + up((size_t)H * (size_t)l.ldt * 2);
     l.total = l.dwacc + up((size_t)V * (size_t)H * sizeof(float));
     return l;
 }
@@ -67,6 +77,50 @@ static rocblas_handle blas_handle()
         if (rocblas_create_handle(&handle) != rocblas_status_success) handle = nullptr;
     });
     return handle;
+}
+
+// out [C, ldo] = transpose of in [R, C] (row-major, 2-byte elements; C a multiple of 8, ldo >= R a multiple of 8).
+// A workgroup moves a 64 x 64 tile through LDS: 16-byte loads along the columns, 16-byte stores along the rows.
+// Rows beyond R inside the last 8-row group of a tile are stored as zeros (they lie in the padding of `out`).
+constexpr int kTrTile = 64;
+__global__ __launch_bounds__(256) void transpose_bf16_kernel(const uint16_t *__restrict__ in, uint16_t *__restrict__ out,
+                                                             int64_t R, int64_t C, int64_t ldo)
+{
+    __shared__ uint16_t tile[kTrTile][kTrTile + 2];  // [row][column], padded: column reads below spread over the banks
+    const int64_t r0 = (int64_t)blockIdx.y * kTrTile, c0 = (int64_t)blockIdx.x * kTrTile;
+    const int tid = threadIdx.x;
+    // load: 64 rows x 8 vectors of 8 columns; thread -> (row = tid / 8 + 32 * pass, vector = tid % 8)
+#pragma unroll
+    for (int pass = 0; pass < 2; ++pass) {
+        const int r = tid / 8 + 32 * pass, cv = (tid % 8) * 8;
+        uint4 v = make_uint4(0u, 0u, 0u, 0u);
+        if (r0 + r < R && c0 + cv < C) v = *reinterpret_cast<const uint4 *>(in + (r0 + r) * C + c0 + cv);
+        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            tile[r][cv + 2 * e] = (uint16_t)(w[e] & 0xFFFFu);
+            tile[r][cv + 2 * e + 1] = (uint16_t)(w[e] >> 16);
+        }
+    }
+    __syncthreads();
+    // store: 64 columns x 8 vectors of 8 rows; thread -> (column = tid / 8 + 32 * pass, vector = tid % 8)
+#pragma unroll
+    for (int pass = 0; pass < 2; ++pass) {
+        const int c = tid / 8 + 32 * pass, rv = (tid % 8) * 8;
+        if (c0 + c >= C || r0 + rv >= R) continue;
+        uint32_t w[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            w[e] = (uint32_t)tile[rv + 2 * e][c] | ((uint32_t)tile[rv + 2 * e + 1][c] << 16);
+        *reinterpret_cast<uint4 *>(out + (c0 + c) * ldo + r0 + rv) = make_uint4(w[0], w[1], w[2], w[3]);
+    }
+}
+
+static hipError_t launch_transpose_bf16(const uint16_t *in, uint16_t *out, int64_t R, int64_t C, int64_t ldo, hipStream_t s)
+{
+    const dim3 grid((unsigned)((C + kTrTile - 1) / kTrTile), (unsigned)((R + kTrTile - 1) / kTrTile));
+    hipLaunchKernelGGL(transpose_bf16_kernel, grid, dim3(256), 0, s, in, out, R, C, ldo);
+    return hipGetLastError();
 }
 
 // column-major C[m,n] = alpha op(A) op(B) + beta C with bf16 A, B and fp32 accumulation
@@ -113,6 +167,8 @@ extern "C" int a3po_fused_lmhead_loss_fwd_bwd(const void *hidden, const void *we
 
     char *ws = static_cast<char *>(workspace);
     uint16_t *zc = reinterpret_cast<uint16_t *>(ws + lay.zchunk);
+    uint16_t *dzt = reinterpret_cast<uint16_t *>(ws + lay.dzt);
+    uint16_t *ht = reinterpret_cast<uint16_t *>(ws + lay.ht);
     float *dwacc = reinterpret_cast<float *>(ws + lay.dwacc);
     const uint16_t *h = static_cast<const uint16_t *>(hidden);
     uint16_t *dh = static_cast<uint16_t *>(dhidden);
@@ -164,8 +220,12 @@ extern "C" int a3po_fused_lmhead_loss_fwd_bwd(const void *hidden, const void *we
         if (!gemm_bf16(hd, rocblas_operation_none, rocblas_operation_none, H, n, V, weight, H, zc, V, 0.0f, dh + c0 * H,
                        H, rocblas_datatype_bf16_r))
             return A3PO_E_LAUNCH;
-        // dW^T [H, V] += h_chunk [H, n] (dz^T [V, n])^T       (fp32 accumulator across chunks)
-        if (!gemm_bf16(hd, rocblas_operation_none, rocblas_operation_transpose, H, V, n, h + c0 * H, H, zc, V,
+        // dW^T [H, V] += hT [n, H]^T dzT [n, V]       (column-major views of the transposed chunks, tokens
+        // contiguous in both; fp32 accumulator across chunks)
+        const int64_t ldt = (n + 7) / 8 * 8;
+        if (launch_transpose_bf16(zc, dzt, n, V, ldt, s) != hipSuccess) return A3PO_E_LAUNCH;
+        if (launch_transpose_bf16(h + c0 * H, ht, n, H, ldt, s) != hipSuccess) return A3PO_E_LAUNCH;
+        if (!gemm_bf16(hd, rocblas_operation_transpose, rocblas_operation_none, H, V, n, ht, ldt, dzt, ldt,
                        c0 == 0 ? 0.0f : 1.0f, dwacc, H, rocblas_datatype_f32_r))
             return A3PO_E_LAUNCH;
     }
