@@ -45,7 +45,8 @@ typedef enum {
 enum {
     A3PO_OK = 0,
     A3PO_E_NULL = -1,        /* a required pointer is NULL                          */
-    A3PO_E_SIZE = -2,        /* T < 0, V <= 0, ld < V, G <= 0, S % G != 0, ...      */
+    A3PO_E_SIZE = -2,        /* T < 0, V <= 0, ld < V, T or ld > 2^40, V >= 2^31,   */
+                             /* G <= 0, S % G != 0, ...                             */
     A3PO_E_DTYPE = -3,       /* dtype is not A3PO_F32 / A3PO_BF16                   */
     A3PO_E_ALIGN = -4,       /* logits / dlogits / workspace base not aligned       */
     A3PO_E_WORKSPACE = -5,   /* workspace_bytes below a3po_workspace_bytes(...)     */

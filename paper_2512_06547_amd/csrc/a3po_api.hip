@@ -9,15 +9,17 @@ using namespace a3po;
 
 namespace {
 
-
 using WsLayout = LossWsLayout;
+
+constexpr int64_t kMaxRows = (int64_t)1 << 40, kMaxStride = (int64_t)1 << 40;
 
 inline bool aligned(const void *p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 
 int check_logits(const void *logits, int dt, int64_t T, int64_t V, int64_t ld)
 {
     if (dt != A3PO_F32 && dt != A3PO_BF16) return A3PO_E_DTYPE;
-    if (T < 0 || V <= 0 || ld < V || V > (int64_t)0x7FFFFFFF) return A3PO_E_SIZE;
+    // (the bounds on T and ld keep every byte offset T * ld * 4 far inside 64 bits)
+    if (T < 0 || V <= 0 || ld < V || V > (int64_t)0x7FFFFFFF || T > kMaxRows || ld > kMaxStride) return A3PO_E_SIZE;
     if (T > 0 && !logits) return A3PO_E_NULL;
     if (!aligned(logits, dt == A3PO_F32 ? 4 : 2)) return A3PO_E_ALIGN;  // element alignment; 16 bytes selects the fast kernels
     return A3PO_OK;
@@ -29,8 +31,6 @@ extern "C" {
 
 size_t a3po_workspace_bytes(int which, int64_t T, int64_t V, int64_t H)
 {
-    (void)V;
-    (void)H;
     if (which == A3PO_WS_LOSS_FWD_BWD) return loss_ws_layout(T).total;
     if (which == A3PO_WS_FUSED_LMHEAD) return lmhead_workspace_bytes(T);
     if (which == A3PO_WS_FUSED_LMHEAD_LOSS) return lmhead_bwd_workspace_bytes(T, V, H);

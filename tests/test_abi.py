@@ -62,6 +62,9 @@ def test_host_validation_rejects_bad_arguments_before_launch(lib):
     assert tl(fake, 0, -1, 8, 8, fake, fake, None, None, None) == -2         # T < 0
     assert tl(fake, 0, 1, 0, 8, fake, fake, None, None, None) == -2          # V <= 0
     assert tl(fake, 0, 1, 9, 8, fake, fake, None, None, None) == -2          # ld < V
+    assert tl(fake, 0, (1 << 40) + 1, 8, 8, fake, fake, None, None, None) == -2      # more rows than any memory holds
+    assert tl(fake, 0, 1, 8, (1 << 40) + 8, fake, fake, None, None, None) == -2      # a stride that would overflow byte offsets
+    assert tl(fake, 0, 1, 1 << 31, 1 << 31, fake, fake, None, None, None) == -2       # ids are int32
     assert tl(None, 0, 1, 8, 8, fake, fake, None, None, None) == -1          # null logits
     assert tl(ctypes.c_void_p(0x1002), 0, 1, 8, 8, fake, fake, None, None, None) == -4   # not element aligned
     assert tl(fake, 0, 1, 8, 8, None, fake, None, None, None) == -1          # null chosen
