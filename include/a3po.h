@@ -116,8 +116,8 @@ const char *a3po_strerror(int code);
  * the stored z[t,y_t] copied bit for bit.  A chosen id outside [0,V) gives logp 0 and a
  * zero chosen logit; lse is still written.  Reads T*V elements once.
  * Logits may be -inf (entries that cannot be sampled: probability exactly 0).  Accuracy of lse and
- * logp: 1e-5 (1 + |value|) + 1.2e-7 max_j |z[t,j]| - the last term is below 1e-5 for logits within
- * +-80, the range language models produce, and grows with the magnitude of the largest logit.
+ * logp: 1e-5 (1 + |value|) whatever the magnitude of the logits (differences z - max are taken before
+ * any scaling, and logp is (z_y - max) - log sum exp(z - max), not z_y - lse).
  */
 int a3po_token_logprobs(const void *logits, a3po_dtype dt, int64_t T, int64_t V, int64_t ld,
                         const int32_t *chosen, float *logp_out, float *lse_out,

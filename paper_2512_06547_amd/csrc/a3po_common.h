@@ -152,11 +152,11 @@ __device__ __forceinline__ void fold(MaxSum &acc, const float *f)
 #pragma unroll
     for (int e = 1; e < N; ++e) vmax = fmaxf(vmax, f[e]);
     const float m_new = fmaxf(acc.m, vmax);
-    const float nm = -m_new * kLog2e;
-    // (acc.m - m_new) first: exactly 0 when the maximum did not move, whatever its magnitude
+    // differences first, then the scaling by log2(e): (z - m) is exact or rounded relative to the difference
+    // itself, so the exponent's error does not grow with the magnitude of the logits
     float s = acc.s * exp2_hw((acc.m - m_new) * kLog2e);
 #pragma unroll
-    for (int e = 0; e < N; ++e) s += exp2_hw(fmaf(f[e], kLog2e, nm));
+    for (int e = 0; e < N; ++e) s += exp2_hw((f[e] - m_new) * kLog2e);
     acc.m = m_new;
     acc.s = s;
 }
@@ -208,12 +208,11 @@ __device__ __forceinline__ void fold(MaxSumU &acc, const float *f)
 #pragma unroll
     for (int e = 1; e < N; ++e) vmax = fmaxf(vmax, f[e]);
     const float m_new = fmaxf(acc.m, vmax);
-    const float nm = -m_new * kLog2e;
     const float scale = exp2_hw((acc.m - m_new) * kLog2e);
     float s = acc.s * scale, u = acc.u * scale;
 #pragma unroll
     for (int e = 0; e < N; ++e) {
-        const float ex = exp2_hw(fmaf(f[e], kLog2e, nm));
+        const float ex = exp2_hw((f[e] - m_new) * kLog2e);
         s += ex;
         u = fmaf(ex, finite_floor(f[e]), u);
     }

@@ -55,7 +55,6 @@ __device__ __forceinline__ void fold_column(const f32x16_t (&acc)[4][4], int b, 
         __builtin_amdgcn_sched_barrier(0);
     }
     const float m_new = fmaxf(run_m, mx);
-    const float nm = -m_new * kLog2e;
     float s = run_s * exp2_hw((run_m - m_new) * kLog2e);
 #pragma unroll
     for (int a = 0; a < 4; ++a) {
@@ -63,7 +62,7 @@ __device__ __forceinline__ void fold_column(const f32x16_t (&acc)[4][4], int b, 
         for (int e = 0; e < 16; ++e) {
             float v = acc[a][b][e];
             if (RAGGED && a * 32 + (e >> 2) * 8 + (e & 3) >= vlim) v = -INFINITY;
-            s += exp2_hw(fmaf(v, kLog2e, nm));
+            s += exp2_hw((v - m_new) * kLog2e);
         }
         __builtin_amdgcn_sched_barrier(0);
     }
@@ -352,9 +351,9 @@ __global__ __launch_bounds__(256) void lmhead_finish_kernel(const uint16_t *__re
             const float2 q = partial[(int64_t)p * T + t];
             tot = combine(tot, MaxSum{q.x, q.y});
         }
-        const float lse = tot.m + logf(tot.s);
-        if (lse_out) lse_out[t] = lse;
-        logp[t] = ok ? dot - lse : 0.0f;
+        const float log_s = logf(tot.s);
+        if (lse_out) lse_out[t] = tot.m + log_s;
+        logp[t] = ok ? (dot - tot.m) - log_s : 0.0f;
     }
 }
 

@@ -35,12 +35,15 @@ constexpr uint32_t kSweepBytes = kRowThreads * 16;
 
 // One vector of the backward pass: f (logits) -> f (gradient entries without the chosen column's +g),
 // and for ENT the running sum of p_j z_j (elements past the row's end hold -inf: p = 0).
+// p_j = exp(z_j - lse) is evaluated as exp2((z_j - m) log2e - log2 s) with m the row's maximum and s its
+// sum of exp(z - m): the difference is taken before the scaling, so the exponent's rounding error is
+// relative to (z_j - m), not to the magnitude of the logits.
 template <int EPV, bool ENT>
-__device__ __forceinline__ void backward_vec(float *f, float neg_g, float nlse, float &pz)
+__device__ __forceinline__ void backward_vec(float *f, float neg_g, float row_max, float nls2, float &pz)
 {
 #pragma unroll
     for (int e = 0; e < EPV; ++e) {
-        const float p = exp2_hw(fmaf(f[e], kLog2e, nlse));
+        const float p = exp2_hw(fmaf(f[e] - row_max, kLog2e, nls2));
         if constexpr (ENT) pz = fmaf(p, finite_floor(f[e]), pz);
         f[e] = neg_g * p;
     }
@@ -132,7 +135,7 @@ __global__ __launch_bounds__(kRowThreads) void loss_rows_kernel(
         const int row_par = parity;
 
         uint4 v[NSWEEP];
-        float g = 0.0f, lse = 0.0f, zy = 0.0f;
+        float g = 0.0f, lse = 0.0f, zy = 0.0f, row_max = 0.0f, nls2 = 0.0f;
         uint32_t zy_bits = 0;
         int64_t next = T;
         if (live) {  // uniform over the workgroup
@@ -193,8 +196,11 @@ __global__ __launch_bounds__(kRowThreads) void loss_rows_kernel(
             if (upcoming < T) nxt = records[upcoming];  // scalar load, lands during the backward pass
             if constexpr (ENT) finish_pending_entropy();
 
-            lse = tot.m + logf(tot.s);
-            const float lt = zy - lse;
+            row_max = tot.m;
+            const float log_s = logf(tot.s);
+            nls2 = -log_s * kLog2e;
+            lse = tot.m + log_s;
+            const float lt = (zy - tot.m) - log_s;  // not zy - lse: lse carries the rounding of a large maximum
             const TokenTerms tt =
                 token_terms(lt, cur.lb, cur.ver, current_version, cur.A, clip_eps, inv_n, prox_mode);
             g = tt.g;
@@ -243,13 +249,12 @@ __global__ __launch_bounds__(kRowThreads) void loss_rows_kernel(
         // (with ENT a counted row whose g is 0 comes through here too and stores exact zeros)
         // (+0 rather than -0 when there is no gradient: the row is then stored as +0 bit for bit, as the zero path does)
         const float neg_g = g != 0.0f ? -g : 0.0f;
-        const float nlse = -lse * kLog2e;
         float pz = 0.0f;
 #pragma unroll
         for (int k = (STASH > 1 ? STASH - 1 : 0); k < LAST; ++k) {
             float f[EPV];
             unpack<DT>(v[k], f);
-            backward_vec<EPV, ENT>(f, neg_g, nlse, pz);
+            backward_vec<EPV, ENT>(f, neg_g, row_max, nls2, pz);
             stream_store(out_row + (size_t)k * kSweepBytes + voff, pack<DT>(f));
             if constexpr (ENT) __builtin_amdgcn_sched_barrier(0);  // one vector's temporaries at a time
         }
@@ -258,7 +263,7 @@ __global__ __launch_bounds__(kRowThreads) void loss_rows_kernel(
             for (int k = 0; k < STASH - 1; ++k) {
                 float f[EPV];
                 unpack<DT>(stash[k + 1][tid], f);
-                backward_vec<EPV, ENT>(f, neg_g, nlse, pz);
+                backward_vec<EPV, ENT>(f, neg_g, row_max, nls2, pz);
                 stream_store(out_row + (size_t)k * kSweepBytes + voff, pack<DT>(f));
             }
         }
@@ -266,7 +271,7 @@ __global__ __launch_bounds__(kRowThreads) void loss_rows_kernel(
             float f[EPV];
             if constexpr (STASH > 0) unpack<DT>(stash[0][tid], f);
             else unpack<DT>(v[LAST], f);
-            backward_vec<EPV, ENT>(f, neg_g, nlse, pz);
+            backward_vec<EPV, ENT>(f, neg_g, row_max, nls2, pz);
             if (last_full) {
                 stream_store(out_row + (size_t)LAST * kSweepBytes + voff, pack<DT>(f));
             } else {
@@ -278,7 +283,7 @@ __global__ __launch_bounds__(kRowThreads) void loss_rows_kernel(
         // The chosen column gets +g.  The thread that stored the vector holding column y
         // rewrites that one element afterwards (same thread, same address: program order).
         if (g != 0.0f && tid == ((y / EPV) & (kRowThreads - 1)))
-            store_elem<DT>(out_row, y, neg_g * exp2_hw(fmaf(zy, kLog2e, nlse)) + g);
+            store_elem<DT>(out_row, y, neg_g * exp2_hw(fmaf(zy - row_max, kLog2e, nls2)) + g);
         if constexpr (ENT) {
 #pragma unroll
             for (int off = kWave / 2; off > 0; off >>= 1) pz += __shfl_xor(pz, off, kWave);
@@ -314,22 +319,24 @@ __global__ __launch_bounds__(kRowThreads) void loss_rows_generic_kernel(const Lo
         const bool live = y >= 0;
         char *out_row = reinterpret_cast<char *>(a.dz) + (size_t)row * row_bytes;
         const char *in_row = reinterpret_cast<const char *>(a.z) + (size_t)row * row_bytes;
-        float g = 0.0f, lse = 0.0f;
+        float g = 0.0f, lse = 0.0f, row_max = 0.0f, nls2 = 0.0f;
         if (live) {
             float m = kNegFloor;
             for (int64_t j = tid; j < V; j += blockDim.x) m = fmaxf(m, load_elem<DT>(in_row, j));
             const float M = block_allreduce<kRowWaves>(MaxSum{m, 0.0f}, red).m;
             float s = 0.0f, u = 0.0f;
-            const float nm = -M * kLog2e;
             for (int64_t j = tid; j < V; j += blockDim.x) {
                 const float zj = load_elem<DT>(in_row, j);
-                const float ex = exp2_hw(fmaf(zj, kLog2e, nm));
+                const float ex = exp2_hw((zj - M) * kLog2e);
                 s += ex;
                 u = fmaf(ex, finite_floor(zj), u);
             }
             const MaxSumU t = block_allreduce<kRowWaves>(MaxSumU{M, s, u}, red);
-            lse = t.m + logf(t.s);
-            const float lt = load_elem<DT>(in_row, y) - lse;
+            row_max = t.m;
+            const float log_s = logf(t.s);
+            nls2 = -log_s * kLog2e;
+            lse = t.m + log_s;
+            const float lt = (load_elem<DT>(in_row, y) - t.m) - log_s;
             const TokenTerms tt =
                 token_terms(lt, cur.lb, cur.ver, a.current_version, cur.A, a.clip_eps, inv_n, a.prox_mode);
             g = tt.g;
@@ -354,9 +361,8 @@ __global__ __launch_bounds__(kRowThreads) void loss_rows_generic_kernel(const Lo
         if (g == 0.0f) {
             for (int64_t j = tid; j < V; j += blockDim.x) store_elem<DT>(out_row, j, 0.0f);
         } else {
-            const float nlse = -lse * kLog2e;
             for (int64_t j = tid; j < V; j += blockDim.x) {
-                float d = -g * exp2_hw(fmaf(load_elem<DT>(in_row, j), kLog2e, nlse));
+                float d = -g * exp2_hw(fmaf(load_elem<DT>(in_row, j) - row_max, kLog2e, nls2));
                 if (j == (int64_t)y) d += g;
                 store_elem<DT>(out_row, j, d);
             }
@@ -417,12 +423,13 @@ __global__ __launch_bounds__(kFwdThreads) void logprob_rows_kernel(const void *z
         }
         const Acc tot = block_allreduce<kFwdWaves>(acc, red);
         if (tid == 0) {
-            const float lse = tot.m + logf(tot.s);
+            const float log_s = logf(tot.s);
+            const float lse = tot.m + log_s;
             const int32_t y = chosen[row];
             const bool ok = y >= 0 && (int64_t)y < V;
             if (lse_out) lse_out[row] = lse;
             if constexpr (ENT) ent_out[row] = entropy_of(tot, lse);
-            logp[row] = ok ? load_elem<DT>(in_row, y) - lse : 0.0f;
+            logp[row] = ok ? (load_elem<DT>(in_row, y) - tot.m) - log_s : 0.0f;
             if (chosen_logit) {
                 if constexpr (DT::kBytes == 4) {
                     reinterpret_cast<uint32_t *>(chosen_logit)[row] =

@@ -166,10 +166,11 @@ __global__ void shard_combine_kernel(const a3po_shard_partial *__restrict__ part
         tot = combine(tot, MaxSumU{q.max, q.sum_exp, q.sum_exp_z});
         zy += q.chosen_logit;  // exactly one shard owns the chosen column; the others hold 0
     }
-    const float lse = tot.m + logf(tot.s);
+    const float log_s = logf(tot.s);
+    const float lse = tot.m + log_s;
     const int32_t y = chosen[t];
     const bool ok = y >= 0 && (int64_t)y < V;
-    logp[t] = ok ? zy - lse : 0.0f;
+    logp[t] = ok ? (zy - tot.m) - log_s : 0.0f;  // not zy - lse: lse carries the rounding of a large maximum
     if (lse_out) lse_out[t] = lse;
     if (ent_out) ent_out[t] = entropy_of(tot, lse);
 }
@@ -217,7 +218,6 @@ __global__ __launch_bounds__(kShardThreads) void shard_bwd_rows_kernel(
             out.flags[row] = 0;
         }
         const float neg_g = -g;
-        const float nlse = -lse * kLog2e;
         const bool dead = g == 0.0f;  // uniform: zero-fill without reading the row
         if (vec) {
             int idx = tid;
@@ -235,7 +235,7 @@ __global__ __launch_bounds__(kShardThreads) void shard_bwd_rows_kernel(
                         float f[EPV];
                         unpack<DT>(v[u], f);
 #pragma unroll
-                        for (int e = 0; e < EPV; ++e) f[e] = neg_g * exp2_hw(fmaf(f[e], kLog2e, nlse));
+                        for (int e = 0; e < EPV; ++e) f[e] = neg_g * exp2_hw((f[e] - lse) * kLog2e);
                         o = pack<DT>(f);
                     }
                     stream_store(out_row + (size_t)(idx + u * kShardThreads) * 16, o);
@@ -247,16 +247,16 @@ __global__ __launch_bounds__(kShardThreads) void shard_bwd_rows_kernel(
                     float f[EPV];
                     unpack<DT>(stream_load(in_row + (size_t)idx * 16), f);
 #pragma unroll
-                    for (int e = 0; e < EPV; ++e) f[e] = neg_g * exp2_hw(fmaf(f[e], kLog2e, nlse));
+                    for (int e = 0; e < EPV; ++e) f[e] = neg_g * exp2_hw((f[e] - lse) * kLog2e);
                     o = pack<DT>(f);
                 }
                 stream_store(out_row + (size_t)idx * 16, o);
             }
             for (int64_t j = (int64_t)nfull * EPV + tid; j < Vs; j += kShardThreads)
-                store_elem<DT>(out_row, j, dead ? 0.0f : neg_g * exp2_hw(fmaf(load_elem<DT>(in_row, j), kLog2e, nlse)));
+                store_elem<DT>(out_row, j, dead ? 0.0f : neg_g * exp2_hw((load_elem<DT>(in_row, j) - lse) * kLog2e));
         } else {
             for (int64_t j = tid; j < Vs; j += kShardThreads)
-                store_elem<DT>(out_row, j, dead ? 0.0f : neg_g * exp2_hw(fmaf(load_elem<DT>(in_row, j), kLog2e, nlse)));
+                store_elem<DT>(out_row, j, dead ? 0.0f : neg_g * exp2_hw((load_elem<DT>(in_row, j) - lse) * kLog2e));
         }
         // The chosen column, if this shard owns it, gets +g: rewritten by the thread that stored it
         // (same thread, same address: program order).  Its softmax entry is pi_theta(y) = exp(log pi)
@@ -323,7 +323,7 @@ __global__ __launch_bounds__(kBurstThreads) void shard_bwd_burst_kernel(
 {
     constexpr int EPV = DT::kPerVec;
     constexpr int kBurstVec = BurstVec<DT>::value;
-    __shared__ float s_negg[2][kBurstThreads], s_nlse[2][kBurstThreads];
+    __shared__ float s_negg[2][kBurstThreads], s_lse[2][kBurstThreads];
     __shared__ int s_ycol[2][kBurstThreads];  // chosen column inside the shard, or -1
     __shared__ unsigned int s_next[2];
     const int tid = threadIdx.x;
@@ -373,7 +373,7 @@ __global__ __launch_bounds__(kBurstThreads) void shard_bwd_burst_kernel(
             }
             const int64_t yl = (int64_t)cur.y - v0;
             s_negg[par][tid] = -g;
-            s_nlse[par][tid] = -lse * kLog2e;
+            s_lse[par][tid] = lse;
             s_ycol[par][tid] = (cur.y >= 0 && yl >= 0 && yl < Vs) ? (int)yl : -1;
         }
         __syncthreads();
@@ -412,11 +412,11 @@ __global__ __launch_bounds__(kBurstThreads) void shard_bwd_burst_kernel(
             char *dst = reinterpret_cast<char *>(dz) + (size_t)(r0 + r) * row_bytes + (size_t)c * 16;
             float f[EPV];
             if (neg_g != 0.0f) {
-                const float nlse = s_nlse[par][r];
+                const float lse = s_lse[par][r];
                 unpack<DT>(v[k], f);
                 const int ye = s_ycol[par][r] - c * EPV;  // the chosen column's place in this vector
 #pragma unroll
-                for (int e = 0; e < EPV; ++e) f[e] = neg_g * exp2_hw(fmaf(f[e], kLog2e, nlse));
+                for (int e = 0; e < EPV; ++e) f[e] = neg_g * exp2_hw((f[e] - lse) * kLog2e);
                 if ((unsigned)ye < (unsigned)EPV) {  // one vector per row: a real branch, not eight selects per vector
                     asm volatile("" ::: "memory");
 #pragma unroll
@@ -510,6 +510,13 @@ static BurstShape burst_shape(int64_t T, int64_t Vs, int64_t esz)
     sh.magic = (uint32_t)((1ull << 32) / (uint64_t)sh.slots_row + 1);  // slots_row >= 2; used only when rows > 1 (then cw == slots_row)
     sh.items = ((T + sh.rows - 1) / sh.rows) * sh.chunks;
     return sh;
+}
+
+int64_t shard_bwd_queue_items(int dt, int64_t T, int64_t Vs)
+{
+    const int64_t esz = dt == A3PO_F32 ? 4 : 2;
+    if (T <= 0 || Vs * esz <= 16) return 0;
+    return burst_shape(T, Vs, esz).items;
 }
 
 hipError_t launch_shard_bwd_rows(const LossArgs &a, int64_t v0, const float *logp_theta, const float *lse, hipStream_t s)
