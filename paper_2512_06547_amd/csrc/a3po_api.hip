@@ -124,6 +124,8 @@ int a3po_loss_fwd_bwd_ex(const void *logits, a3po_dtype dt, int64_t T, int64_t V
     const a3po_loss_options none = {};
     const a3po_loss_options &o = opt ? *opt : none;
     if (int rc = check_logits(logits, (int)dt, T, V, ld)) return rc;
+    // (rows, or gradient bursts of rows too long for the registers, are dealt out through a 32-bit counter)
+    if (T > kQueueMaxItems || shard_bwd_queue_items((int)dt, T, V) > kQueueMaxItems) return A3PO_E_SIZE;
     if (!(clip_eps >= 0.0f && clip_eps < 1.0f) || std::isnan(denom)) return A3PO_E_VALUE;
     if (o.prox_mode < A3PO_PROX_INTERP || o.prox_mode > A3PO_PROX_BEHAV || (o.accumulate != 0 && o.accumulate != 1))
         return A3PO_E_VALUE;
@@ -279,6 +281,7 @@ int a3po_shard_loss_bwd(const void *logits_shard, a3po_dtype dt, int64_t T, int6
     const a3po_loss_options &o = opt ? *opt : none;
     if (int rc = check_logits(logits_shard, (int)dt, T, Vs, ld)) return rc;
     if (v0 < 0 || V <= 0 || v0 + Vs > V || V > (int64_t)0x7FFFFFFF) return A3PO_E_SIZE;
+    if (T > kQueueMaxItems || shard_bwd_queue_items((int)dt, T, Vs) > kQueueMaxItems) return A3PO_E_SIZE;
     if (!(clip_eps >= 0.0f && clip_eps < 1.0f) || std::isnan(denom)) return A3PO_E_VALUE;
     if (o.prox_mode < A3PO_PROX_INTERP || o.prox_mode > A3PO_PROX_BEHAV || (o.accumulate != 0 && o.accumulate != 1))
         return A3PO_E_VALUE;

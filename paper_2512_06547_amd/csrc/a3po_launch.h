@@ -113,6 +113,11 @@ hipError_t launch_shard_combine(const a3po_shard_partial *parts, int32_t P, int6
                                 float *logp, float *lse, float *ent, const TokenRecord *records, hipStream_t s);
 // the loss rows in three streaming passes (partials, merge, gradient bursts) for rows that do not fit on chip
 hipError_t launch_loss_rows_three_pass(const LossArgs &a, hipStream_t s);
+// The row kernel and the gradient bursts hand out work through a 32-bit counter: item index = grid size + number
+// of claims so far, and every workgroup makes one claim past the end.  Item counts above this bound are refused
+// by the entry points (rows for the register-resident kernel, bursts for the streaming one).
+constexpr int64_t kQueueMaxItems = ((int64_t)1 << 32) - ((int64_t)1 << 16);
+int64_t shard_bwd_queue_items(int dt, int64_t T, int64_t Vs);  // bursts launch_shard_bwd_rows would queue (0: no queue)
 // a.V is the shard width here; a.ws_records must come from a prep launch made with the full vocabulary size
 hipError_t launch_shard_bwd_rows(const LossArgs &a, int64_t v0, const float *logp_theta, const float *lse, hipStream_t s);
 

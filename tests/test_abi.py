@@ -94,6 +94,9 @@ def test_host_validation_rejects_bad_arguments_before_launch(lib):
     assert call(a18=ctypes.c_void_p(0x10010)) == -4
     assert call(a13=ctypes.c_void_p(0x1001)) == -4 and call(a0=ctypes.c_void_p(0x1001)) == -4
     assert call(a1=2) == -3 and call(a4=32) == -2
+    # rows are dealt out through a 32-bit counter: a row count it cannot hold is refused (reachable with a tiny V)
+    assert call(a2=(1 << 32) - (1 << 16) + 1, a3=1, a4=8) == -2 and call(a2=1 << 33, a3=1, a4=8) == -2
+    assert call(a2=(1 << 32) - (1 << 16), a3=1, a4=8) == -5              # the largest count passes this check
 
 
 def test_lmhead_entry_points_validate_before_launch(lib):
