@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the A-3PO loss forward+backward hot path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 1p5b|8b|long|tiny|lmhead8b]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 8b|1p5b|long|tiny|lmhead8b]
 
 One step = one pass of the whole path over one synthetic batch already resident in HBM:
 GRPO advantages -> mask count / token records -> fused row kernel (log-softmax + gather,
@@ -246,12 +246,16 @@ def secondary_kernels(a3po, torch, w, b, adv, dz, ws, log, reps=10, shards=8):
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X published dense bf16 peak
 
 
-def bench_lmhead(args, torch, a3po, synth, log):
+def bench_lmhead(args, torch, a3po, synth, log, name=None, steps=None, warmup=None, cpu_rows=None):
     """The fused LM-head workload (hidden states x LM-head weight in front of the loss path): one step =
     GRPO advantages + a3po_fused_lmhead_loss_fwd_bwd (projection, loss, gradient rows, dh, dW).  The
-    hand-written forward-only kernel (a3po_fused_lmhead_logprob) is timed beside it."""
+    forward-only entry point (a3po_fused_lmhead_logprob) is timed beside it.  Returns the JSON line as a dict."""
     import numpy as np
-    lw = synth.LMHEAD_WORKLOADS[args.workload]
+    name = args.workload if name is None else name
+    steps = args.steps if steps is None else steps
+    warmup = args.warmup if warmup is None else warmup
+    cpu_rows = args.cpu_rows if cpu_rows is None else cpu_rows
+    lw = synth.LMHEAD_WORKLOADS[name]
     w = lw.tokens
     T, H, V = w.T, lw.H, w.V
     tk = synth.token_arrays(w)
@@ -279,16 +283,17 @@ def bench_lmhead(args, torch, a3po, synth, log):
         return a3po.fused_lmhead_loss_fwd_bwd(h, W, y, lb, ver, tk["current_version"], adv, mask, w.clip_eps,
                                               workspace=ws)
 
-    for _ in range(args.warmup):
+    out = step()
+    for _ in range(warmup):
         out = step()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    for _ in range(steps):
         out = step()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     st = a3po.stats_to_dict(out["stats"])
-    ms = dt / args.steps * 1e3
+    ms = dt / steps * 1e3
     flops = 6.0 * T * V * H
     tf = flops / (ms * 1e-3) / 1e12
     log(f"fwd+bwd: {ms:.1f} ms/step, {tf:.0f} TFLOP/s on 6TVH, stats {st}")
@@ -296,7 +301,7 @@ def bench_lmhead(args, torch, a3po, synth, log):
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     a3po.fused_lmhead_logprob(h, W, y, workspace=ws_f)
     e0.record()
-    nf = max(1, args.steps // 2)
+    nf = max(1, steps // 2)
     for _ in range(nf):
         a3po.fused_lmhead_logprob(h, W, y, workspace=ws_f)
     e1.record()
@@ -306,7 +311,7 @@ def bench_lmhead(args, torch, a3po, synth, log):
     log(f"fused forward only: {fms:.1f} ms, {ftf:.0f} TFLOP/s on 2TVH")
 
     cpu = None
-    if args.cpu_rows > 0:
+    if cpu_rows > 0:
         import oracle
         n = 16
         hh = synth.hidden_rows(lw, 0, n)
@@ -322,7 +327,7 @@ def bench_lmhead(args, torch, a3po, synth, log):
     line = {
         "metric": "tokens/sec and MFMA TFLOP/s (% peak) for A-3PO loss fwd+bwd through the LM head, "
                   "hidden 4,096 x vocab 151,936, 1 GPU",
-        "value": T * args.steps / dt, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "value": T * steps / dt, "unit": "tokens/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
         "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
         "data": "synthetic",
         "config": {"workload": f"{lw.name}: {w.S} seq x {w.L} tok = {T} tokens, hidden {H}, vocab {V}, bf16; logits "
@@ -336,7 +341,7 @@ def bench_lmhead(args, torch, a3po, synth, log):
                                                   "flops": 2.0 * T * V * H, "kernel": "lmhead_lse_kernel"}},
         "cpu_baseline": cpu,
     }
-    print(json.dumps(line), flush=True)
+    return line
 
 
 def main():
@@ -344,7 +349,8 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="1p5b")
+    ap.add_argument("--workload", default="8b",
+                    help="8b (default: the largest single-GPU logits workload), 1p5b, long, tiny, lmhead8b")
     ap.add_argument("--cpu-rows", type=int, default=32768, help="rows of the oracle baseline sample (0 = skip)")
     ap.add_argument("--phase", default="both", choices=["both", "ragged", "ones"],
                     help="time the workload's own mask, an all-ones mask, or both (default)")
@@ -352,6 +358,8 @@ def main():
                     help="also compute the per-token policy entropy in the row kernel (a3po_loss_fwd_bwd_ex)")
     ap.add_argument("--no-secondary", dest="secondary", action="store_false",
                     help="skip the short timing of the forward-only and vocabulary-sharded kernels")
+    ap.add_argument("--no-lmhead-leg", dest="lmhead_leg", action="store_false",
+                    help="skip the short run of the LM-head workload (lmhead8b) reported under secondary_kernels")
     ap.add_argument("--quiet", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -369,7 +377,7 @@ def main():
     a3po.lib()
     torch.cuda.set_device(0)
     if args.workload in synth.LMHEAD_WORKLOADS:
-        bench_lmhead(args, torch, a3po, synth, log)
+        print(json.dumps(bench_lmhead(args, torch, a3po, synth, log)), flush=True)
         return
     w = synth.WORKLOADS[args.workload]
     b = build_inputs(w, torch, a3po, synth, log)
@@ -419,6 +427,12 @@ def main():
     log(f"plain copy of the logits matrix: {copy_gbs:.0f} GB/s (read+write)")
 
     secondary = secondary_kernels(a3po, torch, w, b, adv, dz, ws, log) if args.secondary else None
+
+    if args.secondary and args.lmhead_leg:
+        # the LM-head workload on the same box in the same run: a few steps of the whole path from hidden states
+        leg = bench_lmhead(args, torch, a3po, synth, log, name="lmhead8b", steps=3, warmup=1, cpu_rows=0)
+        secondary["lmhead8b"] = {k: leg[k] for k in ("value", "unit", "steps", "warmup", "ms_per_step", "config",
+                                                      "roofline", "fused_forward")}
 
     cpu = None
     if args.cpu_rows > 0:
