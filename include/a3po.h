@@ -188,6 +188,25 @@ int a3po_loss_fwd_bwd(const void *logits, a3po_dtype dt, int64_t T, int64_t V, i
                       void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * a3po_loss_fwd_bwd for callers that cannot allocate or hand over device memory beyond inputs and outputs
+ * (code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): the workspace is an
+ * array built into the library, A3PO_NOALLOC_MAX_TOKENS tokens' worth (about 6 MB of every GPU the library
+ * runs on, held until the process ends).  The call allocates and frees nothing; its first use on a device looks
+ * up that device's copy of the array (one hipGetSymbolAddress).  Arguments, results and error codes are those
+ * of a3po_loss_fwd_bwd (same kernels: bit-identical outputs); T above A3PO_NOALLOC_MAX_TOKENS returns
+ * A3PO_E_SIZE.  Every call on a GPU shares that GPU's array: calls that overlap in time on one GPU race (issue
+ * them on one stream, or order the streams).  Nothing the array holds is carried from one call to the next.
+ */
+#define A3PO_NOALLOC_MAX_TOKENS 131072
+int a3po_loss_fwd_bwd_noalloc(const void *logits, a3po_dtype dt, int64_t T, int64_t V, int64_t ld,
+                              const int32_t *chosen, const float *logp_behav,
+                              const int32_t *versions, int32_t current_version,
+                              const float *advantages, const uint8_t *loss_mask,
+                              float clip_eps, float denom,
+                              void *dlogits, float *logp_out, float *logp_prox_out,
+                              float *loss_out, a3po_stats *stats_out, void *stream);
+
+/*
  * a3po_loss_fwd_bwd with the extras of a3po_loss_options (opt == NULL: no extras):
  *  - the two baselines the paper compares against through the same kernels: a caller-supplied
  *    proximal log-prob ("recompute"; lp = logp_prox_in[t], iw = exp(lp - lb), r = exp(lt - lp)) and

@@ -20,6 +20,8 @@ from .binding import (  # noqa: F401
     lib,
     lib_path,
     loss_fwd_bwd,
+    loss_fwd_bwd_noalloc,
+    NOALLOC_MAX_TOKENS,
     proximal_interp,
     shard_combine,
     shard_loss_bwd,

@@ -48,6 +48,8 @@ _SIGNATURES = {
                                                       _P, _P, _P, _P, _P, _P, _P, _SZ, _P]),
     "a3po_loss_fwd_bwd": (ctypes.c_int, [_P, ctypes.c_int, _I64, _I64, _I64, _P, _P, _P, _I32, _P, _P, _F32, _F32,
                                          _P, _P, _P, _P, _P, _P, _SZ, _P]),
+    "a3po_loss_fwd_bwd_noalloc": (ctypes.c_int, [_P, ctypes.c_int, _I64, _I64, _I64, _P, _P, _P, _I32, _P, _P, _F32,
+                                                 _F32, _P, _P, _P, _P, _P, _P]),
     "a3po_loss_fwd_bwd_ex": (ctypes.c_int, [_P, ctypes.c_int, _I64, _I64, _I64, _P, _P, _P, _I32, _P, _P, _F32,
                                             _F32, _P, _P, _P, _P, _P, _P, _SZ, _P, ctypes.POINTER(LossOptions)]),
     "a3po_count_tokens": (ctypes.c_int, [_P, _P, _I64, _I64, _P, _P, _P]),
@@ -244,6 +246,34 @@ def loss_fwd_bwd(logits, chosen, logp_behav, versions, current_version: int, adv
     if want_clipped:
         res["clipped"] = clipped
     return res
+
+
+NOALLOC_MAX_TOKENS = 131072  # A3PO_NOALLOC_MAX_TOKENS
+
+
+def loss_fwd_bwd_noalloc(logits, chosen, logp_behav, versions, current_version: int, advantages, loss_mask,
+                         clip_eps: float, denom: float, dlogits, logp, logp_prox, loss, stats, V=None):
+    """a3po_loss_fwd_bwd_noalloc: every output tensor is the caller's (dlogits like logits, logp / logp_prox
+    float32[T], loss float32[1], stats uint8[sizeof a3po_stats]; logp_prox and stats may be None); the call
+    itself allocates nothing, here or in the library."""
+    torch = _torch()
+    dt, T, V, ld = _logits_meta(logits, V)
+    _vec(chosen, torch.int32, T, "chosen")
+    _vec(logp_behav, torch.float32, T, "logp_behav")
+    _vec(versions, torch.int32, T, "versions")
+    _vec(advantages, torch.float32, T, "advantages")
+    _vec(loss_mask, torch.uint8, T, "loss_mask")
+    assert dlogits.dtype == logits.dtype and dlogits.shape == logits.shape and dlogits.stride() == logits.stride()
+    _vec(logp, torch.float32, T, "logp")
+    if logp_prox is not None:
+        _vec(logp_prox, torch.float32, T, "logp_prox")
+    _vec(loss, torch.float32, 1, "loss")
+    if stats is not None:
+        _vec(stats, torch.uint8, STATS_DTYPE.itemsize, "stats")
+    _check(lib().a3po_loss_fwd_bwd_noalloc(_ptr(logits), dt, T, V, ld, _ptr(chosen), _ptr(logp_behav), _ptr(versions),
+                                           int(current_version), _ptr(advantages), _ptr(loss_mask), float(clip_eps),
+                                           float(denom), _ptr(dlogits), _ptr(logp), _ptr(logp_prox), _ptr(loss),
+                                           _ptr(stats), _stream()), "a3po_loss_fwd_bwd_noalloc")
 
 
 def count_tokens(chosen, loss_mask, V: int, want_count=False):

@@ -1,11 +1,18 @@
 // extern "C" boundary: argument validation on the host, workspace carve-up, launches.
 #include <cmath>
+#include <mutex>
 
 #include "a3po.h"
 #include "a3po_common.h"
 #include "a3po_launch.h"
 
 using namespace a3po;
+
+// Workspace of the entry point that allocates nothing (a3po_loss_fwd_bwd_noalloc): the loss workspace of
+// A3PO_NOALLOC_MAX_TOKENS tokens (per-token records, objective, weights, flags, three-pass partials, per-workgroup
+// partials, each rounded up to 256 bytes).
+constexpr size_t kStaticWsBytes = A3PO_NOALLOC_MAX_TOKENS * (size_t)(16 + 4 + 4 + 1 + 4 + 16) + 8 * 256 + kLossScratchBytes;
+static __device__ __align__(256) unsigned char scratch[kStaticWsBytes];
 
 namespace {
 
@@ -23,6 +30,29 @@ int check_logits(const void *logits, int dt, int64_t T, int64_t V, int64_t ld)
     if (T > 0 && !logits) return A3PO_E_NULL;
     if (!aligned(logits, dt == A3PO_F32 ? 4 : 2)) return A3PO_E_ALIGN;  // element alignment; 16 bytes selects the fast kernels
     return A3PO_OK;
+}
+
+// ---- workspace of the entry point that allocates nothing ----------------------------------------------
+// One array per GPU, part of the loaded code object and held until the process ends.  In host code the
+// array's name is only a handle for hipGetSymbolAddress: the device address is looked up once per device,
+// with that device current, and every launch and copy uses the looked-up pointer.
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[kMaxDevices];  // device address of `scratch` on each GPU, 0 until looked up
+
+// device address of the current device's copy of `scratch` (nullptr on failure)
+void *static_workspace()
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess) return nullptr;
+        g_scratch_ptr[dev] = ptr;
+    }
+    return g_scratch_ptr[dev];
 }
 
 }  // namespace
@@ -186,6 +216,24 @@ int a3po_loss_fwd_bwd(const void *logits, a3po_dtype dt, int64_t T, int64_t V, i
     return a3po_loss_fwd_bwd_ex(logits, dt, T, V, ld, chosen, logp_behav, versions, current_version, advantages,
                                 loss_mask, clip_eps, denom, dlogits, logp_out, logp_prox_out, loss_out, stats_out,
                                 workspace, workspace_bytes, stream, nullptr);
+}
+
+int a3po_loss_fwd_bwd_noalloc(const void *logits, a3po_dtype dt, int64_t T, int64_t V, int64_t ld,
+                              const int32_t *chosen, const float *logp_behav, const int32_t *versions,
+                              int32_t current_version, const float *advantages, const uint8_t *loss_mask,
+                              float clip_eps, float denom, void *dlogits, float *logp_out, float *logp_prox_out,
+                              float *loss_out, a3po_stats *stats_out, void *stream)
+{
+    if (T > (int64_t)A3PO_NOALLOC_MAX_TOKENS) return A3PO_E_SIZE;
+    static_assert(kStaticWsBytes % 256 == 0, "the carve-up below assumes 256-byte granules");
+    if (T > 0 && loss_ws_layout(T).total > kStaticWsBytes) return A3PO_E_SIZE;  // (cannot happen below the token limit)
+    void *ws = static_workspace();
+    if (!ws) return A3PO_E_LAUNCH;
+    // Nothing in the array needs clearing here: the prep kernel rewrites the header, the per-token records and the
+    // row-queue counter at the start of every call, and every other field is written before it is read.
+    return a3po_loss_fwd_bwd_ex(logits, dt, T, V, ld, chosen, logp_behav, versions, current_version, advantages,
+                                loss_mask, clip_eps, denom, dlogits, logp_out, logp_prox_out, loss_out, stats_out, ws,
+                                kStaticWsBytes, stream, nullptr);
 }
 
 int a3po_count_tokens(const int32_t *chosen, const uint8_t *loss_mask, int64_t T, int64_t V, float *denom_out,
