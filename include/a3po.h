@@ -15,8 +15,10 @@
  *  - Data-dependent problems cannot be returned synchronously; they are counted in
  *    a3po_stats (chosen id outside [0,V) => the token is treated as masked; negative
  *    staleness => alpha = 1).
- *  - No global state: calls are re-entrant and may be issued from several host threads
- *    on different streams, as long as they do not share output buffers or a workspace.
+ *  - No state is kept between calls: they are re-entrant and may be issued from several host threads
+ *    on different streams, as long as they do not share output buffers or a workspace.  (Two one-time
+ *    set-ups exist and are thread-safe: the LM-head kernels' LDS limit, and the address of the array that
+ *    a3po_loss_fwd_bwd_noalloc uses in place of a workspace.)
  *  - Logits are row-major [T, V] with a row stride of `ld` elements (ld >= V), float32
  *    or bfloat16.  Row t pairs with chosen[t]; any next-token shift is the caller's.
  *    Base pointers of logits / dlogits must be aligned to their element size.  Rows whose base
@@ -341,7 +343,8 @@ int a3po_shard_loss_bwd(const void *logits_shard, a3po_dtype dt, int64_t T, int6
  * positive multiple of 64, at most 2^20 (A3PO_E_SIZE otherwise).  chosen [T] int32; an id outside [0,V) gives logp 0 (lse still written).
  * logp_out [T] float, lse_out [T] float (nullable).
  * workspace: a3po_workspace_bytes(A3PO_WS_FUSED_LMHEAD, T, V, H) bytes, 256-byte aligned.
- * The first call on a process raises the kernel's dynamic LDS limit (one hipFuncSetAttribute).
+ * The first call in a process raises the kernel's dynamic LDS limit (one hipFuncSetAttribute, done once, safe
+ * against concurrent first calls from several host threads).
  */
 int a3po_fused_lmhead_logprob(const void *hidden, const void *weight, int64_t T, int64_t H, int64_t V,
                               const int32_t *chosen, float *logp_out, float *lse_out,
@@ -352,17 +355,18 @@ int a3po_fused_lmhead_logprob(const void *hidden, const void *weight, int64_t T,
  * then the gradient contracted back through the projection:
  *   z = hidden weight^T,  loss / log-probs / statistics as in a3po_loss_fwd_bwd (same arguments),
  *   dhidden[t, :] = sum_v dlogits[t, v] weight[v, :],   dweight[v, :] = sum_t dlogits[t, v] hidden[t, :].
- * Logits exist only for a chunk of 8,192 tokens at a time, in bfloat16, inside the workspace: the
- * log-probs therefore carry one bfloat16 rounding of each logit (abs error <= 2^-8 max|z|), unlike
- * a3po_fused_lmhead_logprob, which keeps fp32 logits on chip.  The three contractions are plain
- * GEMMs issued to rocBLAS (bfloat16 inputs, fp32 accumulation; dweight is accumulated over chunks
- * in fp32 and rounded to bfloat16 once); everything between them is this library's kernels.
+ * Tokens are taken in chunks of 8,192.  The log-sum-exp and the log-probs of a chunk are folded from fp32
+ * tiles as they leave the matrix cores, exactly as in a3po_fused_lmhead_logprob (both entry points give the
+ * same log pi_theta up to rounding order); the same tiles are also kept in fp32 inside the workspace, for
+ * that chunk only, and the gradient rows dlogits are formed from them in fp32 and rounded once to bfloat16,
+ * the operand type of the matrix cores.  The three contractions are this library's own kernel (bfloat16
+ * operands, fp32 accumulation); dweight is accumulated over the chunks in fp32 and rounded to bfloat16 once.
  * hidden, dhidden [T, H]; weight, dweight [V, H]: row-major, contiguous, bfloat16, 16-byte
- * aligned; H % 8 == 0, H <= 2^20 and V % 8 == 0.  Per-token arguments and outputs as in a3po_loss_fwd_bwd.
- * workspace: a3po_workspace_bytes(A3PO_WS_FUSED_LMHEAD_LOSS, T, V, H) bytes, 256-byte aligned (the fp32
- * accumulator of dweight, a chunk of logits and its transpose: about 4 V H + 4 * 8192 V bytes).
- * Unlike the other entry points this one keeps one process-wide rocBLAS handle, created on first
- * use (rocBLAS allocates its own scratch then); calls that share it must not overlap in time.
+ * aligned; H a positive multiple of 64, at most 2^20; V a multiple of 8 below 2^21; T below 2^22
+ * (A3PO_E_SIZE otherwise).  Per-token arguments and outputs as in a3po_loss_fwd_bwd.
+ * workspace: a3po_workspace_bytes(A3PO_WS_FUSED_LMHEAD_LOSS, T, V, H) bytes, 256-byte aligned: the fp32
+ * accumulator of dweight, W^T and h^T, and a chunk of logits (fp32) and of their gradient (bfloat16, in both
+ * orientations) - about 4 V H + 2 V H + 2 T H + 8 * 8192 V bytes, 14 GB at T = 65,536, H = 4,096, V = 151,936.
  */
 int a3po_fused_lmhead_loss_fwd_bwd(const void *hidden, const void *weight, int64_t T, int64_t H, int64_t V,
                                    const int32_t *chosen, const float *logp_behav,

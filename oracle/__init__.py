@@ -273,6 +273,18 @@ def lmhead_backward(dz, h, W, want_dh=True, want_dw=True):
     return dh, dW
 
 
+def lmhead_backward_matmul(dz, h, W):
+    """The two products of ``lmhead_backward``, dh = dz @ W and dW = dz.T @ h, through NumPy's float64 matrix
+    product instead of the plain loops: the same definition (bfloat16 operands widened exactly, float64 products
+    and sums; only the order of the additions is the library's), for sizes at which the loops would take minutes.
+    Pinned against the loops in tests/test_oracle_pins.py."""
+    h, W = _bf16(h), _bf16(W)
+    dz = _f64(dz)
+    hf = (h.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+    Wf = (W.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+    return dz @ Wf, dz.T @ hf
+
+
 def plan_microbatches(seq_len, n_minibatches, max_tokens):
     """Reference plan of the mini-batch / micro-batch split (Section 4.1: 4 gradient updates per step,
     at most 10,240 tokens per pass), in plain Python.

@@ -10,7 +10,8 @@ ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 OBJ = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "liba3po.so")
-SOURCES = ["a3po_api.hip", "a3po_rows.hip", "a3po_tokens.hip", "a3po_shard.hip", "a3po_lmhead.hip", "a3po_lmhead_bwd.hip"]
+SOURCES = ["a3po_api.hip", "a3po_rows.hip", "a3po_tokens.hip", "a3po_shard.hip", "a3po_gemm.hip", "a3po_lmhead.hip",
+           "a3po_lmhead_bwd.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 # packed fp32 VALU forms are switched off for every device translation unit
 # (the atomic optimizer would turn the row queue's one-lane atomic into a wave-wide scan that
@@ -44,9 +45,7 @@ def build(force: bool = True, verbose: bool = False) -> str:
     os.makedirs(OBJ, exist_ok=True)
     with ThreadPoolExecutor(max_workers=len(SOURCES)) as ex:
         objs = list(ex.map(_compile, sources()))
-    rocm_lib = os.path.join(os.path.dirname(os.path.dirname(os.path.realpath(HIPCC))), "lib")
-    subprocess.check_call([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs,
-                           "-L", rocm_lib, "-lrocblas", f"-Wl,-rpath,{rocm_lib}"])
+    subprocess.check_call([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs])
     if verbose:
         print("built", LIB)
     return LIB

@@ -1,0 +1,457 @@
+// bfloat16 contraction on the matrix cores for the LM-head path:  C[M, N] = A[M, K] B[N, K]^T, both operands
+// row-major with the contracted index contiguous, fp32 accumulation (v_mfma_f32_32x32x16_bf16), and one of four
+// epilogues applied to each 256 x 256 tile as it leaves the accumulators:
+//   kEpiLse        fold the tile into a running (max, sum) per column n over the rows m (the online log-sum-exp
+//                  of the vocabulary when A is the LM-head weight and B the hidden states); C is not written
+//   kEpiLseStore   the same, and the tile is also stored as fp32 (the logits of a token chunk, kept for the
+//                  backward pass)
+//   kEpiStoreBf16  the tile is stored as bfloat16 (the gradient of the hidden states)
+//   kEpiAccumF32   the tile is stored as fp32, or added to what C holds (the weight gradient, summed over chunks)
+//
+// Tiling.  A workgroup of 256 threads (4 wavefronts, one per SIMD) computes a 256 x 256 tile, each wavefront a
+// 128 x 128 quarter = 4 x 4 MFMA tiles = 256 accumulator registers.  In the 32 x 32 result layout a lane owns
+// one column n and 16 rows m of each MFMA tile, so a reduction over m is mostly per lane, and a store of one
+// accumulator register covers 32 consecutive n of two rows.
+//
+// K is walked in stages of 32 through a ring of LDS buffers that direct global -> LDS loads
+// (global_load_lds_dwordx4: lane l of a wavefront lands at lds_base + 16 l; no staging registers, no LDS write
+// instructions) fill a few stages ahead.  LDS layout of one operand stage: 256 rows x 64 bytes, unpadded; the
+// 16-byte piece p of row r sits at physical piece p ^ ((r >> 2) & 3) - the permutation is applied on the global
+// side of the load - so a fragment read (16 consecutive rows, same logical piece) touches 16 distinct bank groups.
+//
+// Schedule of stage i (two k-steps of 16 MFMAs).  A wavefront holds the fragments of a whole stage in registers,
+// twice (this stage and the next).  At the top of stage i it waits for its own loads of stage i+1 and its own
+// fragment reads of stage i, and all wavefronts meet at one barrier: stage i+1 is now visible and the slot of
+// stage i is free.  During the 32 MFMAs of stage i the 16 fragments of stage i+1 are read and the 8 direct loads
+// of stage i + kDmaStages go into the freed slot, two reads and one load per group of four MFMAs.  The ring runs
+// through a workgroup's whole sequence of tiles without a break: the refills of a tile's last stages already
+// bring the next tile's first stages, so a tile's epilogue overlaps with their arrival.
+//
+// Tile order.  One persistent workgroup per compute unit; the workgroups of an XCD (dispatch order deals
+// workgroups round-robin over the XCDs) form a block of ml_count x 4 tiles that share ml_count tiles of A and 4
+// tiles of B through that XCD's L2.  The tile grid is cut into such blocks ("pairs" of a 4-tile column group and an
+// ml_count-tile row round); pair p = group * rounds + round, and each XCD takes a contiguous range of pairs, i.e.
+// it sweeps down the rows of one column group before it moves to the next.  With kEpiLse* a workgroup therefore
+// keeps its running (max, sum) in registers over a whole sweep and writes one partial per column per sweep.
+#include <mutex>
+
+#include "a3po_common.h"
+#include "a3po_launch.h"
+
+namespace a3po {
+
+constexpr int kGemmTile = 256;  // tile edge, both sides
+constexpr int kGemmThreads = 256;
+constexpr int kGemmColTiles = 4;  // tiles of B (columns) side by side in an XCD's block
+
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float f32x16_t __attribute__((ext_vector_type(16)));
+typedef uint32_t gemm_u32x4_t __attribute__((ext_vector_type(4)));
+
+constexpr int kDmaStages = 4;
+constexpr int kDmaK = 32;                                  // K elements per stage
+constexpr int kDmaRowBytes = kDmaK * 2;                    // 64
+constexpr int kDmaOperandBytes = kGemmTile * kDmaRowBytes; // 16,384
+constexpr int kDmaStageBytes = 2 * kDmaOperandBytes;       // 32,768
+constexpr int kDmaRingBytes = kDmaStages * kDmaStageBytes; // 131,072 of the compute unit's 163,840
+constexpr int kGemmRedBytes = 2 * kGemmTile * (int)sizeof(float2);  // column partials of the two row halves
+constexpr int kGemmLdsBytes = kDmaRingBytes + kGemmRedBytes;
+
+typedef __attribute__((address_space(3))) void *lds_ptr_t;
+
+__device__ __forceinline__ void dma16(const char *g, char *l)
+{
+    __builtin_amdgcn_global_load_lds(reinterpret_cast<const gemm_u32x4_t *>(g), (lds_ptr_t)l, 16, 0, 0);
+}
+
+// s_waitcnt with the given vector-memory and LDS counts (the export count is left alone)
+__device__ __forceinline__ constexpr int waitcnt_imm(int vmcnt, int lgkmcnt)
+{
+    return 0x0070 | (vmcnt & 15) | ((vmcnt >> 4) << 14) | ((lgkmcnt & 15) << 8);
+}
+constexpr int kNoVmWait = 63, kNoLgkmWait = 15;
+
+// Folds the 64 rows this lane holds of column block b (4 MFMA tiles x 16 values) into the lane's running
+// (max, sum).  Row offset of acc[a][b][4 i + j] inside the lane's slice is a 32 + 8 i + j; offsets >= mlim lie
+// past the last row (only in the last, ragged tile).  The accumulators are only read.
+// The scheduling fences after each MFMA tile keep the copies of the accumulators short-lived: without them the
+// register allocator spills across the K loop and a reload there waits for every direct load in flight.
+template <bool RAGGED>
+__device__ __forceinline__ void fold_column(const f32x16_t (&acc)[4][4], int b, int mlim, float &run_m, float &run_s)
+{
+    float mx = -INFINITY;
+#pragma unroll
+    for (int a = 0; a < 4; ++a) {
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+            float v = acc[a][b][e];
+            if (RAGGED && a * 32 + (e >> 2) * 8 + (e & 3) >= mlim) v = -INFINITY;
+            mx = fmaxf(mx, v);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    const float m_new = fmaxf(run_m, mx);
+    float s = run_s * exp2_hw((run_m - m_new) * kLog2e);
+#pragma unroll
+    for (int a = 0; a < 4; ++a) {
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+            float v = acc[a][b][e];
+            if (RAGGED && a * 32 + (e >> 2) * 8 + (e & 3) >= mlim) v = -INFINITY;
+            s += exp2_hw((v - m_new) * kLog2e);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    run_m = m_new;
+    run_s = s;
+}
+
+// One accumulator register of every MFMA tile goes to row (8 i + j + 4 (lane >> 5)) of its 32-row block and to
+// column lane & 31: a wavefront's store of one register covers two rows x 32 consecutive columns.
+// EDGE: the tile reaches past M or N; rows / columns beyond are skipped.
+template <int EPI, bool EDGE>
+__device__ __forceinline__ void store_tile(const f32x16_t (&acc)[4][4], void *C, int64_t ldc, int64_t m0, int64_t n0,
+                                           int64_t M, int64_t N, int wm, int wn, int lane, bool add)
+{
+    const int col0 = wn * 128 + (lane & 31);
+    const int row0 = wm * 128 + 4 * (lane >> 5);
+    const int rows_left = (int)(M - m0 < kGemmTile ? M - m0 : kGemmTile);
+    const int cols_left = (int)(N - n0 < kGemmTile ? N - n0 : kGemmTile);
+#pragma unroll
+    for (int a = 0; a < 4; ++a) {
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+            const int row = row0 + a * 32 + (e >> 2) * 8 + (e & 3);
+            if (EDGE && row >= rows_left) continue;
+            const int64_t at = (m0 + row) * ldc + n0 + col0;
+#pragma unroll
+            for (int b = 0; b < 4; ++b) {
+                if (EDGE && col0 + b * 32 >= cols_left) continue;
+                const float v = acc[a][b][e];
+                if constexpr (EPI == kEpiStoreBf16) {
+                    reinterpret_cast<uint16_t *>(C)[at + b * 32] = (uint16_t)(pack_bf16x2(v, 0.0f) & 0xFFFFu);
+                } else if constexpr (EPI == kEpiAccumF32) {
+                    float *p = reinterpret_cast<float *>(C) + at + b * 32;
+                    // every element has one owner per launch and launches are ordered on the stream, so the sum is
+                    // deterministic; the add is done by the memory side and nobody waits for its result
+                    if (add) unsafeAtomicAdd(p, v);
+                    else *p = v;
+                } else {
+                    reinterpret_cast<float *>(C)[at + b * 32] = v;
+                }
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    }
+}
+
+// QUAD: K is a multiple of kDmaStages stages.  Then every tile starts in ring slot 0, the K loop is unrolled by
+// the ring depth (all LDS addresses are constants) and the refill cursor moves once per kDmaStages stages.
+// Otherwise the loop is unrolled by two (the fragment buffers alternate; the number of stages is even) and slot
+// and cursor are tracked per stage.
+template <int EPI, bool QUAD>
+__global__ __launch_bounds__(kGemmThreads) void gemm_nt_kernel(const GemmArgs g)
+{
+    extern __shared__ __align__(16) char lds[];
+    constexpr bool LSE = EPI == kEpiLse || EPI == kEpiLseStore;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave & 1, wn = wave >> 1;  // row half, column half of the tile
+    const int xcd = (int)(blockIdx.x % (unsigned)g.nxcd), slot = (int)(blockIdx.x / (unsigned)g.nxcd);
+    const int nl = slot & (kGemmColTiles - 1), ml = slot / kGemmColTiles;
+    const int64_t M = g.M, N = g.N;
+    const int mtiles = (int)((M + kGemmTile - 1) / kGemmTile), ntiles = (int)((N + kGemmTile - 1) / kGemmTile);
+    const int groups = (ntiles + kGemmColTiles - 1) / kGemmColTiles;
+    const int rounds = (mtiles + g.ml_count - 1) / g.ml_count;
+    const int64_t pairs = (int64_t)groups * rounds;
+    const int64_t p_end = (int64_t)(xcd + 1) * pairs / g.nxcd;
+    const int nstages = (int)(g.K / kDmaK);
+    const int wave_s = __builtin_amdgcn_readfirstlane(wave);  // the wavefront number in a scalar register
+    const uint32_t lda2 = (uint32_t)g.lda * 2u, ldb2 = (uint32_t)g.ldb * 2u;  // row strides in bytes
+
+    // the first pair >= p in this XCD's range whose tile exists for this workgroup's place in the block (else p_end)
+    auto next_tile = [&](int64_t p) {
+        for (; p < p_end; ++p) {
+            const int grp = (int)(p / rounds), rnd = (int)(p % rounds);
+            if (rnd * g.ml_count + ml < mtiles && grp * kGemmColTiles + nl < ntiles) break;
+        }
+        return p;
+    };
+
+    // direct loads: instruction j of an operand covers tile rows (4 j + wave) 16 .. + 15; lane -> row lane >> 2,
+    // physical piece lane & 3, which holds logical piece (lane & 3) ^ ((row >> 2) & 3) = (lane & 3) ^ ((lane >> 4) & 3)
+    const int drow = lane >> 2;
+    const uint32_t dpiece = (uint32_t)((lane & 3) ^ ((lane >> 4) & 3)) * 16u;
+    // fragment reads: row lane & 31 of a 32-row MFMA tile, k half lane >> 5 of k-step s: logical piece 2 s + (lane >> 5),
+    // physical piece that ^ ((row >> 2) & 3) = that ^ ((lane >> 2) & 3)
+    const uint32_t fr[2] = {(uint32_t)(lane & 31) * kDmaRowBytes + (uint32_t)(((lane >> 5) ^ ((lane >> 2) & 3)) * 16),
+                            (uint32_t)(lane & 31) * kDmaRowBytes + (uint32_t)(((2 + (lane >> 5)) ^ ((lane >> 2) & 3)) * 16)};
+    const uint32_t fa_base = (uint32_t)(wm * 128) * kDmaRowBytes;
+    const uint32_t fb_base = kDmaOperandBytes + (uint32_t)(wn * 128) * kDmaRowBytes;
+
+    int64_t p_cur = next_tile((int64_t)xcd * pairs / g.nxcd);
+    if (p_cur >= p_end) return;  // uniform over the workgroup
+
+    // The refill cursor names the tile (r_p) and stage (r_k; QUAD: the first of a group of kDmaStages stages) that
+    // the next refill loads.  Past the workgroup's last tile it stays on that tile's last stage (group): reloads of
+    // bytes that are already there, which keep the number of loads per stage, and with it the s_waitcnt
+    // arithmetic, constant.  Rows past the end of an operand are clamped (computed, never written).
+    int64_t r_p = p_cur;
+    int r_k = 0;
+    const char *r_a = nullptr, *r_b = nullptr;
+    uint32_t aoff[4], boff[4];
+    auto set_tile = [&](int64_t p) {
+        const int mt = (int)(p % rounds) * g.ml_count + ml, nt = (int)(p / rounds) * kGemmColTiles + nl;
+        r_a = reinterpret_cast<const char *>(g.A + (int64_t)mt * kGemmTile * g.lda);
+        r_b = reinterpret_cast<const char *>(g.B + (int64_t)nt * kGemmTile * g.ldb);
+        const int m_last = (int)(M - 1 - (int64_t)mt * kGemmTile), n_last = (int)(N - 1 - (int64_t)nt * kGemmTile);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int r = (4 * j + wave) * 16 + drow;
+            aoff[j] = (uint32_t)min(r, m_last) * lda2 + dpiece;
+            boff[j] = (uint32_t)min(r, n_last) * ldb2 + dpiece;
+        }
+    };
+    set_tile(r_p);
+    // direct load number q of one operand (0: A rows, 1: B rows) of stage r_k + u into ring slot sl
+    auto refill = [&](int sl, int q, int u, int operand) {
+        const uint32_t koff = (uint32_t)(r_k + u) * (uint32_t)kDmaRowBytes;
+        char *dst = lds + sl * kDmaStageBytes + wave_s * 1024 + q * 4096;
+        if (operand == 0) dma16(r_a + koff + aoff[q], dst);
+        else dma16(r_b + koff + boff[q], dst + kDmaOperandBytes);
+    };
+    auto advance = [&](int step) {
+        if (r_k + step < nstages) {
+            r_k += step;
+        } else {
+            const int64_t np = next_tile(r_p + 1);
+            if (np < p_end) {
+                r_p = np;
+                r_k = 0;
+                set_tile(np);
+            }
+        }
+    };
+
+    // prologue: fill the whole ring, then wait for the first stage and read its fragments
+#pragma unroll
+    for (int st = 0; st < kDmaStages; ++st) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            refill(st, q, QUAD ? st : 0, 0);
+            refill(st, q, QUAD ? st : 0, 1);
+        }
+        if (!QUAD) advance(1);
+    }
+    if (QUAD) advance(kDmaStages);
+    __builtin_amdgcn_s_waitcnt(waitcnt_imm(8 * (kDmaStages - 1), kNoLgkmWait));  // everything issued after the first stage may fly
+    __builtin_amdgcn_s_barrier();  // bare, as in the K loop: the rest of the ring stays in flight
+    bf16x8_t fa[2][2][4], fb[2][2][4];  // [buffer][k-step][MFMA tile]
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) {
+#pragma unroll
+        for (int a = 0; a < 4; ++a)
+            fa[0][ks][a] = *reinterpret_cast<const bf16x8_t *>(lds + fa_base + a * 32 * kDmaRowBytes + fr[ks]);
+#pragma unroll
+        for (int b = 0; b < 4; ++b)
+            fb[0][ks][b] = *reinterpret_cast<const bf16x8_t *>(lds + fb_base + b * 32 * kDmaRowBytes + fr[ks]);
+    }
+    int sl_dyn = 0;  // ring slot of the stage being computed (tracked only when !QUAD)
+
+    float run_m[4], run_s[4];  // kEpiLse*: this lane's four columns over the sweep
+#pragma unroll
+    for (int b = 0; b < 4; ++b) {
+        run_m[b] = kNegFloor;
+        run_s[b] = 0.0f;
+    }
+
+    while (p_cur < p_end) {
+        const int grp = (int)(p_cur / rounds);
+        const int64_t m0 = ((int64_t)(p_cur % rounds) * g.ml_count + ml) * kGemmTile;
+        const int64_t n0 = ((int64_t)grp * kGemmColTiles + nl) * kGemmTile;
+        f32x16_t acc[4][4];
+#pragma unroll
+        for (int a = 0; a < 4; ++a)
+#pragma unroll
+            for (int b = 0; b < 4; ++b)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) acc[a][b][e] = 0.0f;
+
+        // One stage out of the fragments in buffer p (read from ring slot sl during the stage before);
+        // u: the stage's position in the cursor's group (0 when !QUAD).
+        auto stage = [&](const int sl, const int u, const int p) __attribute__((always_inline)) {
+            const int nsl = sl + 1 == kDmaStages ? 0 : sl + 1;
+            const char *nxt = lds + nsl * kDmaStageBytes;
+            __builtin_amdgcn_sched_barrier(0);
+            // The next stage has landed (own loads: the kDmaStages - 2 stages after it may still be in flight) and
+            // this stage is in registers (own reads, lgkmcnt(0)): meet.  A bare barrier: the fence that
+            // __syncthreads() carries makes the compiler drain every direct load it can see in flight
+            // (vmcnt(0)), which would empty the ring at each stage.
+            __builtin_amdgcn_s_waitcnt(waitcnt_imm(8 * (kDmaStages - 2), 0));
+            __builtin_amdgcn_s_barrier();
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int grp8 = 0; grp8 < 8; ++grp8) {   // k-step grp8 >> 2, row MFMA tile grp8 & 3
+                const int ks = grp8 >> 2, q = grp8 & 3;
+                // two fragments of the next stage (the next tile's first stage, at the end of a tile) ...
+                if (q < 2) {
+#pragma unroll
+                    for (int a = 2 * q; a < 2 * q + 2; ++a)
+                        fa[p ^ 1][ks][a] = *reinterpret_cast<const bf16x8_t *>(nxt + fa_base + a * 32 * kDmaRowBytes + fr[ks]);
+                } else {
+#pragma unroll
+                    for (int b = 2 * q - 4; b < 2 * q - 2; ++b)
+                        fb[p ^ 1][ks][b] = *reinterpret_cast<const bf16x8_t *>(nxt + fb_base + b * 32 * kDmaRowBytes + fr[ks]);
+                }
+                // ... one direct load into the slot this stage came from ...
+                refill(sl, grp8 >> 1, u, grp8 & 1);
+                // ... and four MFMAs
+#pragma unroll
+                for (int b = 0; b < 4; ++b)
+                    acc[q][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[p][ks][q], fb[p][ks][b], acc[q][b], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        };
+        if (QUAD) {
+            static_assert(kDmaStages == 4, "the unrolled loop names the four ring slots");
+#pragma unroll 1
+            for (int i = 0; i < nstages; i += kDmaStages) {
+                stage(0, 0, 0);
+                stage(1, 1, 1);
+                stage(2, 2, 0);
+                stage(3, 3, 1);
+                advance(kDmaStages);
+            }
+        } else {
+#pragma unroll 1
+            for (int i = 0; i < nstages; i += 2) {  // K % 64 == 0: an even number of stages
+                stage(sl_dyn, 0, 0);
+                advance(1);
+                sl_dyn = sl_dyn + 1 == kDmaStages ? 0 : sl_dyn + 1;
+                stage(sl_dyn, 0, 1);
+                advance(1);
+                sl_dyn = sl_dyn + 1 == kDmaStages ? 0 : sl_dyn + 1;
+            }
+        }
+
+        // ---- the tile's epilogue, while the next tile's first stages arrive ----
+        const int64_t p_next = next_tile(p_cur + 1);
+        const bool edge = m0 + kGemmTile > M || n0 + kGemmTile > N;  // uniform
+        if constexpr (EPI != kEpiLse) {
+            if (edge) store_tile<EPI, true>(acc, g.C, g.ldc, m0, n0, M, N, wm, wn, lane, g.accumulate != 0);
+            else store_tile<EPI, false>(acc, g.C, g.ldc, m0, n0, M, N, wm, wn, lane, g.accumulate != 0);
+        }
+        if constexpr (LSE) {
+            const bool ragged = m0 + kGemmTile > M;
+            const int mlim = (int)(M - m0) - wm * 128 - (lane >> 5) * 4;
+#pragma unroll
+            for (int b = 0; b < 4; ++b) {
+                if (ragged) fold_column<true>(acc, b, mlim, run_m[b], run_s[b]);
+                else fold_column<false>(acc, b, mlim, run_m[b], run_s[b]);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            // end of this column group's sweep: merge the two lane halves, then the two row halves, and write the
+            // workgroup's partial of its 256 columns (the reduction has LDS of its own: the ring keeps running)
+            if (p_next >= p_end || (int)(p_next / rounds) != grp) {
+                float2 *red = reinterpret_cast<float2 *>(lds + kDmaRingBytes);  // [2][256]
+#pragma unroll
+                for (int b = 0; b < 4; ++b) {
+                    MaxSum mine = {run_m[b], run_s[b]};
+                    MaxSum other = {__shfl_xor(mine.m, 32, kWave), __shfl_xor(mine.s, 32, kWave)};
+                    mine = combine(mine, other);
+                    if (lane < 32) red[wm * kGemmTile + wn * 128 + b * 32 + lane] = make_float2(mine.m, mine.s);
+                    run_m[b] = kNegFloor;
+                    run_s[b] = 0.0f;
+                }
+                // (the empty asm statements keep the compiler from moving LDS accesses across the bare barriers)
+                asm volatile("" ::: "memory");
+                __builtin_amdgcn_s_waitcnt(waitcnt_imm(kNoVmWait, 0));
+                __builtin_amdgcn_s_barrier();
+                asm volatile("" ::: "memory");
+                const float2 q0 = red[tid], q1 = red[kGemmTile + tid];
+                const MaxSum tot = combine(MaxSum{q0.x, q0.y}, MaxSum{q1.x, q1.y});
+                if (n0 + tid < N) g.partial[(int64_t)(xcd * g.ml_count + ml) * g.partial_stride + n0 + tid] = make_float2(tot.m, tot.s);
+                asm volatile("" ::: "memory");
+                __builtin_amdgcn_s_waitcnt(waitcnt_imm(kNoVmWait, 0));  // red is read before anyone writes it again
+                __builtin_amdgcn_s_barrier();
+                asm volatile("" ::: "memory");
+            }
+        }
+        p_cur = p_next;
+    }
+    // drain: the reloads past the last stage must have landed before the workgroup ends
+    __builtin_amdgcn_s_waitcnt(waitcnt_imm(0, 0));
+    __builtin_amdgcn_s_barrier();
+}
+
+// Sets every (max, sum) partial to the neutral element, so that slots no workgroup writes (an XCD that did not
+// touch a column group) drop out of the merge.
+__global__ void gemm_partials_init_kernel(float2 *partial, int64_t n)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) partial[i] = make_float2(kNegFloor, 0.0f);
+}
+
+// ---------------------------------------------------------------------------------------
+// host side
+
+// Shape of the persistent grid on the current device: one workgroup per compute unit, dealt round-robin to the
+// XCDs by the dispatcher (eight XCDs on the full chip; a partition with fewer than 64 compute units is one XCD).
+GemmGrid gemm_grid()
+{
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
+        cus = 256;
+    GemmGrid gg;
+    gg.nxcd = (cus >= 64 && cus % 8 == 0) ? 8 : 1;
+    gg.ml_count = cus / gg.nxcd / kGemmColTiles;
+    if (gg.ml_count < 1) gg.ml_count = 1;
+    if (gg.nxcd * gg.ml_count > kGemmMaxPartialSlots) gg.ml_count = kGemmMaxPartialSlots / gg.nxcd;
+    gg.blocks = gg.nxcd * gg.ml_count * kGemmColTiles;
+    return gg;
+}
+
+size_t gemm_partial_slots() { const GemmGrid gg = gemm_grid(); return (size_t)gg.nxcd * gg.ml_count; }
+
+template <int EPI>
+static hipError_t launch_gemm_t(GemmArgs g, hipStream_t s)
+{
+    const GemmGrid gg = gemm_grid();
+    g.nxcd = gg.nxcd;
+    g.ml_count = gg.ml_count;
+    const bool quad = g.K % (kDmaK * kDmaStages) == 0;
+    auto *kernel = quad ? gemm_nt_kernel<EPI, true> : gemm_nt_kernel<EPI, false>;
+    // the kernels' dynamic LDS limit is raised once per process and variant, race-free
+    static std::once_flag once[2];
+    static hipError_t attr_err[2];
+    std::call_once(once[quad], [&] {
+        attr_err[quad] = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLdsBytes);
+    });
+    if (attr_err[quad] != hipSuccess) return attr_err[quad];
+    if (EPI == kEpiLse || EPI == kEpiLseStore) {
+        const int64_t n = (int64_t)gg.nxcd * gg.ml_count * g.partial_stride;
+        hipLaunchKernelGGL(gemm_partials_init_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, g.partial, n);
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL(kernel, dim3(gg.blocks), dim3(kGemmThreads), kGemmLdsBytes, s, g);
+    return hipGetLastError();
+}
+
+hipError_t launch_gemm_nt(const GemmArgs &g, int epilogue, hipStream_t s)
+{
+    // what the kernel's 32-bit offsets and its stage arithmetic assume
+    if (g.M <= 0 || g.N <= 0 || g.K <= 0 || g.K % 64 != 0 || g.lda % 8 != 0 || g.ldb % 8 != 0 || g.lda < g.K ||
+        g.ldb < g.K || g.lda > (1 << 22) || g.ldb > (1 << 22))
+        return hipErrorInvalidValue;
+    switch (epilogue) {
+        case kEpiLse: return launch_gemm_t<kEpiLse>(g, s);
+        case kEpiLseStore: return launch_gemm_t<kEpiLseStore>(g, s);
+        case kEpiStoreBf16: return launch_gemm_t<kEpiStoreBf16>(g, s);
+        case kEpiAccumF32: return launch_gemm_t<kEpiAccumF32>(g, s);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+}  // namespace a3po

@@ -121,9 +121,44 @@ int64_t shard_bwd_queue_items(int dt, int64_t T, int64_t Vs);  // bursts launch_
 // a.V is the shard width here; a.ws_records must come from a prep launch made with the full vocabulary size
 hipError_t launch_shard_bwd_rows(const LossArgs &a, int64_t v0, const float *logp_theta, const float *lse, hipStream_t s);
 
+// ---- bfloat16 contraction on the matrix cores (a3po_gemm.hip): C[M, N] = A[M, K] B[N, K]^T ------------------
+enum GemmEpilogue {
+    kEpiLse = 0,        // running (max, sum) per column n over the rows m -> partial; C untouched
+    kEpiLseStore = 1,   // the same, and C (float) = the product
+    kEpiStoreBf16 = 2,  // C (bfloat16) = the product
+    kEpiAccumF32 = 3    // C (float) = the product, or += when accumulate is set
+};
+
+struct GemmArgs {
+    const uint16_t *A;  // [M, K] bfloat16, row-major, row stride lda elements (a multiple of 8; 16-byte aligned base)
+    int64_t lda;
+    const uint16_t *B;  // [N, K] likewise
+    int64_t ldb;
+    int64_t M, N, K;    // K a multiple of 64 (operands that need it are zero-padded by the caller)
+    void *C;            // [M, N] row-major, row stride ldc elements
+    int64_t ldc;
+    float2 *partial;    // kEpiLse*: [gemm_partial_slots()][partial_stride] (max, sum) per column, merged by the caller
+    int64_t partial_stride;
+    int accumulate;     // kEpiAccumF32
+    int nxcd, ml_count; // filled in by the launcher from the device
+};
+
+struct GemmGrid {
+    int nxcd, ml_count, blocks;
+};
+GemmGrid gemm_grid();
+constexpr int kGemmMaxPartialSlots = 64;  // workspaces are sized for this many; gemm_partial_slots() never exceeds it
+size_t gemm_partial_slots();
+hipError_t launch_gemm_nt(const GemmArgs &g, int epilogue, hipStream_t s);
+
 size_t lmhead_workspace_bytes(int64_t T);
 hipError_t launch_fused_lmhead_logprob(const void *hidden, const void *weight, int64_t T, int64_t H, int64_t V,
                                        const int32_t *chosen, float *logp, float *lse, void *workspace, hipStream_t s);
+
+// merges the (max, sum) partials of a token, adds the chosen logit (a dot product) and writes lse and log pi
+hipError_t launch_lmhead_lse_finish(const void *hidden, const void *weight, int64_t T, int64_t H, int64_t V,
+                                    const int32_t *chosen, const float2 *partial, int64_t partial_stride, float *logp,
+                                    float *lse, hipStream_t s);
 
 size_t lmhead_bwd_workspace_bytes(int64_t T, int64_t V, int64_t H);
 

@@ -1,24 +1,19 @@
 // A-3PO loss forward + backward starting from hidden states and the LM-head weight.
 //
-// The logits of a chunk of tokens are materialised in bfloat16 (chunk x V), run through the fused
-// row kernel in place (log-softmax, proximal interpolation, clipped surrogate, gradient rows), and
-// the gradient chunk is contracted back:  dh = dz W  and  dW += dz^T h.  With 288 GB of HBM a
-// chunk of 8,192 tokens (2.5 GB at V = 151,936) is small change, so the projection is computed
-// once (6 T V H flops in total) instead of being recomputed for the backward pass.
-//
-// The three contractions are plain GEMMs and go to rocBLAS (bfloat16 in, fp32 accumulate); dW is
-// accumulated across chunks in fp32 and rounded to bfloat16 once at the end.  Everything between
-// the GEMMs is this library's own kernels.
-//
-// dW = dz^T h contracts over the tokens, which is the slow dimension of both dz [n, V] and h [n, H] as they
-// lie in memory; the matrix cores want the contracted index contiguous.  The gradient chunk and the hidden
-// chunk are therefore transposed once (dzT [V, n], hT [H, n]; one more read and write of the chunk) and the
-// product runs in the form with both operands contiguous along the tokens: 8.05 against 9.93 ms per chunk
-// for the GEMM at the 8B shape, about 1 ms for the two transposes.
-#include <mutex>
-
-#include <rocblas/rocblas.h>
-
+// Tokens are processed in chunks.  For each chunk
+//   1. z^T = W h_chunk^T on the matrix cores; every 256 x 256 tile is folded into the running (max, sum) of its
+//      tokens while it is still in the accumulators (fp32: the log-sum-exp and the log-probs never see a rounded
+//      logit) and is also stored, as fp32, vocabulary-major, for the backward pass of the same chunk;
+//   2. log pi_theta, then Eq. 2 - Eq. 4 per token: loss terms, statistics and g_t = d loss / d log pi_theta;
+//   3. dz[t, v] = g_t ([v == y_t] - exp(z[t, v] - lse_t)), rounded once to bfloat16 (the matrix cores take
+//      bfloat16 operands), written token-major and vocabulary-major in one pass over the stored logits;
+//   4. dh_chunk = dz W            (contraction over the vocabulary: dz token-major against W^T)
+//   5. dW     += dz^T h_chunk     (contraction over the tokens: dz vocabulary-major against h^T; fp32
+//      accumulator across chunks, rounded to bfloat16 once at the end).
+// All three contractions are the kernel of a3po_gemm.hip, which wants the contracted index contiguous in both
+// operands; W^T and h^T are therefore written once per call.  6 T V H flops per step: the logits of a chunk are
+// kept (4 bytes each, 5 GB for 8,192 tokens at V = 151,936) rather than recomputed, which would be a fourth
+// contraction.
 #include "a3po_common.h"
 #include "a3po_launch.h"
 
@@ -28,25 +23,36 @@ namespace a3po {
 #define A3PO_LM_BWD_CHUNK 8192
 #endif
 constexpr int64_t kLmBwdChunk = A3PO_LM_BWD_CHUNK;  // tokens whose logits live in HBM at a time
+constexpr int64_t kPadK = 128;                      // contracted extents are zero-padded to this
 
 struct LmBwdLayout {
-    size_t loss_ws, zchunk, dzt, ht, dwacc, total;
-    int64_t chunk;
-    int64_t ldt;  // row stride of the transposed chunks: the chunk length rounded up to 8 tokens (16 bytes)
+    size_t lse, g, partial, zt, dzt, dz, wt, ht, dwacc, total;
+    int64_t chunk;  // tokens per chunk
+    int64_t ldn;    // row stride of the vocabulary-major chunk buffers: the chunk length padded to kPadK tokens
+    int64_t ldv;    // row stride of the token-major gradient chunk and of W^T: V padded to kPadK
+    int64_t ldt;    // row stride of h^T: T padded to kPadK
 };
 
 static LmBwdLayout lmhead_bwd_layout(int64_t T, int64_t V, int64_t H)
 {
     auto up = [](size_t x) { return (x + 255) / 256 * 256; };
+    auto pad = [](int64_t x) { return (x + kPadK - 1) / kPadK * kPadK; };
+    const size_t t = (size_t)(T > 0 ? T : 0), v = (size_t)V, h = (size_t)H;
     LmBwdLayout l;
     l.chunk = T < kLmBwdChunk ? (T > 0 ? T : 1) : kLmBwdChunk;
-    l.loss_ws = 0;
-    l.ldt = (l.chunk + 7) / 8 * 8;
-    l.zchunk = up(loss_ws_layout(T).total);
-    l.dzt = l.zchunk + up((size_t)l.chunk * (size_t)V * 2);
-    l.ht = l.dzt + up((size_t)V * (size_t)l.ldt * 2);
-    l.dwacc = l.ht + up((size_t)H * (size_t)l.ldt * 2);
-    l.total = l.dwacc + up((size_t)V * (size_t)H * sizeof(float));
+    l.ldn = pad(l.chunk);
+    l.ldv = pad(V);
+    l.ldt = pad(T > 0 ? T : 1);
+    l.lse = up(loss_ws_layout(T).total);
+    l.g = l.lse + up(t * sizeof(float));
+    l.partial = l.g + up(t * sizeof(float));
+    l.zt = l.partial + up((size_t)kGemmMaxPartialSlots * (size_t)l.chunk * sizeof(float2));
+    l.dzt = l.zt + up(v * (size_t)l.ldn * sizeof(float));
+    l.dz = l.dzt + up(v * (size_t)l.ldn * 2);
+    l.wt = l.dz + up((size_t)l.chunk * (size_t)l.ldv * 2);
+    l.ht = l.wt + up(h * (size_t)l.ldv * 2);
+    l.dwacc = l.ht + up(h * (size_t)l.ldt * 2);
+    l.total = l.dwacc + up(v * h * sizeof(float));
     return l;
 }
 
@@ -62,29 +68,27 @@ __global__ void f32_to_bf16_kernel(const float *__restrict__ src, uint16_t *__re
     }
 }
 
-// (a fill kernel rather than hipMemsetAsync, so that the call can be captured into a HIP graph)
+// (fill kernels rather than hipMemsetAsync, so that the call can be captured into a HIP graph)
 __global__ void zero_bf16_kernel(uint16_t *__restrict__ dst, size_t n)
 {
     const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i < n) dst[i] = 0;
 }
 
-static rocblas_handle blas_handle()
+// zeroes columns [c0, c1) of a row-major 2-byte matrix [R, ld]
+__global__ void zero_columns_kernel(uint16_t *__restrict__ m, int64_t R, int64_t ld, int64_t c0, int64_t c1)
 {
-    static rocblas_handle handle = nullptr;
-    static std::once_flag once;
-    std::call_once(once, [] {
-        if (rocblas_create_handle(&handle) != rocblas_status_success) handle = nullptr;
-    });
-    return handle;
+    const int64_t w = c1 - c0;
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < R * w) m[(i / w) * ld + c0 + i % w] = 0;
 }
 
-// out [C, ldo] = transpose of in [R, C] (row-major, 2-byte elements; C a multiple of 8, ldo >= R a multiple of 8).
+// out [C, ldo] = transpose of in [R, C] (row-major, contiguous, 2-byte elements; C a multiple of 8, ldo >= R a
+// multiple of 8); columns R .. ldo-1 of `out` (the padding of the contracted index) are written as zeros.
 // A workgroup moves a 64 x 64 tile through LDS: 16-byte loads along the columns, 16-byte stores along the rows.
-// Rows beyond R inside the last 8-row group of a tile are stored as zeros (they lie in the padding of `out`).
 constexpr int kTrTile = 64;
-__global__ __launch_bounds__(256) void transpose_bf16_kernel(const uint16_t *__restrict__ in, uint16_t *__restrict__ out,
-                                                             int64_t R, int64_t C, int64_t ldo)
+__global__ __launch_bounds__(256) void transpose_pad_bf16_kernel(const uint16_t *__restrict__ in, uint16_t *__restrict__ out,
+                                                                 int64_t R, int64_t C, int64_t ldo)
 {
     __shared__ uint16_t tile[kTrTile][kTrTile + 2];  // [row][column], padded: column reads below spread over the banks
     const int64_t r0 = (int64_t)blockIdx.y * kTrTile, c0 = (int64_t)blockIdx.x * kTrTile;
@@ -107,7 +111,7 @@ __global__ __launch_bounds__(256) void transpose_bf16_kernel(const uint16_t *__r
 #pragma unroll
     for (int pass = 0; pass < 2; ++pass) {
         const int c = tid / 8 + 32 * pass, rv = (tid % 8) * 8;
-        if (c0 + c >= C || r0 + rv >= R) continue;
+        if (c0 + c >= C || r0 + rv >= ldo) continue;
         uint32_t w[4];
 #pragma unroll
         for (int e = 0; e < 4; ++e)
@@ -116,23 +120,102 @@ __global__ __launch_bounds__(256) void transpose_bf16_kernel(const uint16_t *__r
     }
 }
 
-static hipError_t launch_transpose_bf16(const uint16_t *in, uint16_t *out, int64_t R, int64_t C, int64_t ldo, hipStream_t s)
+static hipError_t launch_transpose_pad(const uint16_t *in, uint16_t *out, int64_t R, int64_t C, int64_t ldo, hipStream_t s)
 {
-    const dim3 grid((unsigned)((C + kTrTile - 1) / kTrTile), (unsigned)((R + kTrTile - 1) / kTrTile));
-    hipLaunchKernelGGL(transpose_bf16_kernel, grid, dim3(256), 0, s, in, out, R, C, ldo);
+    const dim3 grid((unsigned)((C + kTrTile - 1) / kTrTile), (unsigned)((ldo + kTrTile - 1) / kTrTile));
+    hipLaunchKernelGGL(transpose_pad_bf16_kernel, grid, dim3(256), 0, s, in, out, R, C, ldo);
     return hipGetLastError();
 }
 
-// column-major C[m,n] = alpha op(A) op(B) + beta C with bf16 A, B and fp32 accumulation
-static bool gemm_bf16(rocblas_handle hd, rocblas_operation ta, rocblas_operation tb, int64_t m, int64_t n, int64_t k,
-                      const void *A, int64_t lda, const void *B, int64_t ldb, float beta, void *C, int64_t ldc,
-                      rocblas_datatype c_type)
+// Per-token terms of a chunk once its log-probs are known (Eq. 2 - Eq. 4): what the fused row kernel does for
+// logits that come from memory.  Tokens that do not enter the loss get zeros.
+__global__ void lmhead_token_terms_kernel(const TokenRecord *__restrict__ records, int64_t n, int32_t current_version,
+                                          float clip_eps, const WsHeader *__restrict__ hdr, float *logp, float *prox,
+                                          float *obj, float *iw, uint8_t *flags, float *g_out)
 {
-    const float alpha = 1.0f;
-    return rocblas_gemm_ex(hd, ta, tb, (rocblas_int)m, (rocblas_int)n, (rocblas_int)k, &alpha, A, rocblas_datatype_bf16_r,
-                           (rocblas_int)lda, B, rocblas_datatype_bf16_r, (rocblas_int)ldb, &beta, C, c_type,
-                           (rocblas_int)ldc, C, c_type, (rocblas_int)ldc, rocblas_datatype_f32_r,
-                           rocblas_gemm_algo_standard, 0, 0) == rocblas_status_success;
+    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= n) return;
+    const TokenRecord rec = records[t];
+    if (rec.y < 0) {
+        logp[t] = 0.0f;
+        if (prox) prox[t] = 0.0f;
+        obj[t] = 0.0f;
+        iw[t] = 0.0f;
+        flags[t] = 0;
+        g_out[t] = 0.0f;
+        return;
+    }
+    const TokenTerms tt = token_terms(logp[t], rec.lb, rec.ver, current_version, rec.A, clip_eps, hdr->inv_n, A3PO_PROX_INTERP);
+    if (prox) prox[t] = tt.lp;
+    obj[t] = tt.obj;
+    iw[t] = tt.iw;
+    flags[t] = (uint8_t)(kFlagCounted | (tt.clipped ? kFlagClipped : 0) | (tt.negative_staleness ? kFlagNegStale : 0));
+    g_out[t] = tt.g;
+}
+
+// Gradient of a chunk's logits from the stored fp32 logits z^T [V, ldn] (vocabulary-major):
+//   dz[t, v] = g_t ([v == y_t] - exp(z[t, v] - lse_t)),
+// rounded once to bfloat16 and written both vocabulary-major (dzt [V, ldn], the operand of the weight gradient)
+// and token-major (dz [n, ldv], the operand of the hidden-state gradient).  A workgroup takes a tile of 64
+// vocabulary rows x 64 tokens: 16-byte loads and 8-byte stores along the tokens, then through LDS 16-byte stores
+// along the vocabulary.  Token columns n .. (multiple of 64) of dzt are written as zeros (they pad the
+// contraction over the tokens); a token with g = 0 gives an exactly zero column.
+constexpr int kDzTile = 64;
+__global__ __launch_bounds__(256) void lmhead_dz_kernel(const float *__restrict__ zt, int64_t V, int64_t n, int64_t ldn,
+                                                        const float *__restrict__ lse, const float *__restrict__ g,
+                                                        const TokenRecord *__restrict__ records,
+                                                        uint16_t *__restrict__ dzt, uint16_t *__restrict__ dz, int64_t ldv)
+{
+    __shared__ __align__(16) uint16_t tile[kDzTile][kDzTile + 8];  // [token][vocabulary row], rows 144 bytes apart
+    const int tid = threadIdx.x;
+    const int64_t v0 = (int64_t)blockIdx.x * kDzTile, t0 = (int64_t)blockIdx.y * kDzTile;
+    const int tq = tid & 15;            // this thread's four tokens: t0 + 4 tq ..
+    const int64_t t4 = t0 + 4 * tq;
+    float neg_g[4], tl[4];
+    int32_t ty[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const bool in = t4 + i < n;
+        neg_g[i] = in ? -g[t4 + i] : 0.0f;
+        tl[i] = in ? lse[t4 + i] : 0.0f;
+        ty[i] = in ? records[t4 + i].y : -1;
+    }
+#pragma unroll
+    for (int pass = 0; pass < 4; ++pass) {
+        const int vr = (tid >> 4) + 16 * pass;
+        const int64_t v = v0 + vr;
+        float d[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+        if (v < V) {
+            const float4 z = *reinterpret_cast<const float4 *>(zt + v * ldn + t4);
+            const float zz[4] = {z.x, z.y, z.z, z.w};
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                if (neg_g[i] != 0.0f) {  // (also keeps whatever lies in the padding columns of z^T out)
+                    const float p = exp2_hw((zz[i] - tl[i]) * kLog2e);
+                    d[i] = neg_g[i] * p - ((int64_t)ty[i] == v ? neg_g[i] : 0.0f);
+                }
+            }
+            const uint32_t lo = pack_bf16x2(d[0], d[1]), hi = pack_bf16x2(d[2], d[3]);
+            *reinterpret_cast<uint2 *>(dzt + v * ldn + t4) = make_uint2(lo, hi);
+            tile[4 * tq + 0][vr] = (uint16_t)(lo & 0xFFFFu);
+            tile[4 * tq + 1][vr] = (uint16_t)(lo >> 16);
+            tile[4 * tq + 2][vr] = (uint16_t)(hi & 0xFFFFu);
+            tile[4 * tq + 3][vr] = (uint16_t)(hi >> 16);
+        }
+    }
+    __syncthreads();
+    // token-major: 64 tokens x 128 bytes; thread -> token tid / 4, 16 vocabulary rows (tid % 4) 16 ..
+    const int tr = tid >> 2, vq = (tid & 3) * 16;
+    if (t0 + tr < n) {
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+            const int64_t v = v0 + vq + 8 * half;
+            if (v < V) {  // V and the tile origin are multiples of 8: a vector is inside or outside as a whole
+                const uint4 w = *reinterpret_cast<const uint4 *>(&tile[tr][vq + 8 * half]);
+                *reinterpret_cast<uint4 *>(dz + (t0 + tr) * ldv + v) = w;
+            }
+        }
+    }
 }
 
 }  // namespace a3po
@@ -148,7 +231,9 @@ extern "C" int a3po_fused_lmhead_loss_fwd_bwd(const void *hidden, const void *we
                                               void *stream)
 {
     auto aligned = [](const void *p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; };
-    if (T < 0 || V <= 0 || H <= 0 || H % 8 != 0 || H > (1 << 20) || V % 8 != 0 || V > (int64_t)0x7FFFFFFF)
+    // H <= 2^20 and V < 2^21 keep the contraction kernel's 32-bit byte offsets inside a 256-row tile below 2^32
+    // (and T < 2^22: a row of h^T is T elements long)
+    if (T < 0 || V <= 0 || H <= 0 || H % 64 != 0 || H > (1 << 20) || V % 8 != 0 || V > (1 << 21) - 128 || T > (1 << 22) - 128)
         return A3PO_E_SIZE;
     if (!(clip_eps >= 0.0f && clip_eps < 1.0f) || denom != denom) return A3PO_E_VALUE;
     if (!loss_out || !weight || !dweight) return A3PO_E_NULL;
@@ -161,21 +246,24 @@ extern "C" int a3po_fused_lmhead_loss_fwd_bwd(const void *hidden, const void *we
     if (!aligned(workspace, 256)) return A3PO_E_ALIGN;
 
     hipStream_t s = static_cast<hipStream_t>(stream);
-    rocblas_handle hd = blas_handle();
-    if (!hd || rocblas_set_stream(hd, s) != rocblas_status_success) return A3PO_E_LAUNCH;
-    if (rocblas_set_pointer_mode(hd, rocblas_pointer_mode_host) != rocblas_status_success) return A3PO_E_LAUNCH;
-
     char *ws = static_cast<char *>(workspace);
-    uint16_t *zc = reinterpret_cast<uint16_t *>(ws + lay.zchunk);
+    float *lse = reinterpret_cast<float *>(ws + lay.lse);
+    float *gtok = reinterpret_cast<float *>(ws + lay.g);
+    float2 *partial = reinterpret_cast<float2 *>(ws + lay.partial);
+    float *zt = reinterpret_cast<float *>(ws + lay.zt);
     uint16_t *dzt = reinterpret_cast<uint16_t *>(ws + lay.dzt);
+    uint16_t *dz = reinterpret_cast<uint16_t *>(ws + lay.dz);
+    uint16_t *wt = reinterpret_cast<uint16_t *>(ws + lay.wt);
     uint16_t *ht = reinterpret_cast<uint16_t *>(ws + lay.ht);
     float *dwacc = reinterpret_cast<float *>(ws + lay.dwacc);
     const uint16_t *h = static_cast<const uint16_t *>(hidden);
+    const uint16_t *W = static_cast<const uint16_t *>(weight);
     uint16_t *dh = static_cast<uint16_t *>(dhidden);
+    const size_t nw = (size_t)V * (size_t)H;
 
     LossArgs a;
-    a.z = zc;
-    a.dz = zc;
+    a.z = nullptr;
+    a.dz = nullptr;
     a.dt = A3PO_BF16;
     a.T = T;
     a.V = V;
@@ -193,52 +281,85 @@ extern "C" int a3po_fused_lmhead_loss_fwd_bwd(const void *hidden, const void *we
     a.loss_out = loss_out;
     a.stats_out = stats_out;
     carve_loss_ws(a, ws, T);
+    const WsHeader *hdr = reinterpret_cast<const WsHeader *>(a.ws_header);
 
     // token count, 1/N and the per-token records for the whole batch
     if (launch_loss_prep(a, s) != hipSuccess) return A3PO_E_LAUNCH;
+    if (T == 0) {
+        if (launch_loss_finish(a, s) != hipSuccess) return A3PO_E_LAUNCH;
+        hipLaunchKernelGGL(zero_bf16_kernel, dim3((unsigned)((nw + 255) / 256)), dim3(256), 0, s,
+                           static_cast<uint16_t *>(dweight), nw);
+        return hipGetLastError() == hipSuccess ? A3PO_OK : A3PO_E_LAUNCH;
+    }
+    // the transposed operands of the two backward contractions, padding of the contracted index zeroed
+    if (launch_transpose_pad(W, wt, V, H, lay.ldv, s) != hipSuccess) return A3PO_E_LAUNCH;
+    if (launch_transpose_pad(h, ht, T, H, lay.ldt, s) != hipSuccess) return A3PO_E_LAUNCH;
+    if (lay.ldv > V) {  // padding columns of the token-major gradient chunk: never written below
+        const int64_t cells = lay.chunk * (lay.ldv - V);
+        hipLaunchKernelGGL(zero_columns_kernel, dim3((unsigned)((cells + 255) / 256)), dim3(256), 0, s, dz, lay.chunk,
+                           lay.ldv, V, lay.ldv);
+        if (hipGetLastError() != hipSuccess) return A3PO_E_LAUNCH;
+    }
 
     for (int64_t c0 = 0; c0 < T; c0 += lay.chunk) {
         const int64_t n = T - c0 < lay.chunk ? T - c0 : lay.chunk;
-        // logits of the chunk: z^T [V, n] = W [H, V]^T h_chunk [H, n]   (column-major views)
-        if (!gemm_bf16(hd, rocblas_operation_transpose, rocblas_operation_none, V, n, H, weight, H, h + c0 * H, H, 0.0f,
-                       zc, V, rocblas_datatype_bf16_r))
+        const int64_t npad = (n + kPadK - 1) / kPadK * kPadK;
+        // 1. z^T [V, n] = W h_chunk^T, folded into (max, sum) per token on the way out
+        GemmArgs fw = {};
+        fw.A = W;
+        fw.lda = H;
+        fw.B = h + c0 * H;
+        fw.ldb = H;
+        fw.M = V;
+        fw.N = n;
+        fw.K = H;
+        fw.C = zt;
+        fw.ldc = lay.ldn;
+        fw.partial = partial;
+        fw.partial_stride = lay.chunk;
+        if (launch_gemm_nt(fw, kEpiLseStore, s) != hipSuccess) return A3PO_E_LAUNCH;
+        // 2. log pi_theta and the per-token terms
+        if (launch_lmhead_lse_finish(h + c0 * H, W, n, H, V, chosen + c0, partial, lay.chunk, logp_out + c0, lse + c0, s) !=
+            hipSuccess)
             return A3PO_E_LAUNCH;
-        // loss forward + gradient rows over the chunk, in place
-        LossArgs c = a;
-        c.T = n;
-        c.ws_records = a.ws_records + c0;
-        c.logp_out = logp_out + c0;
-        c.prox_out = logp_prox_out ? logp_prox_out + c0 : nullptr;
-        c.ws_obj = a.ws_obj + c0;
-        c.ws_iw = a.ws_iw + c0;
-        c.ws_flags = a.ws_flags + c0;
-        c.ws_lse = a.ws_lse + c0;
-        c.ws_partial = a.ws_partial + c0;
-        if (c0 > 0 && launch_reset_row_queue(ws, s) != hipSuccess) return A3PO_E_LAUNCH;
-        if (launch_loss_rows(c, s) != hipSuccess) return A3PO_E_LAUNCH;
-        // dh_chunk^T [H, n] = W [H, V] dz^T [V, n]
-        if (!gemm_bf16(hd, rocblas_operation_none, rocblas_operation_none, H, n, V, weight, H, zc, V, 0.0f, dh + c0 * H,
-                       H, rocblas_datatype_bf16_r))
-            return A3PO_E_LAUNCH;
-        // dW^T [H, V] += hT [n, H]^T dzT [n, V]       (column-major views of the transposed chunks, tokens
-        // contiguous in both; fp32 accumulator across chunks)
-        const int64_t ldt = (n + 7) / 8 * 8;
-        if (launch_transpose_bf16(zc, dzt, n, V, ldt, s) != hipSuccess) return A3PO_E_LAUNCH;
-        if (launch_transpose_bf16(h + c0 * H, ht, n, H, ldt, s) != hipSuccess) return A3PO_E_LAUNCH;
-        if (!gemm_bf16(hd, rocblas_operation_transpose, rocblas_operation_none, H, V, n, ht, ldt, dzt, ldt,
-                       c0 == 0 ? 0.0f : 1.0f, dwacc, H, rocblas_datatype_f32_r))
-            return A3PO_E_LAUNCH;
+        hipLaunchKernelGGL(lmhead_token_terms_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s,
+                           a.ws_records + c0, n, current_version, clip_eps, hdr, logp_out + c0,
+                           logp_prox_out ? logp_prox_out + c0 : nullptr, a.ws_obj + c0, a.ws_iw + c0, a.ws_flags + c0,
+                           gtok + c0);
+        if (hipGetLastError() != hipSuccess) return A3PO_E_LAUNCH;
+        // 3. the gradient chunk in both layouts
+        const dim3 dz_grid((unsigned)((V + kDzTile - 1) / kDzTile), (unsigned)(npad / kDzTile));
+        hipLaunchKernelGGL(lmhead_dz_kernel, dz_grid, dim3(256), 0, s, zt, V, n, lay.ldn, lse + c0, gtok + c0,
+                           a.ws_records + c0, dzt, dz, lay.ldv);
+        if (hipGetLastError() != hipSuccess) return A3PO_E_LAUNCH;
+        // 4. dh_chunk [n, H] = dz [n, V] (W^T [H, V])^T
+        GemmArgs bh = {};
+        bh.A = dz;
+        bh.lda = lay.ldv;
+        bh.B = wt;
+        bh.ldb = lay.ldv;
+        bh.M = n;
+        bh.N = H;
+        bh.K = lay.ldv;
+        bh.C = dh + c0 * H;
+        bh.ldc = H;
+        if (launch_gemm_nt(bh, kEpiStoreBf16, s) != hipSuccess) return A3PO_E_LAUNCH;
+        // 5. dW [V, H] += dz^T [V, n] (h^T [H, n])^T     (fp32 accumulator across chunks)
+        GemmArgs bw = {};
+        bw.A = dzt;
+        bw.lda = lay.ldn;
+        bw.B = ht + c0;
+        bw.ldb = lay.ldt;
+        bw.M = V;
+        bw.N = H;
+        bw.K = npad;
+        bw.C = dwacc;
+        bw.ldc = H;
+        bw.accumulate = c0 > 0;
+        if (launch_gemm_nt(bw, kEpiAccumF32, s) != hipSuccess) return A3PO_E_LAUNCH;
     }
     if (launch_loss_finish(a, s) != hipSuccess) return A3PO_E_LAUNCH;
-    const size_t nw = (size_t)V * (size_t)H;
-    if (T == 0) {
-        hipLaunchKernelGGL(zero_bf16_kernel, dim3((unsigned)((nw + 255) / 256)), dim3(256), 0, s,
-                           static_cast<uint16_t *>(dweight), nw);
-        if (hipGetLastError() != hipSuccess) return A3PO_E_LAUNCH;
-    } else {
-        hipLaunchKernelGGL(f32_to_bf16_kernel, dim3((unsigned)((nw / 2 + 255) / 256)), dim3(256), 0, s, dwacc,
-                           static_cast<uint16_t *>(dweight), nw);
-        if (hipGetLastError() != hipSuccess) return A3PO_E_LAUNCH;
-    }
-    return A3PO_OK;
+    hipLaunchKernelGGL(f32_to_bf16_kernel, dim3((unsigned)((nw / 2 + 255) / 256)), dim3(256), 0, s, dwacc,
+                       static_cast<uint16_t *>(dweight), nw);
+    return hipGetLastError() == hipSuccess ? A3PO_OK : A3PO_E_LAUNCH;
 }

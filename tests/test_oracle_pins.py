@@ -539,6 +539,19 @@ def test_lmhead_backward_against_numpy_and_finite_differences():
     assert np.abs(num_dW - dW).max() < 1e-6 * np.abs(dW).max() + 1e-10
 
 
+def test_lmhead_backward_matmul_form_equals_the_loops():
+    # the matrix-product form used for the larger GPU cases against the plain loops, on a ragged shape
+    T, H, V = 37, 24, 53
+    h = bf16_bits(rng.standard_normal((T, H)))
+    W = bf16_bits(rng.standard_normal((V, H)))
+    dz = rng.standard_normal((T, V)) * np.exp(rng.standard_normal((T, V)) * 3)
+    dh, dW = oracle.lmhead_backward(dz, h, W)
+    dh2, dW2 = oracle.lmhead_backward_matmul(dz, h, W)
+    ah, aW = oracle.lmhead_backward(np.abs(dz), h & 0x7FFF, W & 0x7FFF)
+    assert (np.abs(dh - dh2) <= 1e-13 * ah).all() and (np.abs(dW - dW2) <= 1e-13 * aW).all()
+    assert dh2.shape == (T, H) and dW2.shape == (V, H)
+
+
 # ----------------------------------------------------------------------------- entropy, loss variants
 
 def test_entropy_closed_forms_and_scipy():
