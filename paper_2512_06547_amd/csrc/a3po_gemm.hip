@@ -55,7 +55,10 @@ constexpr int kDmaOperandBytes = kGemmTile * kDmaRowBytes; // 16,384
 constexpr int kDmaStageBytes = 2 * kDmaOperandBytes;       // 32,768
 constexpr int kDmaRingBytes = kDmaStages * kDmaStageBytes; // 131,072 of the compute unit's 163,840
 constexpr int kGemmRedBytes = 2 * kGemmTile * (int)sizeof(float2);  // column partials of the two row halves
-constexpr int kGemmLdsBytes = kDmaRingBytes + kGemmRedBytes;
+// per-wavefront staging tile of the store epilogues: one 32 x 32 MFMA tile in fp32, rows 40 floats apart
+constexpr int kStageLd = 40;
+constexpr int kStageBytes = 32 * kStageLd * (int)sizeof(float);  // 5,120
+constexpr int kGemmLdsBytes = kDmaRingBytes + kGemmRedBytes + 4 * kStageBytes;  // 155,648 of 163,840
 
 typedef __attribute__((address_space(3))) void *lds_ptr_t;
 
@@ -71,6 +74,17 @@ __device__ __forceinline__ constexpr int waitcnt_imm(int vmcnt, int lgkmcnt)
 }
 constexpr int kNoVmWait = 63, kNoLgkmWait = 15;
 
+// One accumulator value for ordinary arithmetic.  The accumulators live in the accumulation half of the register
+// file, which only the matrix cores and memory instructions address; everything else needs a copy.  The volatile
+// statement gives every use its own short-lived copy: left to itself the compiler copies a whole tile once, keeps
+// the 256 copies alive across the epilogue and spills them (and the next tile's fragments) to scratch memory.
+__device__ __forceinline__ float acc_value(float in_acc)
+{
+    float v;
+    asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(v) : "a"(in_acc));
+    return v;
+}
+
 // Folds the 64 rows this lane holds of column block b (4 MFMA tiles x 16 values) into the lane's running
 // (max, sum).  Row offset of acc[a][b][4 i + j] inside the lane's slice is a 32 + 8 i + j; offsets >= mlim lie
 // past the last row (only in the last, ragged tile).  The accumulators are only read.
@@ -84,7 +98,7 @@ __device__ __forceinline__ void fold_column(const f32x16_t (&acc)[4][4], int b, 
     for (int a = 0; a < 4; ++a) {
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
-            float v = acc[a][b][e];
+            float v = acc_value(acc[a][b][e]);
             if (RAGGED && a * 32 + (e >> 2) * 8 + (e & 3) >= mlim) v = -INFINITY;
             mx = fmaxf(mx, v);
         }
@@ -96,7 +110,7 @@ __device__ __forceinline__ void fold_column(const f32x16_t (&acc)[4][4], int b, 
     for (int a = 0; a < 4; ++a) {
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
-            float v = acc[a][b][e];
+            float v = acc_value(acc[a][b][e]);
             if (RAGGED && a * 32 + (e >> 2) * 8 + (e & 3) >= mlim) v = -INFINITY;
             s += exp2_hw((v - m_new) * kLog2e);
         }
@@ -127,7 +141,7 @@ __device__ __forceinline__ void store_tile(const f32x16_t (&acc)[4][4], void *C,
 #pragma unroll
             for (int b = 0; b < 4; ++b) {
                 if (EDGE && col0 + b * 32 >= cols_left) continue;
-                const float v = acc[a][b][e];
+                const float v = acc_value(acc[a][b][e]);
                 if constexpr (EPI == kEpiStoreBf16) {
                     reinterpret_cast<uint16_t *>(C)[at + b * 32] = (uint16_t)(pack_bf16x2(v, 0.0f) & 0xFFFFu);
                 } else if constexpr (EPI == kEpiAccumF32) {
@@ -140,8 +154,43 @@ __device__ __forceinline__ void store_tile(const f32x16_t (&acc)[4][4], void *C,
                     reinterpret_cast<float *>(C)[at + b * 32] = v;
                 }
             }
+            __builtin_amdgcn_sched_barrier(0);  // one row's address and values at a time
         }
-        __builtin_amdgcn_sched_barrier(0);
+    }
+}
+
+// The same for a tile that lies inside C, with 16-byte stores: each 32 x 32 MFMA tile goes through a staging tile in
+// LDS that belongs to this wavefront alone (LDS instructions of one wavefront execute in order, so no waits or
+// barriers are needed between its writes and its reads), and leaves as 8 rows x 128 bytes (fp32) or 8 rows x 64
+// bytes (bfloat16) per store instruction instead of 2 rows x 32 elements.
+template <int EPI>
+__device__ __forceinline__ void store_tile_wide(const f32x16_t (&acc)[4][4], void *C, int64_t ldc, int64_t m0, int64_t n0,
+                                                int wm, int wn, int lane, float *stage)
+{
+    static_assert(EPI == kEpiStoreBf16 || EPI == kEpiLseStore || EPI == kEpiAccumF32, "plain stores only");
+    const int wcol = lane & 31, wrow = 4 * (lane >> 5);  // where this lane's accumulator registers sit in the tile
+    const int rrow = lane >> 3, rcol = (lane & 7) * 4;   // what it reads back: 4 consecutive columns of row rrow + 8 pass
+#pragma unroll
+    for (int a = 0; a < 4; ++a) {
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+#pragma unroll
+            for (int e = 0; e < 16; ++e) stage[(wrow + (e >> 2) * 8 + (e & 3)) * kStageLd + wcol] = acc_value(acc[a][b][e]);
+            asm volatile("" ::: "memory");
+            const int64_t at = (m0 + wm * 128 + a * 32 + rrow) * ldc + n0 + wn * 128 + b * 32 + rcol;
+#pragma unroll
+            for (int pass = 0; pass < 4; ++pass) {
+                const float4 v = *reinterpret_cast<const float4 *>(stage + (rrow + 8 * pass) * kStageLd + rcol);
+                if constexpr (EPI == kEpiStoreBf16) {
+                    *reinterpret_cast<uint2 *>(reinterpret_cast<uint16_t *>(C) + at + (int64_t)pass * 8 * ldc) =
+                        make_uint2(pack_bf16x2(v.x, v.y), pack_bf16x2(v.z, v.w));
+                } else {
+                    *reinterpret_cast<float4 *>(reinterpret_cast<float *>(C) + at + (int64_t)pass * 8 * ldc) = v;
+                }
+            }
+            asm volatile("" ::: "memory");
+            __builtin_amdgcn_sched_barrier(0);
+        }
     }
 }
 
@@ -337,8 +386,17 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_nt_kernel(const GemmArgs g)
         const int64_t p_next = next_tile(p_cur + 1);
         const bool edge = m0 + kGemmTile > M || n0 + kGemmTile > N;  // uniform
         if constexpr (EPI != kEpiLse) {
-            if (edge) store_tile<EPI, true>(acc, g.C, g.ldc, m0, n0, M, N, wm, wn, lane, g.accumulate != 0);
-            else store_tile<EPI, false>(acc, g.C, g.ldc, m0, n0, M, N, wm, wn, lane, g.accumulate != 0);
+            // tiles inside C leave with 16-byte stores (the launcher checks that rows of C start on 16 bytes);
+            // only sums into C go element by element, through the memory side's adders
+            float *stage = reinterpret_cast<float *>(lds + kDmaRingBytes + kGemmRedBytes + wave_s * kStageBytes);
+            if (edge) {
+                store_tile<EPI, true>(acc, g.C, g.ldc, m0, n0, M, N, wm, wn, lane, g.accumulate != 0);
+            } else if constexpr (EPI == kEpiAccumF32) {
+                if (g.accumulate != 0) store_tile<EPI, false>(acc, g.C, g.ldc, m0, n0, M, N, wm, wn, lane, true);
+                else store_tile_wide<EPI>(acc, g.C, g.ldc, m0, n0, wm, wn, lane, stage);
+            } else {
+                store_tile_wide<EPI>(acc, g.C, g.ldc, m0, n0, wm, wn, lane, stage);
+            }
         }
         if constexpr (LSE) {
             const bool ragged = m0 + kGemmTile > M;
@@ -445,6 +503,7 @@ hipError_t launch_gemm_nt(const GemmArgs &g, int epilogue, hipStream_t s)
     if (g.M <= 0 || g.N <= 0 || g.K <= 0 || g.K % 64 != 0 || g.lda % 8 != 0 || g.ldb % 8 != 0 || g.lda < g.K ||
         g.ldb < g.K || g.lda > (1 << 22) || g.ldb > (1 << 22))
         return hipErrorInvalidValue;
+    if (epilogue != kEpiLse && (g.ldc % 8 != 0 || (reinterpret_cast<uintptr_t>(g.C) & 15) != 0)) return hipErrorInvalidValue;
     switch (epilogue) {
         case kEpiLse: return launch_gemm_t<kEpiLse>(g, s);
         case kEpiLseStore: return launch_gemm_t<kEpiLseStore>(g, s);
