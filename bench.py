@@ -278,25 +278,33 @@ def bench_lmhead(args, torch, a3po, synth, log, name=None, steps=None, warmup=No
     ws = torch.empty(a3po.workspace_bytes(T, V, H, which=2), dtype=torch.uint8, device="cuda")
     adv = torch.empty(T, dtype=torch.float32, device="cuda")
 
-    def step():
-        a3po.grpo_advantages(rewards, w.G, seq_id, out=adv)
-        return a3po.fused_lmhead_loss_fwd_bwd(h, W, y, lb, ver, tk["current_version"], adv, mask, w.clip_eps,
-                                              workspace=ws)
+    def run_phase(m, label):
+        """K timed steps with loss mask m.  Only counted tokens are projected, so the algorithmic flops are
+        6 N V H with N the counted tokens (forward, dh, dW; the logits of a chunk are kept, not recomputed)."""
+        def step():
+            a3po.grpo_advantages(rewards, w.G, seq_id, out=adv)
+            return a3po.fused_lmhead_loss_fwd_bwd(h, W, y, lb, ver, tk["current_version"], adv, m, w.clip_eps,
+                                                  workspace=ws)
+        out = step()
+        for _ in range(warmup):
+            out = step()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            out = step()
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        st = a3po.stats_to_dict(out["stats"])
+        ms = dt / steps * 1e3
+        flops = 6.0 * st["n_tokens"] * V * H
+        tf = flops / (ms * 1e-3) / 1e12
+        log(f"fwd+bwd, {label}: {ms:.1f} ms/step, {st['n_tokens']} counted tokens, {tf:.0f} TFLOP/s on 6 N V H, "
+            f"{T / ms * 1e3 / 1e3:.0f} k tokens/s")
+        return dict(dt=dt, ms=ms, st=st, flops=flops, tf=tf)
 
-    out = step()
-    for _ in range(warmup):
-        out = step()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(steps):
-        out = step()
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    st = a3po.stats_to_dict(out["stats"])
-    ms = dt / steps * 1e3
-    flops = 6.0 * T * V * H
-    tf = flops / (ms * 1e-3) / 1e12
-    log(f"fwd+bwd: {ms:.1f} ms/step, {tf:.0f} TFLOP/s on 6TVH, stats {st}")
+    rag = run_phase(mask, "workload's mask")
+    one = run_phase(torch.ones_like(mask), "all-ones mask")
+    dt, ms, st, flops, tf = rag["dt"], rag["ms"], rag["st"], rag["flops"], rag["tf"]
 
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     a3po.fused_lmhead_logprob(h, W, y, workspace=ws_f)
@@ -331,11 +339,15 @@ def bench_lmhead(args, torch, a3po, synth, log, name=None, steps=None, warmup=No
         "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
         "data": "synthetic",
         "config": {"workload": f"{lw.name}: {w.S} seq x {w.L} tok = {T} tokens, hidden {H}, vocab {V}, bf16; logits "
-                               f"kept in fp32 for 8,192 tokens at a time (6 T V H flops), {st['n_tokens']} counted tokens",
+                               f"only counted tokens are projected ({st['n_tokens']}; 6 N V H flops), their logits kept in fp32 8,192 tokens at a time",
                    "tokens": T, "hidden": H, "vocab": V, "counted_tokens": st["n_tokens"]},
         "roofline": {"bound": "mfma", "achieved": tf, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": tf / MFMA_BF16_PEAK_TFLOPS, "traffic": None, "flops": flops,
-                     "kernel": "whole step (gemm_nt_kernel x 3 per chunk of 8,192 tokens + lmhead_dz_kernel)"},
+                     "kernel": "whole step (gemm_nt_kernel x 3 per chunk of 8,192 counted tokens + lmhead_dz_kernel)"},
+        "all_rows_counted": {"value": T * steps / one["dt"], "unit": "tokens/s", "ms_per_step": one["ms"],
+                             "roofline": {"bound": "mfma", "achieved": one["tf"], "peak": MFMA_BF16_PEAK_TFLOPS,
+                                          "unit": "TFLOP/s", "frac": one["tf"] / MFMA_BF16_PEAK_TFLOPS,
+                                          "flops": one["flops"]}},
         "fused_forward": {"ms": fms, "roofline": {"bound": "mfma", "achieved": ftf, "peak": MFMA_BF16_PEAK_TFLOPS,
                                                   "unit": "TFLOP/s", "frac": ftf / MFMA_BF16_PEAK_TFLOPS,
                                                   "flops": 2.0 * T * V * H, "kernel": "gemm_nt_kernel (log-sum-exp epilogue)"}},
@@ -432,7 +444,7 @@ def main():
         # the LM-head workload on the same box in the same run: a few steps of the whole path from hidden states
         leg = bench_lmhead(args, torch, a3po, synth, log, name="lmhead8b", steps=3, warmup=1, cpu_rows=0)
         secondary["lmhead8b"] = {k: leg[k] for k in ("value", "unit", "steps", "warmup", "ms_per_step", "config",
-                                                      "roofline", "fused_forward")}
+                                                      "roofline", "all_rows_counted", "fused_forward")}
 
     cpu = None
     if args.cpu_rows > 0:

@@ -207,13 +207,20 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_nt_kernel(const GemmArgs g)
     const int wm = wave & 1, wn = wave >> 1;  // row half, column half of the tile
     const int xcd = (int)(blockIdx.x % (unsigned)g.nxcd), slot = (int)(blockIdx.x / (unsigned)g.nxcd);
     const int nl = slot & (kGemmColTiles - 1), ml = slot / kGemmColTiles;
-    const int64_t M = g.M, N = g.N;
+    int64_t M = g.M, N = g.N, K = g.K;
+    if (g.dyn_dim != kDynNone) {  // an extent that only the device knows (uniform: one scalar load)
+        const int64_t v = dyn_extent(g.dyn, 0);
+        if (g.dyn_dim == kDynM) M = v;
+        else if (g.dyn_dim == kDynN) N = v;
+        else K = (v + 127) / 128 * 128;
+        if (v <= 0) return;
+    }
     const int mtiles = (int)((M + kGemmTile - 1) / kGemmTile), ntiles = (int)((N + kGemmTile - 1) / kGemmTile);
     const int groups = (ntiles + kGemmColTiles - 1) / kGemmColTiles;
     const int rounds = (mtiles + g.ml_count - 1) / g.ml_count;
     const int64_t pairs = (int64_t)groups * rounds;
     const int64_t p_end = (int64_t)(xcd + 1) * pairs / g.nxcd;
-    const int nstages = (int)(g.K / kDmaK);
+    const int nstages = (int)(K / kDmaK);
     const int wave_s = __builtin_amdgcn_readfirstlane(wave);  // the wavefront number in a scalar register
     const uint32_t lda2 = (uint32_t)g.lda * 2u, ldb2 = (uint32_t)g.ldb * 2u;  // row strides in bytes
 
@@ -503,6 +510,7 @@ hipError_t launch_gemm_nt(const GemmArgs &g, int epilogue, hipStream_t s)
     if (g.M <= 0 || g.N <= 0 || g.K <= 0 || g.K % 64 != 0 || g.lda % 8 != 0 || g.ldb % 8 != 0 || g.lda < g.K ||
         g.ldb < g.K || g.lda > (1 << 22) || g.ldb > (1 << 22))
         return hipErrorInvalidValue;
+    if (g.dyn_dim != kDynNone && (!g.dyn.n || (g.dyn_dim == kDynK && g.K % 128 != 0))) return hipErrorInvalidValue;
     if (epilogue != kEpiLse && (g.ldc % 8 != 0 || (reinterpret_cast<uintptr_t>(g.C) & 15) != 0)) return hipErrorInvalidValue;
     switch (epilogue) {
         case kEpiLse: return launch_gemm_t<kEpiLse>(g, s);

@@ -129,6 +129,21 @@ enum GemmEpilogue {
     kEpiAccumF32 = 3    // C (float) = the product, or += when accumulate is set
 };
 
+// An extent that is only known on the device when the launch is queued (the number of tokens that enter the loss):
+// extent = clamp(*n - offset, 0, cap), or the host's value when n is null.
+struct DynCount {
+    const int64_t *n = nullptr;
+    int64_t offset = 0, cap = 0;
+};
+__host__ __device__ inline int64_t dyn_extent(const DynCount &d, int64_t host_value)
+{
+    if (!d.n) return host_value;
+    const int64_t v = *d.n - d.offset;
+    return v < 0 ? 0 : (v > d.cap ? d.cap : v);
+}
+
+enum GemmDynDim { kDynNone = 0, kDynM = 1, kDynN = 2, kDynK = 3 };
+
 struct GemmArgs {
     const uint16_t *A;  // [M, K] bfloat16, row-major, row stride lda elements (a multiple of 8; 16-byte aligned base)
     int64_t lda;
@@ -140,6 +155,8 @@ struct GemmArgs {
     float2 *partial;    // kEpiLse*: [gemm_partial_slots()][partial_stride] (max, sum) per column, merged by the caller
     int64_t partial_stride;
     int accumulate;     // kEpiAccumF32
+    int dyn_dim;        // GemmDynDim: which of M, N, K is replaced by dyn_extent(dyn, .) on the device (K: rounded up
+    DynCount dyn;       // to 128; the host's M, N, K are then upper bounds).  A zero extent makes the launch a no-op.
     int nxcd, ml_count; // filled in by the launcher from the device
 };
 
@@ -156,9 +173,10 @@ hipError_t launch_fused_lmhead_logprob(const void *hidden, const void *weight, i
                                        const int32_t *chosen, float *logp, float *lse, void *workspace, hipStream_t s);
 
 // merges the (max, sum) partials of a token, adds the chosen logit (a dot product) and writes lse and log pi
+// (T is an upper bound when `count` names a device-side token count)
 hipError_t launch_lmhead_lse_finish(const void *hidden, const void *weight, int64_t T, int64_t H, int64_t V,
                                     const int32_t *chosen, const float2 *partial, int64_t partial_stride, float *logp,
-                                    float *lse, hipStream_t s);
+                                    float *lse, hipStream_t s, DynCount count = DynCount());
 
 size_t lmhead_bwd_workspace_bytes(int64_t T, int64_t V, int64_t H);
 

@@ -14,11 +14,11 @@ __global__ __launch_bounds__(256) void lmhead_finish_kernel(const uint16_t *__re
                                                             const uint16_t *__restrict__ h, int64_t T, int64_t H,
                                                             int64_t V, const int32_t *__restrict__ chosen,
                                                             const float2 *__restrict__ partial, int64_t partial_stride,
-                                                            int nparts, float *logp, float *lse_out)
+                                                            int nparts, float *logp, float *lse_out, DynCount count)
 {
     const int lane = threadIdx.x & 63;
     const int64_t t = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (t >= T) return;
+    if (t >= dyn_extent(count, T)) return;
     const int32_t y = chosen[t];
     const bool ok = y >= 0 && (int64_t)y < V;
     float dot = 0.0f;
@@ -54,12 +54,12 @@ size_t lmhead_workspace_bytes(int64_t T)
 
 hipError_t launch_lmhead_lse_finish(const void *hidden, const void *weight, int64_t T, int64_t H, int64_t V,
                                     const int32_t *chosen, const float2 *partial, int64_t partial_stride, float *logp,
-                                    float *lse, hipStream_t s)
+                                    float *lse, hipStream_t s, DynCount count)
 {
     const unsigned grid = (unsigned)((T + 3) / 4);
     hipLaunchKernelGGL(lmhead_finish_kernel, dim3(grid), dim3(256), 0, s, reinterpret_cast<const uint16_t *>(weight),
                        reinterpret_cast<const uint16_t *>(hidden), T, H, V, chosen, partial, partial_stride,
-                       (int)gemm_partial_slots(), logp, lse);
+                       (int)gemm_partial_slots(), logp, lse, count);
     return hipGetLastError();
 }
 

@@ -1,6 +1,12 @@
 // A-3PO loss forward + backward starting from hidden states and the LM-head weight.
 //
-// Tokens are processed in chunks.  For each chunk
+// Only tokens that enter the loss (mask != 0 and a valid chosen id) are projected at all: every other token has
+// log-prob 0 by definition and contributes nothing to the loss or to either gradient, so its hidden row never
+// reaches the matrix cores.  The counted tokens are compacted on the device (an index of their positions, their
+// hidden rows gathered into a dense matrix); how many there are is known only on the device, so every launch
+// below is sized for the worst case and reads the count from memory - nothing waits for the host.
+//
+// The compacted tokens are processed in chunks.  For each chunk
 //   1. z^T = W h_chunk^T on the matrix cores; every 256 x 256 tile is folded into the running (max, sum) of its
 //      tokens while it is still in the accumulators (fp32: the log-sum-exp and the log-probs never see a rounded
 //      logit) and is also stored, as fp32, vocabulary-major, for the backward pass of the same chunk;
@@ -11,9 +17,9 @@
 //   5. dW     += dz^T h_chunk     (contraction over the tokens: dz vocabulary-major against h^T; fp32
 //      accumulator across chunks, rounded to bfloat16 once at the end).
 // All three contractions are the kernel of a3po_gemm.hip, which wants the contracted index contiguous in both
-// operands; W^T and h^T are therefore written once per call.  6 T V H flops per step: the logits of a chunk are
-// kept (4 bytes each, 5 GB for 8,192 tokens at V = 151,936) rather than recomputed, which would be a fourth
-// contraction.
+// operands; W^T and h^T are therefore written once per call.  6 N V H flops per step for N counted tokens: the
+// logits of a chunk are kept (4 bytes each, 5 GB for 8,192 tokens at V = 151,936) rather than recomputed, which
+// would be a fourth contraction.  Finally the rows of dh are scattered back to their tokens.
 #include "a3po_common.h"
 #include "a3po_launch.h"
 
@@ -26,12 +32,14 @@ constexpr int64_t kLmBwdChunk = A3PO_LM_BWD_CHUNK;  // tokens whose logits live 
 constexpr int64_t kPadK = 128;                      // contracted extents are zero-padded to this
 
 struct LmBwdLayout {
-    size_t lse, g, partial, zt, dzt, dz, wt, ht, dwacc, total;
-    int64_t chunk;  // tokens per chunk
+    size_t lse, g, logp, ysel, index, pos, counts, partial, zt, dzt, dz, wt, hc, ht, dhc, dwacc, total;
+    int64_t chunk;  // compacted tokens per chunk
     int64_t ldn;    // row stride of the vocabulary-major chunk buffers: the chunk length padded to kPadK tokens
     int64_t ldv;    // row stride of the token-major gradient chunk and of W^T: V padded to kPadK
     int64_t ldt;    // row stride of h^T: T padded to kPadK
 };
+
+constexpr int kCompactBlock = 1024;  // tokens per workgroup of the compaction kernels
 
 static LmBwdLayout lmhead_bwd_layout(int64_t T, int64_t V, int64_t H)
 {
@@ -43,28 +51,39 @@ static LmBwdLayout lmhead_bwd_layout(int64_t T, int64_t V, int64_t H)
     l.ldn = pad(l.chunk);
     l.ldv = pad(V);
     l.ldt = pad(T > 0 ? T : 1);
+    // per compacted token: lse, g, log pi, chosen id, position of the token; per token: its compacted position
     l.lse = up(loss_ws_layout(T).total);
     l.g = l.lse + up(t * sizeof(float));
-    l.partial = l.g + up(t * sizeof(float));
+    l.logp = l.g + up(t * sizeof(float));
+    l.ysel = l.logp + up(t * sizeof(float));
+    l.index = l.ysel + up(t * sizeof(int32_t));
+    l.pos = l.index + up(t * sizeof(int32_t));
+    l.counts = l.pos + up(t * sizeof(int32_t));
+    l.partial = l.counts + up(((t + kCompactBlock - 1) / kCompactBlock + 1) * sizeof(int32_t));
     l.zt = l.partial + up((size_t)kGemmMaxPartialSlots * (size_t)l.chunk * sizeof(float2));
     l.dzt = l.zt + up(v * (size_t)l.ldn * sizeof(float));
     l.dz = l.dzt + up(v * (size_t)l.ldn * 2);
     l.wt = l.dz + up((size_t)l.chunk * (size_t)l.ldv * 2);
-    l.ht = l.wt + up(h * (size_t)l.ldv * 2);
-    l.dwacc = l.ht + up(h * (size_t)l.ldt * 2);
+    l.hc = l.wt + up(h * (size_t)l.ldv * 2);
+    l.ht = l.hc + up(t * h * 2);
+    l.dhc = l.ht + up(h * (size_t)l.ldt * 2);
+    l.dwacc = l.dhc + up(t * h * 2);
     l.total = l.dwacc + up(v * h * sizeof(float));
     return l;
 }
 
 size_t lmhead_bwd_workspace_bytes(int64_t T, int64_t V, int64_t H) { return lmhead_bwd_layout(T, V, H).total; }
 
-__global__ void f32_to_bf16_kernel(const float *__restrict__ src, uint16_t *__restrict__ dst, size_t n)
+// dst = src rounded to bfloat16, or zeros when no token was counted (src was then never written)
+__global__ void f32_to_bf16_kernel(const float *__restrict__ src, uint16_t *__restrict__ dst, size_t n,
+                                   const int64_t *__restrict__ n_counted)
 {
     const size_t i = ((size_t)blockIdx.x * blockDim.x + threadIdx.x) * 2;
+    const bool any = *n_counted > 0;
     if (i + 1 < n) {
-        *reinterpret_cast<uint32_t *>(dst + i) = pack_bf16x2(src[i], src[i + 1]);
+        *reinterpret_cast<uint32_t *>(dst + i) = any ? pack_bf16x2(src[i], src[i + 1]) : 0u;
     } else if (i < n) {
-        dst[i] = (uint16_t)(pack_bf16x2(src[i], 0.0f) & 0xFFFFu);
+        dst[i] = any ? (uint16_t)(pack_bf16x2(src[i], 0.0f) & 0xFFFFu) : (uint16_t)0;
     }
 }
 
@@ -88,8 +107,10 @@ __global__ void zero_columns_kernel(uint16_t *__restrict__ m, int64_t R, int64_t
 // A workgroup moves a 64 x 64 tile through LDS: 16-byte loads along the columns, 16-byte stores along the rows.
 constexpr int kTrTile = 64;
 __global__ __launch_bounds__(256) void transpose_pad_bf16_kernel(const uint16_t *__restrict__ in, uint16_t *__restrict__ out,
-                                                                 int64_t R, int64_t C, int64_t ldo)
+                                                                 int64_t R, int64_t C, int64_t ldo,
+                                                                 const int64_t *__restrict__ R_dev)
 {
+    if (R_dev) R = *R_dev;  // rows that exist (the rest of `in` is not read)
     __shared__ uint16_t tile[kTrTile][kTrTile + 2];  // [row][column], padded: column reads below spread over the banks
     const int64_t r0 = (int64_t)blockIdx.y * kTrTile, c0 = (int64_t)blockIdx.x * kTrTile;
     const int tid = threadIdx.x;
@@ -120,37 +141,137 @@ __global__ __launch_bounds__(256) void transpose_pad_bf16_kernel(const uint16_t 
     }
 }
 
-static hipError_t launch_transpose_pad(const uint16_t *in, uint16_t *out, int64_t R, int64_t C, int64_t ldo, hipStream_t s)
+static hipError_t launch_transpose_pad(const uint16_t *in, uint16_t *out, int64_t R, int64_t C, int64_t ldo,
+                                       const int64_t *R_dev, hipStream_t s)
 {
     const dim3 grid((unsigned)((C + kTrTile - 1) / kTrTile), (unsigned)((ldo + kTrTile - 1) / kTrTile));
-    hipLaunchKernelGGL(transpose_pad_bf16_kernel, grid, dim3(256), 0, s, in, out, R, C, ldo);
+    hipLaunchKernelGGL(transpose_pad_bf16_kernel, grid, dim3(256), 0, s, in, out, R, C, ldo, R_dev);
     return hipGetLastError();
 }
 
-// Per-token terms of a chunk once its log-probs are known (Eq. 2 - Eq. 4): what the fused row kernel does for
-// logits that come from memory.  Tokens that do not enter the loss get zeros.
-__global__ void lmhead_token_terms_kernel(const TokenRecord *__restrict__ records, int64_t n, int32_t current_version,
-                                          float clip_eps, const WsHeader *__restrict__ hdr, float *logp, float *prox,
-                                          float *obj, float *iw, uint8_t *flags, float *g_out)
+// ---- compaction of the counted tokens ----------------------------------------------------------------
+// counts[b] = counted tokens among tokens [b, b + 1) * kCompactBlock (a record with y >= 0 is a counted token)
+__global__ __launch_bounds__(256) void compact_count_kernel(const TokenRecord *__restrict__ records, int64_t T,
+                                                            int32_t *__restrict__ counts)
 {
-    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (t >= n) return;
-    const TokenRecord rec = records[t];
-    if (rec.y < 0) {
-        logp[t] = 0.0f;
-        if (prox) prox[t] = 0.0f;
-        obj[t] = 0.0f;
-        iw[t] = 0.0f;
-        flags[t] = 0;
-        g_out[t] = 0.0f;
-        return;
+    __shared__ int s_cnt[4];
+    const int64_t t0 = (int64_t)blockIdx.x * kCompactBlock + threadIdx.x * 4;
+    int c = 0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) c += (t0 + i < T && records[t0 + i].y >= 0) ? 1 : 0;
+#pragma unroll
+    for (int off = kWave / 2; off > 0; off >>= 1) c += __shfl_xor(c, off, kWave);
+    if ((threadIdx.x & 63) == 0) s_cnt[threadIdx.x >> 6] = c;
+    __syncthreads();
+    if (threadIdx.x == 0) counts[blockIdx.x] = s_cnt[0] + s_cnt[1] + s_cnt[2] + s_cnt[3];
+}
+
+// Positions: counted token t gets the compacted position pos[t] = number of counted tokens before it, and
+// index[pos] = t, ysel[pos] = its chosen id.  Tokens that are not counted get pos = -1 and their per-token
+// outputs (zeros) here, since no later kernel visits them.
+__global__ __launch_bounds__(256) void compact_index_kernel(const TokenRecord *__restrict__ records, int64_t T,
+                                                            const int32_t *__restrict__ counts,
+                                                            int32_t *__restrict__ index, int32_t *__restrict__ pos,
+                                                            int32_t *__restrict__ ysel, float *logp, float *prox,
+                                                            float *obj, float *iw, uint8_t *flags)
+{
+    __shared__ int s_part[4], s_base;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    // counted tokens in the blocks before this one
+    int before = 0;
+    for (int b = tid; b < (int)blockIdx.x; b += 256) before += counts[b];
+#pragma unroll
+    for (int off = kWave / 2; off > 0; off >>= 1) before += __shfl_xor(before, off, kWave);
+    if (lane == 0) s_part[wave] = before;
+    __syncthreads();
+    if (tid == 0) s_base = s_part[0] + s_part[1] + s_part[2] + s_part[3];
+    __syncthreads();
+    // this thread's four tokens, then an exclusive scan of the threads' counts over the workgroup
+    const int64_t t0 = (int64_t)blockIdx.x * kCompactBlock + tid * 4;
+    int y[4], c = 0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        y[i] = t0 + i < T ? records[t0 + i].y : -1;
+        c += y[i] >= 0 ? 1 : 0;
     }
-    const TokenTerms tt = token_terms(logp[t], rec.lb, rec.ver, current_version, rec.A, clip_eps, hdr->inv_n, A3PO_PROX_INTERP);
+    int incl = c;
+#pragma unroll
+    for (int off = 1; off < kWave; off <<= 1) {
+        const int up = __shfl_up(incl, off, kWave);
+        if (lane >= off) incl += up;
+    }
+    __syncthreads();  // s_part is reused
+    if (lane == kWave - 1) s_part[wave] = incl;
+    __syncthreads();
+    int at = s_base + incl - c;
+    for (int w = 0; w < wave; ++w) at += s_part[w];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int64_t t = t0 + i;
+        if (t >= T) break;
+        if (y[i] >= 0) {
+            pos[t] = at;
+            index[at] = (int32_t)t;
+            ysel[at] = y[i];
+            ++at;
+        } else {
+            pos[t] = -1;
+            logp[t] = 0.0f;
+            if (prox) prox[t] = 0.0f;
+            obj[t] = 0.0f;
+            iw[t] = 0.0f;
+            flags[t] = 0;
+        }
+    }
+}
+
+// dst[j, :] = src[index[j], :] for j < *n (rows of C 2-byte elements, C a multiple of 8); one wavefront per row
+__global__ __launch_bounds__(256) void gather_rows_kernel(const uint16_t *__restrict__ src, uint16_t *__restrict__ dst,
+                                                          const int32_t *__restrict__ index, const int64_t *__restrict__ n,
+                                                          int64_t C)
+{
+    const int64_t j = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (j >= *n) return;
+    const uint16_t *from = src + (int64_t)index[j] * C;
+    uint16_t *to = dst + j * C;
+    for (int64_t k = (int64_t)(threadIdx.x & 63) * 8; k < C; k += 64 * 8)
+        *reinterpret_cast<uint4 *>(to + k) = *reinterpret_cast<const uint4 *>(from + k);
+}
+
+// dst[t, :] = src[pos[t], :] where pos[t] >= 0, zeros elsewhere (every row of dst is written)
+__global__ __launch_bounds__(256) void scatter_rows_kernel(const uint16_t *__restrict__ src, uint16_t *__restrict__ dst,
+                                                           const int32_t *__restrict__ pos, int64_t T, int64_t C)
+{
+    const int64_t t = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (t >= T) return;
+    const int32_t p = pos[t];
+    uint16_t *to = dst + t * C;
+    for (int64_t k = (int64_t)(threadIdx.x & 63) * 8; k < C; k += 64 * 8)
+        *reinterpret_cast<uint4 *>(to + k) =
+            p >= 0 ? *reinterpret_cast<const uint4 *>(src + (int64_t)p * C + k) : make_uint4(0u, 0u, 0u, 0u);
+}
+
+// Per-token terms of a chunk of compacted tokens once their log-probs are known (Eq. 2 - Eq. 4): what the fused
+// row kernel does for logits that come from memory.  Compacted token j of the chunk is token index[j]; its
+// outputs go to that token's place, g stays in compacted order for the gradient kernel.
+__global__ void lmhead_token_terms_kernel(const TokenRecord *__restrict__ records, const int32_t *__restrict__ index,
+                                          DynCount count, int32_t current_version, float clip_eps,
+                                          const WsHeader *__restrict__ hdr, const float *__restrict__ logp_c,
+                                          float *logp, float *prox, float *obj, float *iw, uint8_t *flags,
+                                          float *g_out)
+{
+    const int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (j >= dyn_extent(count, 0)) return;
+    const int64_t t = index[j];
+    const TokenRecord rec = records[t];
+    const float lt = logp_c[j];
+    const TokenTerms tt = token_terms(lt, rec.lb, rec.ver, current_version, rec.A, clip_eps, hdr->inv_n, A3PO_PROX_INTERP);
+    logp[t] = lt;
     if (prox) prox[t] = tt.lp;
     obj[t] = tt.obj;
     iw[t] = tt.iw;
     flags[t] = (uint8_t)(kFlagCounted | (tt.clipped ? kFlagClipped : 0) | (tt.negative_staleness ? kFlagNegStale : 0));
-    g_out[t] = tt.g;
+    g_out[j] = tt.g;
 }
 
 // Gradient of a chunk's logits from the stored fp32 logits z^T [V, ldn] (vocabulary-major):
@@ -158,17 +279,20 @@ __global__ void lmhead_token_terms_kernel(const TokenRecord *__restrict__ record
 // rounded once to bfloat16 and written both vocabulary-major (dzt [V, ldn], the operand of the weight gradient)
 // and token-major (dz [n, ldv], the operand of the hidden-state gradient).  A workgroup takes a tile of 64
 // vocabulary rows x 64 tokens: 16-byte loads and 8-byte stores along the tokens, then through LDS 16-byte stores
-// along the vocabulary.  Token columns n .. (multiple of 64) of dzt are written as zeros (they pad the
-// contraction over the tokens); a token with g = 0 gives an exactly zero column.
+// along the vocabulary.  Token columns n .. (next multiple of 128) of dzt are written as zeros (they pad the
+// contraction over the tokens); a token with g = 0 gives an exactly zero column.  lse, g, ysel: the chunk's
+// tokens in compacted order.
 constexpr int kDzTile = 64;
-__global__ __launch_bounds__(256) void lmhead_dz_kernel(const float *__restrict__ zt, int64_t V, int64_t n, int64_t ldn,
+__global__ __launch_bounds__(256) void lmhead_dz_kernel(const float *__restrict__ zt, int64_t V, DynCount count, int64_t ldn,
                                                         const float *__restrict__ lse, const float *__restrict__ g,
-                                                        const TokenRecord *__restrict__ records,
+                                                        const int32_t *__restrict__ ysel,
                                                         uint16_t *__restrict__ dzt, uint16_t *__restrict__ dz, int64_t ldv)
 {
     __shared__ __align__(16) uint16_t tile[kDzTile][kDzTile + 8];  // [token][vocabulary row], rows 144 bytes apart
     const int tid = threadIdx.x;
+    const int64_t n = dyn_extent(count, 0);
     const int64_t v0 = (int64_t)blockIdx.x * kDzTile, t0 = (int64_t)blockIdx.y * kDzTile;
+    if (t0 >= (n + kPadK - 1) / kPadK * kPadK) return;  // past the padded chunk (uniform)
     const int tq = tid & 15;            // this thread's four tokens: t0 + 4 tq ..
     const int64_t t4 = t0 + 4 * tq;
     float neg_g[4], tl[4];
@@ -178,7 +302,7 @@ __global__ __launch_bounds__(256) void lmhead_dz_kernel(const float *__restrict_
         const bool in = t4 + i < n;
         neg_g[i] = in ? -g[t4 + i] : 0.0f;
         tl[i] = in ? lse[t4 + i] : 0.0f;
-        ty[i] = in ? records[t4 + i].y : -1;
+        ty[i] = in ? ysel[t4 + i] : -1;
     }
 #pragma unroll
     for (int pass = 0; pass < 4; ++pass) {
@@ -247,18 +371,24 @@ extern "C" int a3po_fused_lmhead_loss_fwd_bwd(const void *hidden, const void *we
 
     hipStream_t s = static_cast<hipStream_t>(stream);
     char *ws = static_cast<char *>(workspace);
-    float *lse = reinterpret_cast<float *>(ws + lay.lse);
+    float *lse = reinterpret_cast<float *>(ws + lay.lse);        // the next four: compacted order
     float *gtok = reinterpret_cast<float *>(ws + lay.g);
+    float *logp_c = reinterpret_cast<float *>(ws + lay.logp);
+    int32_t *ysel = reinterpret_cast<int32_t *>(ws + lay.ysel);
+    int32_t *index = reinterpret_cast<int32_t *>(ws + lay.index);  // compacted position -> token
+    int32_t *pos = reinterpret_cast<int32_t *>(ws + lay.pos);      // token -> compacted position or -1
+    int32_t *counts = reinterpret_cast<int32_t *>(ws + lay.counts);
     float2 *partial = reinterpret_cast<float2 *>(ws + lay.partial);
     float *zt = reinterpret_cast<float *>(ws + lay.zt);
     uint16_t *dzt = reinterpret_cast<uint16_t *>(ws + lay.dzt);
     uint16_t *dz = reinterpret_cast<uint16_t *>(ws + lay.dz);
     uint16_t *wt = reinterpret_cast<uint16_t *>(ws + lay.wt);
-    uint16_t *ht = reinterpret_cast<uint16_t *>(ws + lay.ht);
+    uint16_t *hc = reinterpret_cast<uint16_t *>(ws + lay.hc);      // hidden rows of the counted tokens
+    uint16_t *ht = reinterpret_cast<uint16_t *>(ws + lay.ht);      // and their transpose
+    uint16_t *dhc = reinterpret_cast<uint16_t *>(ws + lay.dhc);
     float *dwacc = reinterpret_cast<float *>(ws + lay.dwacc);
     const uint16_t *h = static_cast<const uint16_t *>(hidden);
     const uint16_t *W = static_cast<const uint16_t *>(weight);
-    uint16_t *dh = static_cast<uint16_t *>(dhidden);
     const size_t nw = (size_t)V * (size_t)H;
 
     LossArgs a;
@@ -282,6 +412,7 @@ extern "C" int a3po_fused_lmhead_loss_fwd_bwd(const void *hidden, const void *we
     a.stats_out = stats_out;
     carve_loss_ws(a, ws, T);
     const WsHeader *hdr = reinterpret_cast<const WsHeader *>(a.ws_header);
+    const int64_t *n_counted = &hdr->n_counted;  // device: known once the prep kernel has run
 
     // token count, 1/N and the per-token records for the whole batch
     if (launch_loss_prep(a, s) != hipSuccess) return A3PO_E_LAUNCH;
@@ -291,9 +422,16 @@ extern "C" int a3po_fused_lmhead_loss_fwd_bwd(const void *hidden, const void *we
                            static_cast<uint16_t *>(dweight), nw);
         return hipGetLastError() == hipSuccess ? A3PO_OK : A3PO_E_LAUNCH;
     }
-    // the transposed operands of the two backward contractions, padding of the contracted index zeroed
-    if (launch_transpose_pad(W, wt, V, H, lay.ldv, s) != hipSuccess) return A3PO_E_LAUNCH;
-    if (launch_transpose_pad(h, ht, T, H, lay.ldt, s) != hipSuccess) return A3PO_E_LAUNCH;
+    // compaction of the counted tokens, their hidden rows, and the transposed operands of the two backward
+    // contractions (padding of the contracted index zeroed)
+    const unsigned cblocks = (unsigned)((T + kCompactBlock - 1) / kCompactBlock);
+    hipLaunchKernelGGL(compact_count_kernel, dim3(cblocks), dim3(256), 0, s, a.ws_records, T, counts);
+    hipLaunchKernelGGL(compact_index_kernel, dim3(cblocks), dim3(256), 0, s, a.ws_records, T, counts, index, pos, ysel,
+                       logp_out, logp_prox_out, a.ws_obj, a.ws_iw, a.ws_flags);
+    hipLaunchKernelGGL(gather_rows_kernel, dim3((unsigned)((T + 3) / 4)), dim3(256), 0, s, h, hc, index, n_counted, H);
+    if (hipGetLastError() != hipSuccess) return A3PO_E_LAUNCH;
+    if (launch_transpose_pad(W, wt, V, H, lay.ldv, nullptr, s) != hipSuccess) return A3PO_E_LAUNCH;
+    if (launch_transpose_pad(hc, ht, T, H, lay.ldt, n_counted, s) != hipSuccess) return A3PO_E_LAUNCH;
     if (lay.ldv > V) {  // padding columns of the token-major gradient chunk: never written below
         const int64_t cells = lay.chunk * (lay.ldv - V);
         hipLaunchKernelGGL(zero_columns_kernel, dim3((unsigned)((cells + 255) / 256)), dim3(256), 0, s, dz, lay.chunk,
@@ -301,36 +439,43 @@ extern "C" int a3po_fused_lmhead_loss_fwd_bwd(const void *hidden, const void *we
         if (hipGetLastError() != hipSuccess) return A3PO_E_LAUNCH;
     }
 
+    // Chunks of compacted tokens.  The host only knows the upper bound T; a chunk that starts past the counted
+    // tokens finds an extent of zero on the device and its launches return at once.
     for (int64_t c0 = 0; c0 < T; c0 += lay.chunk) {
-        const int64_t n = T - c0 < lay.chunk ? T - c0 : lay.chunk;
-        const int64_t npad = (n + kPadK - 1) / kPadK * kPadK;
+        const int64_t nmax = T - c0 < lay.chunk ? T - c0 : lay.chunk;
+        const int64_t kmax = (nmax + kPadK - 1) / kPadK * kPadK;
+        DynCount cnt;
+        cnt.n = n_counted;
+        cnt.offset = c0;
+        cnt.cap = nmax;
         // 1. z^T [V, n] = W h_chunk^T, folded into (max, sum) per token on the way out
         GemmArgs fw = {};
         fw.A = W;
         fw.lda = H;
-        fw.B = h + c0 * H;
+        fw.B = hc + c0 * H;
         fw.ldb = H;
         fw.M = V;
-        fw.N = n;
+        fw.N = nmax;
         fw.K = H;
         fw.C = zt;
         fw.ldc = lay.ldn;
         fw.partial = partial;
         fw.partial_stride = lay.chunk;
+        fw.dyn_dim = kDynN;
+        fw.dyn = cnt;
         if (launch_gemm_nt(fw, kEpiLseStore, s) != hipSuccess) return A3PO_E_LAUNCH;
         // 2. log pi_theta and the per-token terms
-        if (launch_lmhead_lse_finish(h + c0 * H, W, n, H, V, chosen + c0, partial, lay.chunk, logp_out + c0, lse + c0, s) !=
-            hipSuccess)
+        if (launch_lmhead_lse_finish(hc + c0 * H, W, nmax, H, V, ysel + c0, partial, lay.chunk, logp_c + c0, lse + c0, s,
+                                     cnt) != hipSuccess)
             return A3PO_E_LAUNCH;
-        hipLaunchKernelGGL(lmhead_token_terms_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s,
-                           a.ws_records + c0, n, current_version, clip_eps, hdr, logp_out + c0,
-                           logp_prox_out ? logp_prox_out + c0 : nullptr, a.ws_obj + c0, a.ws_iw + c0, a.ws_flags + c0,
-                           gtok + c0);
+        hipLaunchKernelGGL(lmhead_token_terms_kernel, dim3((unsigned)((nmax + 255) / 256)), dim3(256), 0, s,
+                           a.ws_records, index + c0, cnt, current_version, clip_eps, hdr, logp_c + c0, logp_out,
+                           logp_prox_out, a.ws_obj, a.ws_iw, a.ws_flags, gtok + c0);
         if (hipGetLastError() != hipSuccess) return A3PO_E_LAUNCH;
         // 3. the gradient chunk in both layouts
-        const dim3 dz_grid((unsigned)((V + kDzTile - 1) / kDzTile), (unsigned)(npad / kDzTile));
-        hipLaunchKernelGGL(lmhead_dz_kernel, dz_grid, dim3(256), 0, s, zt, V, n, lay.ldn, lse + c0, gtok + c0,
-                           a.ws_records + c0, dzt, dz, lay.ldv);
+        const dim3 dz_grid((unsigned)((V + kDzTile - 1) / kDzTile), (unsigned)(kmax / kDzTile));
+        hipLaunchKernelGGL(lmhead_dz_kernel, dz_grid, dim3(256), 0, s, zt, V, cnt, lay.ldn, lse + c0, gtok + c0,
+                           ysel + c0, dzt, dz, lay.ldv);
         if (hipGetLastError() != hipSuccess) return A3PO_E_LAUNCH;
         // 4. dh_chunk [n, H] = dz [n, V] (W^T [H, V])^T
         GemmArgs bh = {};
@@ -338,11 +483,13 @@ extern "C" int a3po_fused_lmhead_loss_fwd_bwd(const void *hidden, const void *we
         bh.lda = lay.ldv;
         bh.B = wt;
         bh.ldb = lay.ldv;
-        bh.M = n;
+        bh.M = nmax;
         bh.N = H;
         bh.K = lay.ldv;
-        bh.C = dh + c0 * H;
+        bh.C = dhc + c0 * H;
         bh.ldc = H;
+        bh.dyn_dim = kDynM;
+        bh.dyn = cnt;
         if (launch_gemm_nt(bh, kEpiStoreBf16, s) != hipSuccess) return A3PO_E_LAUNCH;
         // 5. dW [V, H] += dz^T [V, n] (h^T [H, n])^T     (fp32 accumulator across chunks)
         GemmArgs bw = {};
@@ -352,14 +499,18 @@ extern "C" int a3po_fused_lmhead_loss_fwd_bwd(const void *hidden, const void *we
         bw.ldb = lay.ldt;
         bw.M = V;
         bw.N = H;
-        bw.K = npad;
+        bw.K = kmax;
         bw.C = dwacc;
         bw.ldc = H;
         bw.accumulate = c0 > 0;
+        bw.dyn_dim = kDynK;
+        bw.dyn = cnt;
         if (launch_gemm_nt(bw, kEpiAccumF32, s) != hipSuccess) return A3PO_E_LAUNCH;
     }
     if (launch_loss_finish(a, s) != hipSuccess) return A3PO_E_LAUNCH;
+    hipLaunchKernelGGL(scatter_rows_kernel, dim3((unsigned)((T + 3) / 4)), dim3(256), 0, s, dhc,
+                       static_cast<uint16_t *>(dhidden), pos, T, H);
     hipLaunchKernelGGL(f32_to_bf16_kernel, dim3((unsigned)((nw / 2 + 255) / 256)), dim3(256), 0, s, dwacc,
-                       static_cast<uint16_t *>(dweight), nw);
+                       static_cast<uint16_t *>(dweight), nw, n_counted);
     return hipGetLastError() == hipSuccess ? A3PO_OK : A3PO_E_LAUNCH;
 }
