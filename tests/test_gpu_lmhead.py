@@ -94,6 +94,60 @@ def test_fused_lmhead_full_vocabulary_sampled_tokens(a3po):
     close(logp.cpu().numpy()[rows], ref["logp"], "logp")
 
 
+_FIRST_CALL_FROM_TWO_THREADS = r"""
+import sys, threading
+import numpy as np, torch
+sys.path.insert(0, sys.argv[1])
+import oracle, paper_2512_06547_amd as a3po
+
+def bits(x):
+    u = np.asarray(x, dtype=np.float32).view(np.uint32).astype(np.uint64)
+    return ((u + 0x7FFF + ((u >> 16) & 1)) >> 16).astype(np.uint16)
+
+a3po.lib()
+torch.cuda.set_device(0)
+cases = []
+for i, (T, H, V) in enumerate([(700, 128, 3000), (300, 192, 5000)]):   # one shape per kernel variant (ring-depth multiple or not)
+    r = np.random.default_rng(i)
+    h, W, y = bits(r.standard_normal((T, H))), bits(r.standard_normal((V, H)) * 0.3), r.integers(0, V, T).astype(np.int32)
+    cases.append(dict(h=h, W=W, y=y, hd=torch.from_numpy(h).view(torch.bfloat16).cuda(),
+                      Wd=torch.from_numpy(W).view(torch.bfloat16).cuda(), yd=torch.from_numpy(y).cuda(),
+                      stream=torch.cuda.Stream()))
+torch.cuda.synchronize()
+gate, out = threading.Barrier(4), {}
+
+def worker(k, c):
+    with torch.cuda.stream(c["stream"]):
+        gate.wait()                                 # all threads enter the library together: its first calls
+        out[k] = a3po.fused_lmhead_logprob(c["hd"], c["Wd"], c["yd"])
+        c["stream"].synchronize()
+
+threads = [threading.Thread(target=worker, args=(k, cases[k % 2])) for k in range(4)]
+[t.start() for t in threads]
+[t.join() for t in threads]
+assert len(out) == 4
+for k in range(4):
+    c = cases[k % 2]
+    ref = oracle.token_logprobs(oracle.lmhead_logits(c["h"], c["W"]), c["y"])
+    for got, want in ((out[k][0], ref["logp"]), (out[k][1], ref["lse"])):
+        err = np.abs(got.cpu().numpy().astype(np.float64) - want)
+        assert (err <= 1e-5 * np.abs(want) + 2e-5).all(), (k, err.max())
+print("ok")
+"""
+
+
+def test_first_calls_from_several_host_threads_at_once(a3po):
+    """The one-time set-up of the matrix-core kernels (their LDS limit) is race-free: a fresh process whose very
+    first calls into the library come from four host threads at the same moment, on two streams and through both
+    kernel variants, gets the oracle's log-probs from every call."""
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    p = subprocess.run([sys.executable, "-c", _FIRST_CALL_FROM_TWO_THREADS, root], capture_output=True, text=True, timeout=240)
+    assert p.returncode == 0 and p.stdout.strip().endswith("ok"), p.stdout[-2000:] + p.stderr[-4000:]
+
+
 # ------------------------------------------------------------------------------------------ forward + backward
 #
 # The reference is the plain fp64 oracle with nothing rounded: z = h W^T, log-softmax, Eq. 2 - Eq. 4, the
