@@ -1,5 +1,5 @@
 // bfloat16 contraction on the matrix cores for the LM-head path:  C[M, N] = A[M, K] B[N, K]^T, both operands
-// row-major with the contracted index contiguous, fp32 accumulation (v_mfma_f32_32x32x16_bf16), and one of four
+// row-major with the contracted index contiguous, fp32 accumulation (v_mfma_f32_16x16x32_bf16), and one of four
 // epilogues applied to each 256 x 256 tile as it leaves the accumulators:
 //   kEpiLse        fold the tile into a running (max, sum) per column n over the rows m (the online log-sum-exp
 //                  of the vocabulary when A is the LM-head weight and B the hidden states); C is not written
@@ -8,24 +8,27 @@
 //   kEpiStoreBf16  the tile is stored as bfloat16 (the gradient of the hidden states)
 //   kEpiAccumF32   the tile is stored as fp32, or added to what C holds (the weight gradient, summed over chunks)
 //
-// Tiling.  A workgroup of 256 threads (4 wavefronts, one per SIMD) computes a 256 x 256 tile, each wavefront a
-// 128 x 128 quarter = 4 x 4 MFMA tiles = 256 accumulator registers.  In the 32 x 32 result layout a lane owns
-// one column n and 16 rows m of each MFMA tile, so a reduction over m is mostly per lane, and a store of one
-// accumulator register covers 32 consecutive n of two rows.
+// Tiling.  A workgroup of 512 threads (8 wavefronts, two per SIMD) computes a 256 x 256 tile, each wavefront a
+// 128 x 64 part = 8 x 4 MFMA tiles of 16 x 16 = 128 accumulator registers.  Two wavefronts per SIMD: while one
+// waits (for the stage barrier, for its fragments) the other keeps the matrix core busy, which one wavefront with
+// 256 accumulators cannot; the 16 x 16 x 32 instruction also draws less power per flop than the 32 x 32 x 16 one,
+// and at these sizes the chip is power-limited (the clock falls as the matrix cores get busier).  In the 16 x 16
+// result layout a lane owns one column n and 4 rows m of each MFMA tile, so a reduction over m is mostly per
+// lane.
 //
-// K is walked in stages of 32 through a ring of LDS buffers that direct global -> LDS loads
+// K is walked in stages of 32 (one MFMA deep) through a ring of LDS buffers that direct global -> LDS loads
 // (global_load_lds_dwordx4: lane l of a wavefront lands at lds_base + 16 l; no staging registers, no LDS write
 // instructions) fill a few stages ahead.  LDS layout of one operand stage: 256 rows x 64 bytes, unpadded; the
 // 16-byte piece p of row r sits at physical piece p ^ ((r >> 2) & 3) - the permutation is applied on the global
 // side of the load - so a fragment read (16 consecutive rows, same logical piece) touches 16 distinct bank groups.
 //
-// Schedule of stage i (two k-steps of 16 MFMAs).  A wavefront holds the fragments of a whole stage in registers,
-// twice (this stage and the next).  At the top of stage i it waits for its own loads of stage i+1 and its own
-// fragment reads of stage i, and all wavefronts meet at one barrier: stage i+1 is now visible and the slot of
-// stage i is free.  During the 32 MFMAs of stage i the 16 fragments of stage i+1 are read and the 8 direct loads
-// of stage i + kDmaStages go into the freed slot, two reads and one load per group of four MFMAs.  The ring runs
-// through a workgroup's whole sequence of tiles without a break: the refills of a tile's last stages already
-// bring the next tile's first stages, so a tile's epilogue overlaps with their arrival.
+// Schedule of stage i (32 MFMAs per wavefront).  At the top a wavefront waits for its own loads of stage i+1 and
+// its own fragment reads, and all wavefronts meet at one barrier: stage i+1 is now visible and the slot of stage i
+// is free.  The 8 row fragments live in one set of registers: each is re-read for stage i+1 right after its last
+// use in stage i; the 4 column fragments, which every MFMA group of the stage needs, alternate between two sets.
+// The 4 direct loads of stage i + kDmaStages go into the freed slot, spread over the stage.  The ring runs through
+// a workgroup's whole sequence of tiles without a break: the refills of a tile's last stages already bring the
+// next tile's first stages, so a tile's epilogue overlaps with their arrival.
 //
 // Tile order.  One persistent workgroup per compute unit; the workgroups of an XCD (dispatch order deals
 // workgroups round-robin over the XCDs) form a block of ml_count x 4 tiles that share ml_count tiles of A and 4
@@ -41,11 +44,12 @@
 namespace a3po {
 
 constexpr int kGemmTile = 256;  // tile edge, both sides
-constexpr int kGemmThreads = 256;
+constexpr int kGemmThreads = 512;
+constexpr int kGemmWaves = kGemmThreads / kWave;
 constexpr int kGemmColTiles = 4;  // tiles of B (columns) side by side in an XCD's block
 
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
-typedef float f32x16_t __attribute__((ext_vector_type(16)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
 typedef uint32_t gemm_u32x4_t __attribute__((ext_vector_type(4)));
 
 constexpr int kDmaStages = 4;
@@ -55,10 +59,10 @@ constexpr int kDmaOperandBytes = kGemmTile * kDmaRowBytes; // 16,384
 constexpr int kDmaStageBytes = 2 * kDmaOperandBytes;       // 32,768
 constexpr int kDmaRingBytes = kDmaStages * kDmaStageBytes; // 131,072 of the compute unit's 163,840
 constexpr int kGemmRedBytes = 2 * kGemmTile * (int)sizeof(float2);  // column partials of the two row halves
-// per-wavefront staging tile of the store epilogues: one 32 x 32 MFMA tile in fp32, rows 40 floats apart
-constexpr int kStageLd = 40;
-constexpr int kStageBytes = 32 * kStageLd * (int)sizeof(float);  // 5,120
-constexpr int kGemmLdsBytes = kDmaRingBytes + kGemmRedBytes + 4 * kStageBytes;  // 155,648 of 163,840
+// per-wavefront staging tile of the store epilogues: 16 rows x 32 columns of fp32, rows 36 floats apart
+constexpr int kStageLd = 36;
+constexpr int kStageBytes = 16 * kStageLd * (int)sizeof(float);  // 2,304
+constexpr int kGemmLdsBytes = kDmaRingBytes + kGemmRedBytes + kGemmWaves * kStageBytes;  // 153,600 of 163,840
 
 typedef __attribute__((address_space(3))) void *lds_ptr_t;
 
@@ -74,112 +78,101 @@ __device__ __forceinline__ constexpr int waitcnt_imm(int vmcnt, int lgkmcnt)
 }
 constexpr int kNoVmWait = 63, kNoLgkmWait = 15;
 
-// One accumulator value for ordinary arithmetic.  The accumulators live in the accumulation half of the register
-// file, which only the matrix cores and memory instructions address; everything else needs a copy.  The volatile
-// statement gives every use its own short-lived copy: left to itself the compiler copies a whole tile once, keeps
-// the 256 copies alive across the epilogue and spills them (and the next tile's fragments) to scratch memory.
-__device__ __forceinline__ float acc_value(float in_acc)
-{
-    float v;
-    asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(v) : "a"(in_acc));
-    return v;
-}
+// Accumulator layout of a wavefront: acc[a][b][i] is row a 16 + 4 (lane >> 4) + i, column b 16 + (lane & 15) of its
+// 128 x 64 part of the tile.
 
-// Folds the 64 rows this lane holds of column block b (4 MFMA tiles x 16 values) into the lane's running
-// (max, sum).  Row offset of acc[a][b][4 i + j] inside the lane's slice is a 32 + 8 i + j; offsets >= mlim lie
-// past the last row (only in the last, ragged tile).  The accumulators are only read.
-// The scheduling fences after each MFMA tile keep the copies of the accumulators short-lived: without them the
-// register allocator spills across the K loop and a reload there waits for every direct load in flight.
+// Folds the 32 rows this lane holds of column block b (8 MFMA tiles x 4 values) into the lane's running
+// (max, sum).  Row offsets >= mlim lie past the last row (only in the last, ragged tile); mlim is relative to the
+// lane's first row.  The accumulators are only read.
 template <bool RAGGED>
-__device__ __forceinline__ void fold_column(const f32x16_t (&acc)[4][4], int b, int mlim, float &run_m, float &run_s)
+__device__ __forceinline__ void fold_column(const f32x4_t (&acc)[8][4], int b, int mlim, float &run_m, float &run_s)
 {
     float mx = -INFINITY;
 #pragma unroll
-    for (int a = 0; a < 4; ++a) {
+    for (int a = 0; a < 8; ++a) {
 #pragma unroll
-        for (int e = 0; e < 16; ++e) {
-            float v = acc_value(acc[a][b][e]);
-            if (RAGGED && a * 32 + (e >> 2) * 8 + (e & 3) >= mlim) v = -INFINITY;
+        for (int i = 0; i < 4; ++i) {
+            float v = acc[a][b][i];
+            if (RAGGED && a * 16 + i >= mlim) v = -INFINITY;
             mx = fmaxf(mx, v);
         }
-        __builtin_amdgcn_sched_barrier(0);
     }
     const float m_new = fmaxf(run_m, mx);
     float s = run_s * exp2_hw((run_m - m_new) * kLog2e);
 #pragma unroll
-    for (int a = 0; a < 4; ++a) {
+    for (int a = 0; a < 8; ++a) {
 #pragma unroll
-        for (int e = 0; e < 16; ++e) {
-            float v = acc_value(acc[a][b][e]);
-            if (RAGGED && a * 32 + (e >> 2) * 8 + (e & 3) >= mlim) v = -INFINITY;
+        for (int i = 0; i < 4; ++i) {
+            float v = acc[a][b][i];
+            if (RAGGED && a * 16 + i >= mlim) v = -INFINITY;
             s += exp2_hw((v - m_new) * kLog2e);
         }
-        __builtin_amdgcn_sched_barrier(0);
     }
     run_m = m_new;
     run_s = s;
 }
 
-// One accumulator register of every MFMA tile goes to row (8 i + j + 4 (lane >> 5)) of its 32-row block and to
-// column lane & 31: a wavefront's store of one register covers two rows x 32 consecutive columns.
-// EDGE: the tile reaches past M or N; rows / columns beyond are skipped.
+// Element-wise store of a wavefront's part of the tile: one accumulator register covers 4 rows x 16 consecutive
+// columns.  EDGE: the tile reaches past M or N; rows / columns beyond are skipped.  Used for tiles on the edge and
+// for sums into C, which go through the memory side's adders (every element has one owner per launch and launches
+// are ordered on the stream, so the sum is deterministic; nobody waits for its result).
 template <int EPI, bool EDGE>
-__device__ __forceinline__ void store_tile(const f32x16_t (&acc)[4][4], void *C, int64_t ldc, int64_t m0, int64_t n0,
+__device__ __forceinline__ void store_tile(const f32x4_t (&acc)[8][4], void *C, int64_t ldc, int64_t m0, int64_t n0,
                                            int64_t M, int64_t N, int wm, int wn, int lane, bool add)
 {
-    const int col0 = wn * 128 + (lane & 31);
-    const int row0 = wm * 128 + 4 * (lane >> 5);
+    const int col0 = wn * 64 + (lane & 15);
+    const int row0 = wm * 128 + 4 * (lane >> 4);
     const int rows_left = (int)(M - m0 < kGemmTile ? M - m0 : kGemmTile);
     const int cols_left = (int)(N - n0 < kGemmTile ? N - n0 : kGemmTile);
 #pragma unroll
-    for (int a = 0; a < 4; ++a) {
+    for (int a = 0; a < 8; ++a) {
 #pragma unroll
-        for (int e = 0; e < 16; ++e) {
-            const int row = row0 + a * 32 + (e >> 2) * 8 + (e & 3);
+        for (int i = 0; i < 4; ++i) {
+            const int row = row0 + a * 16 + i;
             if (EDGE && row >= rows_left) continue;
             const int64_t at = (m0 + row) * ldc + n0 + col0;
 #pragma unroll
             for (int b = 0; b < 4; ++b) {
-                if (EDGE && col0 + b * 32 >= cols_left) continue;
-                const float v = acc_value(acc[a][b][e]);
+                if (EDGE && col0 + b * 16 >= cols_left) continue;
+                const float v = acc[a][b][i];
                 if constexpr (EPI == kEpiStoreBf16) {
-                    reinterpret_cast<uint16_t *>(C)[at + b * 32] = (uint16_t)(pack_bf16x2(v, 0.0f) & 0xFFFFu);
+                    reinterpret_cast<uint16_t *>(C)[at + b * 16] = (uint16_t)(pack_bf16x2(v, 0.0f) & 0xFFFFu);
                 } else if constexpr (EPI == kEpiAccumF32) {
-                    float *p = reinterpret_cast<float *>(C) + at + b * 32;
-                    // every element has one owner per launch and launches are ordered on the stream, so the sum is
-                    // deterministic; the add is done by the memory side and nobody waits for its result
+                    float *p = reinterpret_cast<float *>(C) + at + b * 16;
                     if (add) unsafeAtomicAdd(p, v);
                     else *p = v;
                 } else {
-                    reinterpret_cast<float *>(C)[at + b * 32] = v;
+                    reinterpret_cast<float *>(C)[at + b * 16] = v;
                 }
             }
-            __builtin_amdgcn_sched_barrier(0);  // one row's address and values at a time
         }
+        __builtin_amdgcn_sched_barrier(0);
     }
 }
 
-// The same for a tile that lies inside C, with 16-byte stores: each 32 x 32 MFMA tile goes through a staging tile in
-// LDS that belongs to this wavefront alone (LDS instructions of one wavefront execute in order, so no waits or
-// barriers are needed between its writes and its reads), and leaves as 8 rows x 128 bytes (fp32) or 8 rows x 64
-// bytes (bfloat16) per store instruction instead of 2 rows x 32 elements.
+// The same for a tile that lies inside C, with 16-byte stores: 16 rows x 32 columns at a time go through a staging
+// tile in LDS that belongs to this wavefront alone (LDS instructions of one wavefront execute in order, so no waits
+// or barriers are needed between its writes and its reads) and leave as 8 rows x 128 bytes (fp32) or 8 rows x 64
+// bytes (bfloat16) per store instruction.
 template <int EPI>
-__device__ __forceinline__ void store_tile_wide(const f32x16_t (&acc)[4][4], void *C, int64_t ldc, int64_t m0, int64_t n0,
+__device__ __forceinline__ void store_tile_wide(const f32x4_t (&acc)[8][4], void *C, int64_t ldc, int64_t m0, int64_t n0,
                                                 int wm, int wn, int lane, float *stage)
 {
     static_assert(EPI == kEpiStoreBf16 || EPI == kEpiLseStore || EPI == kEpiAccumF32, "plain stores only");
-    const int wcol = lane & 31, wrow = 4 * (lane >> 5);  // where this lane's accumulator registers sit in the tile
+    const int wcol = lane & 15, wrow = 4 * (lane >> 4);  // where this lane's accumulator registers sit in a 16 x 16 tile
     const int rrow = lane >> 3, rcol = (lane & 7) * 4;   // what it reads back: 4 consecutive columns of row rrow + 8 pass
 #pragma unroll
-    for (int a = 0; a < 4; ++a) {
+    for (int a = 0; a < 8; ++a) {
 #pragma unroll
-        for (int b = 0; b < 4; ++b) {
+        for (int bp = 0; bp < 2; ++bp) {  // column blocks 2 bp, 2 bp + 1
 #pragma unroll
-            for (int e = 0; e < 16; ++e) stage[(wrow + (e >> 2) * 8 + (e & 3)) * kStageLd + wcol] = acc_value(acc[a][b][e]);
+            for (int bb = 0; bb < 2; ++bb)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) stage[(wrow + i) * kStageLd + bb * 16 + wcol] = acc[a][2 * bp + bb][i];
             asm volatile("" ::: "memory");
-            const int64_t at = (m0 + wm * 128 + a * 32 + rrow) * ldc + n0 + wn * 128 + b * 32 + rcol;
+            const int64_t at = (m0 + wm * 128 + a * 16 + rrow) * ldc + n0 + wn * 64 + bp * 32 + rcol;
 #pragma unroll
-            for (int pass = 0; pass < 4; ++pass) {
+            for (int pass = 0; pass < 2; ++pass) {
                 const float4 v = *reinterpret_cast<const float4 *>(stage + (rrow + 8 * pass) * kStageLd + rcol);
                 if constexpr (EPI == kEpiStoreBf16) {
                     *reinterpret_cast<uint2 *>(reinterpret_cast<uint16_t *>(C) + at + (int64_t)pass * 8 * ldc) =
@@ -196,15 +189,16 @@ __device__ __forceinline__ void store_tile_wide(const f32x16_t (&acc)[4][4], voi
 
 // QUAD: K is a multiple of kDmaStages stages.  Then every tile starts in ring slot 0, the K loop is unrolled by
 // the ring depth (all LDS addresses are constants) and the refill cursor moves once per kDmaStages stages.
-// Otherwise the loop is unrolled by two (the fragment buffers alternate; the number of stages is even) and slot
+// Otherwise the loop is unrolled by two (the column fragments alternate; the number of stages is even) and slot
 // and cursor are tracked per stage.
 template <int EPI, bool QUAD>
 __global__ __launch_bounds__(kGemmThreads) void gemm_nt_kernel(const GemmArgs g)
 {
     extern __shared__ __align__(16) char lds[];
     constexpr bool LSE = EPI == kEpiLse || EPI == kEpiLseStore;
+    constexpr int kLoads = 4;  // direct loads per wavefront and stage: two 16-row blocks of A, two of B
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave & 1, wn = wave >> 1;  // row half, column half of the tile
+    const int wm = wave & 1, wn = wave >> 1;  // row half (128 rows), column quarter (64 columns) of the tile
     const int xcd = (int)(blockIdx.x % (unsigned)g.nxcd), slot = (int)(blockIdx.x / (unsigned)g.nxcd);
     const int nl = slot & (kGemmColTiles - 1), ml = slot / kGemmColTiles;
     int64_t M = g.M, N = g.N, K = g.K;
@@ -233,16 +227,15 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_nt_kernel(const GemmArgs g)
         return p;
     };
 
-    // direct loads: instruction j of an operand covers tile rows (4 j + wave) 16 .. + 15; lane -> row lane >> 2,
+    // direct loads: instruction j of an operand covers tile rows (8 j + wave) 16 .. + 15; lane -> row lane >> 2,
     // physical piece lane & 3, which holds logical piece (lane & 3) ^ ((row >> 2) & 3) = (lane & 3) ^ ((lane >> 4) & 3)
     const int drow = lane >> 2;
     const uint32_t dpiece = (uint32_t)((lane & 3) ^ ((lane >> 4) & 3)) * 16u;
-    // fragment reads: row lane & 31 of a 32-row MFMA tile, k half lane >> 5 of k-step s: logical piece 2 s + (lane >> 5),
-    // physical piece that ^ ((row >> 2) & 3) = that ^ ((lane >> 2) & 3)
-    const uint32_t fr[2] = {(uint32_t)(lane & 31) * kDmaRowBytes + (uint32_t)(((lane >> 5) ^ ((lane >> 2) & 3)) * 16),
-                            (uint32_t)(lane & 31) * kDmaRowBytes + (uint32_t)(((2 + (lane >> 5)) ^ ((lane >> 2) & 3)) * 16)};
-    const uint32_t fa_base = (uint32_t)(wm * 128) * kDmaRowBytes;
-    const uint32_t fb_base = kDmaOperandBytes + (uint32_t)(wn * 128) * kDmaRowBytes;
+    // fragment reads: row lane & 15 of a 16-row block, k quarter lane >> 4 = logical piece, physical piece
+    // that ^ ((row >> 2) & 3) = that ^ ((lane >> 2) & 3); block t of an operand starts at t * 1024 bytes
+    const uint32_t fr = (uint32_t)(lane & 15) * kDmaRowBytes + (uint32_t)(((lane >> 4) ^ ((lane >> 2) & 3)) * 16);
+    const uint32_t fa_base = (uint32_t)(wm * 8) * 1024u + fr;
+    const uint32_t fb_base = kDmaOperandBytes + (uint32_t)(wn * 4) * 1024u + fr;
 
     int64_t p_cur = next_tile((int64_t)xcd * pairs / g.nxcd);
     if (p_cur >= p_end) return;  // uniform over the workgroup
@@ -254,15 +247,15 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_nt_kernel(const GemmArgs g)
     int64_t r_p = p_cur;
     int r_k = 0;
     const char *r_a = nullptr, *r_b = nullptr;
-    uint32_t aoff[4], boff[4];
+    uint32_t aoff[2], boff[2];
     auto set_tile = [&](int64_t p) {
         const int mt = (int)(p % rounds) * g.ml_count + ml, nt = (int)(p / rounds) * kGemmColTiles + nl;
         r_a = reinterpret_cast<const char *>(g.A + (int64_t)mt * kGemmTile * g.lda);
         r_b = reinterpret_cast<const char *>(g.B + (int64_t)nt * kGemmTile * g.ldb);
         const int m_last = (int)(M - 1 - (int64_t)mt * kGemmTile), n_last = (int)(N - 1 - (int64_t)nt * kGemmTile);
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int r = (4 * j + wave) * 16 + drow;
+        for (int j = 0; j < 2; ++j) {
+            const int r = (8 * j + wave) * 16 + drow;
             aoff[j] = (uint32_t)min(r, m_last) * lda2 + dpiece;
             boff[j] = (uint32_t)min(r, n_last) * ldb2 + dpiece;
         }
@@ -271,7 +264,7 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_nt_kernel(const GemmArgs g)
     // direct load number q of one operand (0: A rows, 1: B rows) of stage r_k + u into ring slot sl
     auto refill = [&](int sl, int q, int u, int operand) {
         const uint32_t koff = (uint32_t)(r_k + u) * (uint32_t)kDmaRowBytes;
-        char *dst = lds + sl * kDmaStageBytes + wave_s * 1024 + q * 4096;
+        char *dst = lds + sl * kDmaStageBytes + wave_s * 1024 + q * 8192;
         if (operand == 0) dma16(r_a + koff + aoff[q], dst);
         else dma16(r_b + koff + boff[q], dst + kDmaOperandBytes);
     };
@@ -292,25 +285,20 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_nt_kernel(const GemmArgs g)
 #pragma unroll
     for (int st = 0; st < kDmaStages; ++st) {
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
+        for (int q = 0; q < 2; ++q) {
             refill(st, q, QUAD ? st : 0, 0);
             refill(st, q, QUAD ? st : 0, 1);
         }
         if (!QUAD) advance(1);
     }
     if (QUAD) advance(kDmaStages);
-    __builtin_amdgcn_s_waitcnt(waitcnt_imm(8 * (kDmaStages - 1), kNoLgkmWait));  // everything issued after the first stage may fly
+    __builtin_amdgcn_s_waitcnt(waitcnt_imm(kLoads * (kDmaStages - 1), kNoLgkmWait));  // everything issued after the first stage may fly
     __builtin_amdgcn_s_barrier();  // bare, as in the K loop: the rest of the ring stays in flight
-    bf16x8_t fa[2][2][4], fb[2][2][4];  // [buffer][k-step][MFMA tile]
+    bf16x8_t fa[8], fb[2][4];
 #pragma unroll
-    for (int ks = 0; ks < 2; ++ks) {
+    for (int a = 0; a < 8; ++a) fa[a] = *reinterpret_cast<const bf16x8_t *>(lds + fa_base + a * 1024);
 #pragma unroll
-        for (int a = 0; a < 4; ++a)
-            fa[0][ks][a] = *reinterpret_cast<const bf16x8_t *>(lds + fa_base + a * 32 * kDmaRowBytes + fr[ks]);
-#pragma unroll
-        for (int b = 0; b < 4; ++b)
-            fb[0][ks][b] = *reinterpret_cast<const bf16x8_t *>(lds + fb_base + b * 32 * kDmaRowBytes + fr[ks]);
-    }
+    for (int b = 0; b < 4; ++b) fb[0][b] = *reinterpret_cast<const bf16x8_t *>(lds + fb_base + b * 1024);
     int sl_dyn = 0;  // ring slot of the stage being computed (tracked only when !QUAD)
 
     float run_m[4], run_s[4];  // kEpiLse*: this lane's four columns over the sweep
@@ -324,16 +312,16 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_nt_kernel(const GemmArgs g)
         const int grp = (int)(p_cur / rounds);
         const int64_t m0 = ((int64_t)(p_cur % rounds) * g.ml_count + ml) * kGemmTile;
         const int64_t n0 = ((int64_t)grp * kGemmColTiles + nl) * kGemmTile;
-        f32x16_t acc[4][4];
+        f32x4_t acc[8][4];
 #pragma unroll
-        for (int a = 0; a < 4; ++a)
+        for (int a = 0; a < 8; ++a)
 #pragma unroll
             for (int b = 0; b < 4; ++b)
 #pragma unroll
-                for (int e = 0; e < 16; ++e) acc[a][b][e] = 0.0f;
+                for (int i = 0; i < 4; ++i) acc[a][b][i] = 0.0f;
 
-        // One stage out of the fragments in buffer p (read from ring slot sl during the stage before);
-        // u: the stage's position in the cursor's group (0 when !QUAD).
+        // One stage out of the row fragments fa and the column fragments fb[p] (read from ring slot sl during the
+        // stage before); u: the stage's position in the cursor's group (0 when !QUAD).
         auto stage = [&](const int sl, const int u, const int p) __attribute__((always_inline)) {
             const int nsl = sl + 1 == kDmaStages ? 0 : sl + 1;
             const char *nxt = lds + nsl * kDmaStageBytes;
@@ -342,28 +330,21 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_nt_kernel(const GemmArgs g)
             // this stage is in registers (own reads, lgkmcnt(0)): meet.  A bare barrier: the fence that
             // __syncthreads() carries makes the compiler drain every direct load it can see in flight
             // (vmcnt(0)), which would empty the ring at each stage.
-            __builtin_amdgcn_s_waitcnt(waitcnt_imm(8 * (kDmaStages - 2), 0));
+            __builtin_amdgcn_s_waitcnt(waitcnt_imm(kLoads * (kDmaStages - 2), 0));
             __builtin_amdgcn_s_barrier();
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int grp8 = 0; grp8 < 8; ++grp8) {   // k-step grp8 >> 2, row MFMA tile grp8 & 3
-                const int ks = grp8 >> 2, q = grp8 & 3;
-                // two fragments of the next stage (the next tile's first stage, at the end of a tile) ...
-                if (q < 2) {
-#pragma unroll
-                    for (int a = 2 * q; a < 2 * q + 2; ++a)
-                        fa[p ^ 1][ks][a] = *reinterpret_cast<const bf16x8_t *>(nxt + fa_base + a * 32 * kDmaRowBytes + fr[ks]);
-                } else {
-#pragma unroll
-                    for (int b = 2 * q - 4; b < 2 * q - 2; ++b)
-                        fb[p ^ 1][ks][b] = *reinterpret_cast<const bf16x8_t *>(nxt + fb_base + b * 32 * kDmaRowBytes + fr[ks]);
-                }
-                // ... one direct load into the slot this stage came from ...
-                refill(sl, grp8 >> 1, u, grp8 & 1);
-                // ... and four MFMAs
+            for (int a = 0; a < 8; ++a) {
+                // a column fragment of the next stage, a direct load into the slot this stage came from ...
+                if (a < 4) fb[p ^ 1][a] = *reinterpret_cast<const bf16x8_t *>(nxt + fb_base + a * 1024);
+                if ((a & 1) == 0) refill(sl, a >> 2, u, (a >> 1) & 1);
+                // ... four MFMAs ...
 #pragma unroll
                 for (int b = 0; b < 4; ++b)
-                    acc[q][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[p][ks][q], fb[p][ks][b], acc[q][b], 0, 0, 0);
+                    acc[a][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[a], fb[p][b], acc[a][b], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+                // ... and this row fragment's successor, into the registers those MFMAs have just read
+                fa[a] = *reinterpret_cast<const bf16x8_t *>(nxt + fa_base + a * 1024);
                 __builtin_amdgcn_sched_barrier(0);
             }
         };
@@ -395,35 +376,38 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_nt_kernel(const GemmArgs g)
         if constexpr (EPI != kEpiLse) {
             // tiles inside C leave with 16-byte stores (the launcher checks that rows of C start on 16 bytes);
             // only sums into C go element by element, through the memory side's adders
-            float *stage = reinterpret_cast<float *>(lds + kDmaRingBytes + kGemmRedBytes + wave_s * kStageBytes);
+            float *stage_tile = reinterpret_cast<float *>(lds + kDmaRingBytes + kGemmRedBytes + wave_s * kStageBytes);
             if (edge) {
                 store_tile<EPI, true>(acc, g.C, g.ldc, m0, n0, M, N, wm, wn, lane, g.accumulate != 0);
             } else if constexpr (EPI == kEpiAccumF32) {
                 if (g.accumulate != 0) store_tile<EPI, false>(acc, g.C, g.ldc, m0, n0, M, N, wm, wn, lane, true);
-                else store_tile_wide<EPI>(acc, g.C, g.ldc, m0, n0, wm, wn, lane, stage);
+                else store_tile_wide<EPI>(acc, g.C, g.ldc, m0, n0, wm, wn, lane, stage_tile);
             } else {
-                store_tile_wide<EPI>(acc, g.C, g.ldc, m0, n0, wm, wn, lane, stage);
+                store_tile_wide<EPI>(acc, g.C, g.ldc, m0, n0, wm, wn, lane, stage_tile);
             }
         }
         if constexpr (LSE) {
             const bool ragged = m0 + kGemmTile > M;
-            const int mlim = (int)(M - m0) - wm * 128 - (lane >> 5) * 4;
+            const int mlim = (int)(M - m0) - wm * 128 - (lane >> 4) * 4;
 #pragma unroll
             for (int b = 0; b < 4; ++b) {
                 if (ragged) fold_column<true>(acc, b, mlim, run_m[b], run_s[b]);
                 else fold_column<false>(acc, b, mlim, run_m[b], run_s[b]);
                 __builtin_amdgcn_sched_barrier(0);
             }
-            // end of this column group's sweep: merge the two lane halves, then the two row halves, and write the
+            // end of this column group's sweep: merge the four lane groups, then the two row halves, and write the
             // workgroup's partial of its 256 columns (the reduction has LDS of its own: the ring keeps running)
             if (p_next >= p_end || (int)(p_next / rounds) != grp) {
                 float2 *red = reinterpret_cast<float2 *>(lds + kDmaRingBytes);  // [2][256]
 #pragma unroll
                 for (int b = 0; b < 4; ++b) {
                     MaxSum mine = {run_m[b], run_s[b]};
-                    MaxSum other = {__shfl_xor(mine.m, 32, kWave), __shfl_xor(mine.s, 32, kWave)};
-                    mine = combine(mine, other);
-                    if (lane < 32) red[wm * kGemmTile + wn * 128 + b * 32 + lane] = make_float2(mine.m, mine.s);
+#pragma unroll
+                    for (int off = 16; off <= 32; off <<= 1) {
+                        const MaxSum other = {__shfl_xor(mine.m, off, kWave), __shfl_xor(mine.s, off, kWave)};
+                        mine = combine(mine, other);
+                    }
+                    if (lane < 16) red[wm * kGemmTile + wn * 64 + b * 16 + lane] = make_float2(mine.m, mine.s);
                     run_m[b] = kNegFloor;
                     run_s[b] = 0.0f;
                 }
@@ -432,9 +416,12 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_nt_kernel(const GemmArgs g)
                 __builtin_amdgcn_s_waitcnt(waitcnt_imm(kNoVmWait, 0));
                 __builtin_amdgcn_s_barrier();
                 asm volatile("" ::: "memory");
-                const float2 q0 = red[tid], q1 = red[kGemmTile + tid];
-                const MaxSum tot = combine(MaxSum{q0.x, q0.y}, MaxSum{q1.x, q1.y});
-                if (n0 + tid < N) g.partial[(int64_t)(xcd * g.ml_count + ml) * g.partial_stride + n0 + tid] = make_float2(tot.m, tot.s);
+                if (tid < kGemmTile) {
+                    const float2 q0 = red[tid], q1 = red[kGemmTile + tid];
+                    const MaxSum tot = combine(MaxSum{q0.x, q0.y}, MaxSum{q1.x, q1.y});
+                    if (n0 + tid < N)
+                        g.partial[(int64_t)(xcd * g.ml_count + ml) * g.partial_stride + n0 + tid] = make_float2(tot.m, tot.s);
+                }
                 asm volatile("" ::: "memory");
                 __builtin_amdgcn_s_waitcnt(waitcnt_imm(kNoVmWait, 0));  // red is read before anyone writes it again
                 __builtin_amdgcn_s_barrier();
