@@ -355,18 +355,22 @@ int a3po_fused_lmhead_logprob(const void *hidden, const void *weight, int64_t T,
  * then the gradient contracted back through the projection:
  *   z = hidden weight^T,  loss / log-probs / statistics as in a3po_loss_fwd_bwd (same arguments),
  *   dhidden[t, :] = sum_v dlogits[t, v] weight[v, :],   dweight[v, :] = sum_t dlogits[t, v] hidden[t, :].
- * Tokens are taken in chunks of 8,192.  The log-sum-exp and the log-probs of a chunk are folded from fp32
- * tiles as they leave the matrix cores, exactly as in a3po_fused_lmhead_logprob (both entry points give the
- * same log pi_theta up to rounding order); the same tiles are also kept in fp32 inside the workspace, for
- * that chunk only, and the gradient rows dlogits are formed from them in fp32 and rounded once to bfloat16,
- * the operand type of the matrix cores.  The three contractions are this library's own kernel (bfloat16
- * operands, fp32 accumulation); dweight is accumulated over the chunks in fp32 and rounded to bfloat16 once.
+ * Only tokens that enter the loss (mask != 0, valid id) are projected: every other token has log-prob 0 and a
+ * zero row of dhidden by definition and costs nothing beyond that row's zero fill.  The counted tokens are
+ * compacted on the device and taken in chunks of 8,192.  The log-sum-exp and the log-probs of a chunk are
+ * folded from fp32 tiles as they leave the matrix cores, exactly as in a3po_fused_lmhead_logprob (both entry
+ * points give the same log pi_theta up to rounding order); the same tiles are also kept in fp32 inside the
+ * workspace, for that chunk only, and the gradient rows dlogits are formed from them in fp32 and rounded once
+ * to bfloat16, the operand type of the matrix cores.  The three contractions are this library's own kernel
+ * (bfloat16 operands, fp32 accumulation); dweight is contracted over up to 65,536 counted tokens at a time,
+ * accumulated in fp32 beyond that, and rounded to bfloat16 once.
  * hidden, dhidden [T, H]; weight, dweight [V, H]: row-major, contiguous, bfloat16, 16-byte
  * aligned; H a positive multiple of 64, at most 2^20; V a multiple of 8 below 2^21; T below 2^22
  * (A3PO_E_SIZE otherwise).  Per-token arguments and outputs as in a3po_loss_fwd_bwd.
  * workspace: a3po_workspace_bytes(A3PO_WS_FUSED_LMHEAD_LOSS, T, V, H) bytes, 256-byte aligned: the fp32
- * accumulator of dweight, W^T and h^T, and a chunk of logits (fp32) and of their gradient (bfloat16, in both
- * orientations) - about 4 V H + 2 V H + 2 T H + 8 * 8192 V bytes, 14 GB at T = 65,536, H = 4,096, V = 151,936.
+ * accumulator of dweight, W^T, the gathered hidden rows and their transpose, a chunk of logits (fp32) and of
+ * its gradient, and the vocabulary-major gradient of up to 65,536 tokens - about 6 V H + 6 T H + 6 * 8192 V +
+ * 2 V min(T, 65536) bytes, 33 GB at T = 65,536, H = 4,096, V = 151,936.
  */
 int a3po_fused_lmhead_loss_fwd_bwd(const void *hidden, const void *weight, int64_t T, int64_t H, int64_t V,
                                    const int32_t *chosen, const float *logp_behav,

@@ -150,6 +150,36 @@ __device__ __forceinline__ void store_tile(const f32x4_t (&acc)[8][4], void *C, 
     }
 }
 
+// fp32 store of C^T (element (m, n) at C[n * ldc + m]): the four values of an accumulator register are four
+// consecutive m of one column n, i.e. 16 contiguous bytes, so every register leaves with one 16-byte store and no
+// staging; a wavefront's instruction covers 16 columns x 64 contiguous bytes.  M is a multiple of 4, so a group of
+// four rows lies inside or outside as a whole.  `add`: sums into C through the memory side's adders.
+template <bool EDGE>
+__device__ __forceinline__ void store_tile_transposed(const f32x4_t (&acc)[8][4], float *C, int64_t ldc, int64_t m0,
+                                                      int64_t n0, int64_t M, int64_t N, int wm, int wn, int lane, bool add)
+{
+    const int col0 = wn * 64 + (lane & 15);
+    const int row0 = wm * 128 + 4 * (lane >> 4);
+    const int rows_left = (int)(M - m0 < kGemmTile ? M - m0 : kGemmTile);
+    const int cols_left = (int)(N - n0 < kGemmTile ? N - n0 : kGemmTile);
+#pragma unroll
+    for (int b = 0; b < 4; ++b) {
+        if (EDGE && col0 + b * 16 >= cols_left) continue;
+        float *col = C + (n0 + col0 + b * 16) * ldc + m0 + row0;
+#pragma unroll
+        for (int a = 0; a < 8; ++a) {
+            if (EDGE && row0 + a * 16 >= rows_left) continue;
+            if (add) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) unsafeAtomicAdd(col + a * 16 + i, acc[a][b][i]);
+            } else {
+                *reinterpret_cast<float4 *>(col + a * 16) = make_float4(acc[a][b][0], acc[a][b][1], acc[a][b][2], acc[a][b][3]);
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    }
+}
+
 // The same for a tile that lies inside C, with 16-byte stores: 16 rows x 32 columns at a time go through a staging
 // tile in LDS that belongs to this wavefront alone (LDS instructions of one wavefront execute in order, so no waits
 // or barriers are needed between its writes and its reads) and leave as 8 rows x 128 bytes (fp32) or 8 rows x 64
@@ -250,23 +280,26 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_nt_kernel(const GemmArgs g)
     uint32_t aoff[2], boff[2];
     auto set_tile = [&](int64_t p) {
         const int mt = (int)(p % rounds) * g.ml_count + ml, nt = (int)(p / rounds) * kGemmColTiles + nl;
-        r_a = reinterpret_cast<const char *>(g.A + (int64_t)mt * kGemmTile * g.lda);
+        r_a = reinterpret_cast<const char *>(g.A + (int64_t)mt * kGemmTile * g.lda);  // (a 256-row band of panels is as long)
         r_b = reinterpret_cast<const char *>(g.B + (int64_t)nt * kGemmTile * g.ldb);
         const int m_last = (int)(M - 1 - (int64_t)mt * kGemmTile), n_last = (int)(N - 1 - (int64_t)nt * kGemmTile);
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
             const int r = (8 * j + wave) * 16 + drow;
-            aoff[j] = (uint32_t)min(r, m_last) * lda2 + dpiece;
-            boff[j] = (uint32_t)min(r, n_last) * ldb2 + dpiece;
+            // panels: every row of the band exists (padding), rows are 128 bytes apart
+            aoff[j] = g.a_panel ? (uint32_t)r * 128u + dpiece : (uint32_t)min(r, m_last) * lda2 + dpiece;
+            boff[j] = g.b_panel ? (uint32_t)r * 128u + dpiece : (uint32_t)min(r, n_last) * ldb2 + dpiece;
         }
     };
     set_tile(r_p);
     // direct load number q of one operand (0: A rows, 1: B rows) of stage r_k + u into ring slot sl
     auto refill = [&](int sl, int q, int u, int operand) {
-        const uint32_t koff = (uint32_t)(r_k + u) * (uint32_t)kDmaRowBytes;
+        const uint32_t st = (uint32_t)(r_k + u);
+        const uint32_t koff = st * (uint32_t)kDmaRowBytes;                 // rows: 64 bytes further along the row
+        const uint32_t poff = (st >> 1) * 32768u + (st & 1u) * 64u;        // panels: the next half block
         char *dst = lds + sl * kDmaStageBytes + wave_s * 1024 + q * 8192;
-        if (operand == 0) dma16(r_a + koff + aoff[q], dst);
-        else dma16(r_b + koff + boff[q], dst + kDmaOperandBytes);
+        if (operand == 0) dma16(r_a + (g.a_panel ? poff : koff) + aoff[q], dst);
+        else dma16(r_b + (g.b_panel ? poff : koff) + boff[q], dst + kDmaOperandBytes);
     };
     auto advance = [&](int step) {
         if (r_k + step < nstages) {
@@ -377,7 +410,12 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_nt_kernel(const GemmArgs g)
             // tiles inside C leave with 16-byte stores (the launcher checks that rows of C start on 16 bytes);
             // only sums into C go element by element, through the memory side's adders
             float *stage_tile = reinterpret_cast<float *>(lds + kDmaRingBytes + kGemmRedBytes + wave_s * kStageBytes);
-            if (edge) {
+            if (EPI != kEpiStoreBf16 && g.transposed != 0) {
+                float *ct = reinterpret_cast<float *>(g.C);
+                const bool add = EPI == kEpiAccumF32 && g.accumulate != 0;
+                if (edge) store_tile_transposed<true>(acc, ct, g.ldc, m0, n0, M, N, wm, wn, lane, add);
+                else store_tile_transposed<false>(acc, ct, g.ldc, m0, n0, M, N, wm, wn, lane, add);
+            } else if (edge) {
                 store_tile<EPI, true>(acc, g.C, g.ldc, m0, n0, M, N, wm, wn, lane, g.accumulate != 0);
             } else if constexpr (EPI == kEpiAccumF32) {
                 if (g.accumulate != 0) store_tile<EPI, false>(acc, g.C, g.ldc, m0, n0, M, N, wm, wn, lane, true);
@@ -498,6 +536,9 @@ hipError_t launch_gemm_nt(const GemmArgs &g, int epilogue, hipStream_t s)
         g.ldb < g.K || g.lda > (1 << 22) || g.ldb > (1 << 22))
         return hipErrorInvalidValue;
     if (g.dyn_dim != kDynNone && (!g.dyn.n || (g.dyn_dim == kDynK && g.K % 128 != 0))) return hipErrorInvalidValue;
+    if ((g.a_panel && g.lda % 64 != 0) || (g.b_panel && g.ldb % 64 != 0)) return hipErrorInvalidValue;
+    if (g.transposed != 0 && (g.M % 4 != 0 || g.dyn_dim == kDynM || epilogue == kEpiStoreBf16 || epilogue == kEpiLse))
+        return hipErrorInvalidValue;
     if (epilogue != kEpiLse && (g.ldc % 8 != 0 || (reinterpret_cast<uintptr_t>(g.C) & 15) != 0)) return hipErrorInvalidValue;
     switch (epilogue) {
         case kEpiLse: return launch_gemm_t<kEpiLse>(g, s);

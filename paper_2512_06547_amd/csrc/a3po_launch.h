@@ -154,11 +154,25 @@ struct GemmArgs {
     int64_t ldc;
     float2 *partial;    // kEpiLse*: [gemm_partial_slots()][partial_stride] (max, sum) per column, merged by the caller
     int64_t partial_stride;
+    int a_panel, b_panel;  // the operand is stored in panels instead of rows (see panel_offset): lda / ldb is then the
+                           // K extent of the buffer (a multiple of 64), rows are padded to a multiple of 256
     int accumulate;     // kEpiAccumF32
+    int transposed;     // kEpiLseStore / kEpiAccumF32: element (m, n) goes to C[n * ldc + m] (C^T row-major, row stride
+                        // ldc): a lane's four accumulator values are then 16 contiguous bytes.  Needs M % 4 == 0.
     int dyn_dim;        // GemmDynDim: which of M, N, K is replaced by dyn_extent(dyn, .) on the device (K: rounded up
     DynCount dyn;       // to 128; the host's M, N, K are then upper bounds).  A zero extent makes the launch a no-op.
     int nxcd, ml_count; // filled in by the launcher from the device
 };
+
+// Panel layout of a bfloat16 operand of the contraction kernel: the matrix is cut into blocks of 256 rows x 64
+// contracted elements, each stored as 256 rows x 128 bytes = 32 KiB contiguous; blocks of one 256-row band follow
+// each other along K.  A stage of the kernel (256 rows x 32 elements) then reads half of one such block: one
+// contiguous 32 KiB region instead of 256 pieces a whole row apart.  Element offset of (row, k), kext = K extent:
+__host__ __device__ inline int64_t panel_offset(int64_t row, int64_t k, int64_t kext)
+{
+    return ((row >> 8) * (kext >> 6) + (k >> 6)) * 16384 + (row & 255) * 64 + (k & 63);
+}
+inline size_t panel_elements(int64_t rows, int64_t kext) { return (size_t)((rows + 255) / 256 * 256) * (size_t)kext; }
 
 struct GemmGrid {
     int nxcd, ml_count, blocks;

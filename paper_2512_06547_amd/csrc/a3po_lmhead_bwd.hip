@@ -7,15 +7,16 @@
 // below is sized for the worst case and reads the count from memory - nothing waits for the host.
 //
 // The compacted tokens are processed in chunks.  For each chunk
-//   1. z^T = W h_chunk^T on the matrix cores; every 256 x 256 tile is folded into the running (max, sum) of its
+//   1. z = h_chunk W^T on the matrix cores; every 256 x 256 tile is folded into the running (max, sum) of its
 //      tokens while it is still in the accumulators (fp32: the log-sum-exp and the log-probs never see a rounded
-//      logit) and is also stored, as fp32, vocabulary-major, for the backward pass of the same chunk;
+//      logit) and is also stored, as fp32, for the backward pass of the same chunk;
 //   2. log pi_theta, then Eq. 2 - Eq. 4 per token: loss terms, statistics and g_t = d loss / d log pi_theta;
 //   3. dz[t, v] = g_t ([v == y_t] - exp(z[t, v] - lse_t)), rounded once to bfloat16 (the matrix cores take
 //      bfloat16 operands), written token-major and vocabulary-major in one pass over the stored logits;
 //   4. dh_chunk = dz W            (contraction over the vocabulary: dz token-major against W^T)
-//   5. dW     += dz^T h_chunk     (contraction over the tokens: dz vocabulary-major against h^T; fp32
-//      accumulator across chunks, rounded to bfloat16 once at the end).
+// and once per group of kLmDwGroup chunks
+//   5. dW     += dz^T h_group     (contraction over the tokens: h^T against dz vocabulary-major; fp32
+//      accumulator across groups, rounded to bfloat16 once at the end).
 // All three contractions are the kernel of a3po_gemm.hip, which wants the contracted index contiguous in both
 // operands; W^T and h^T are therefore written once per call.  6 N V H flops per step for N counted tokens: the
 // logits of a chunk are kept (4 bytes each, 5 GB for 8,192 tokens at V = 151,936) rather than recomputed, which
@@ -29,14 +30,19 @@ namespace a3po {
 #define A3PO_LM_BWD_CHUNK 8192
 #endif
 constexpr int64_t kLmBwdChunk = A3PO_LM_BWD_CHUNK;  // tokens whose logits live in HBM at a time
+// The weight gradient is contracted once per this many chunks: every contraction into it ends with a pass over the
+// whole V x H accumulator, so fewer, longer ones are cheaper; the price is the vocabulary-major gradient of a
+// whole group in memory (20 GB for 65,536 tokens at V = 151,936; batches up to that size need a single contraction and no
+// accumulation pass at all).
+constexpr int64_t kLmDwGroup = 8;
 constexpr int64_t kPadK = 128;                      // contracted extents are zero-padded to this
 
 struct LmBwdLayout {
     size_t lse, g, logp, ysel, index, pos, counts, partial, zt, dzt, dz, wt, hc, ht, dhc, dwacc, total;
     int64_t chunk;  // compacted tokens per chunk
-    int64_t ldn;    // row stride of the vocabulary-major chunk buffers: the chunk length padded to kPadK tokens
-    int64_t ldv;    // row stride of the token-major gradient chunk and of W^T: V padded to kPadK
-    int64_t ldt;    // row stride of h^T: T padded to kPadK
+    int64_t ldg;    // K extent of the vocabulary-major gradient: the tokens of a group of chunks, padded to kPadK
+    int64_t ldv;    // K extent of the token-major gradient chunk and of W^T (and row stride of the chunk's logits): V padded
+    int64_t ldt;    // K extent of h^T: T padded to kPadK
 };
 
 constexpr int kCompactBlock = 1024;  // tokens per workgroup of the compaction kernels
@@ -48,7 +54,7 @@ static LmBwdLayout lmhead_bwd_layout(int64_t T, int64_t V, int64_t H)
     const size_t t = (size_t)(T > 0 ? T : 0), v = (size_t)V, h = (size_t)H;
     LmBwdLayout l;
     l.chunk = T < kLmBwdChunk ? (T > 0 ? T : 1) : kLmBwdChunk;
-    l.ldn = pad(l.chunk);
+    l.ldg = pad(T < kLmDwGroup * kLmBwdChunk ? (T > 0 ? T : 1) : kLmDwGroup * kLmBwdChunk);
     l.ldv = pad(V);
     l.ldt = pad(T > 0 ? T : 1);
     // per compacted token: lse, g, log pi, chosen id, position of the token; per token: its compacted position
@@ -61,12 +67,13 @@ static LmBwdLayout lmhead_bwd_layout(int64_t T, int64_t V, int64_t H)
     l.counts = l.pos + up(t * sizeof(int32_t));
     l.partial = l.counts + up(((t + kCompactBlock - 1) / kCompactBlock + 1) * sizeof(int32_t));
     l.zt = l.partial + up((size_t)kGemmMaxPartialSlots * (size_t)l.chunk * sizeof(float2));
-    l.dzt = l.zt + up(v * (size_t)l.ldn * sizeof(float));
-    l.dz = l.dzt + up(v * (size_t)l.ldn * 2);
-    l.wt = l.dz + up((size_t)l.chunk * (size_t)l.ldv * 2);
-    l.hc = l.wt + up(h * (size_t)l.ldv * 2);
+    l.dzt = l.zt + up((size_t)l.chunk * (size_t)l.ldv * sizeof(float));
+    // the four operands that this file's own kernels write are kept in the contraction kernel's panel layout
+    l.dz = l.dzt + up(panel_elements(V, l.ldg) * 2);
+    l.wt = l.dz + up(panel_elements(l.chunk, l.ldv) * 2);
+    l.hc = l.wt + up(panel_elements(H, l.ldv) * 2);
     l.ht = l.hc + up(t * h * 2);
-    l.dhc = l.ht + up(h * (size_t)l.ldt * 2);
+    l.dhc = l.ht + up(panel_elements(H, l.ldt) * 2);
     l.dwacc = l.dhc + up(t * h * 2);
     l.total = l.dwacc + up(v * h * sizeof(float));
     return l;
@@ -94,16 +101,17 @@ __global__ void zero_bf16_kernel(uint16_t *__restrict__ dst, size_t n)
     if (i < n) dst[i] = 0;
 }
 
-// zeroes columns [c0, c1) of a row-major 2-byte matrix [R, ld]
-__global__ void zero_columns_kernel(uint16_t *__restrict__ m, int64_t R, int64_t ld, int64_t c0, int64_t c1)
+// zeroes the contracted positions [k0, k1) of every row of a panel-layout operand with `rows` rows (a multiple of 256)
+__global__ void zero_panel_columns_kernel(uint16_t *__restrict__ m, int64_t rows, int64_t kext, int64_t k0, int64_t k1)
 {
-    const int64_t w = c1 - c0;
+    const int64_t w = k1 - k0;
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < R * w) m[(i / w) * ld + c0 + i % w] = 0;
+    if (i < rows * w) m[panel_offset(i / w, k0 + i % w, kext)] = 0;
 }
 
-// out [C, ldo] = transpose of in [R, C] (row-major, contiguous, 2-byte elements; C a multiple of 8, ldo >= R a
-// multiple of 8); columns R .. ldo-1 of `out` (the padding of the contracted index) are written as zeros.
+// out = transpose of in [R, C] (row-major, contiguous, 2-byte elements; C a multiple of 8) as a panel-layout operand
+// with C rows and K extent ldo (>= R, a multiple of 64); positions R .. ldo-1 of every row (the padding of the
+// contracted index) are written as zeros.
 // A workgroup moves a 64 x 64 tile through LDS: 16-byte loads along the columns, 16-byte stores along the rows.
 constexpr int kTrTile = 64;
 __global__ __launch_bounds__(256) void transpose_pad_bf16_kernel(const uint16_t *__restrict__ in, uint16_t *__restrict__ out,
@@ -137,7 +145,7 @@ __global__ __launch_bounds__(256) void transpose_pad_bf16_kernel(const uint16_t 
 #pragma unroll
         for (int e = 0; e < 4; ++e)
             w[e] = (uint32_t)tile[rv + 2 * e][c] | ((uint32_t)tile[rv + 2 * e + 1][c] << 16);
-        *reinterpret_cast<uint4 *>(out + (c0 + c) * ldo + r0 + rv) = make_uint4(w[0], w[1], w[2], w[3]);
+        *reinterpret_cast<uint4 *>(out + panel_offset(c0 + c, r0 + rv, ldo)) = make_uint4(w[0], w[1], w[2], w[3]);
     }
 }
 
@@ -274,70 +282,62 @@ __global__ void lmhead_token_terms_kernel(const TokenRecord *__restrict__ record
     g_out[j] = tt.g;
 }
 
-// Gradient of a chunk's logits from the stored fp32 logits z^T [V, ldn] (vocabulary-major):
+// Gradient of a chunk's logits from the stored fp32 logits z [n, ldv] (token-major):
 //   dz[t, v] = g_t ([v == y_t] - exp(z[t, v] - lse_t)),
-// rounded once to bfloat16 and written both vocabulary-major (dzt [V, ldn], the operand of the weight gradient)
-// and token-major (dz [n, ldv], the operand of the hidden-state gradient).  A workgroup takes a tile of 64
-// vocabulary rows x 64 tokens: 16-byte loads and 8-byte stores along the tokens, then through LDS 16-byte stores
-// along the vocabulary.  Token columns n .. (next multiple of 128) of dzt are written as zeros (they pad the
-// contraction over the tokens); a token with g = 0 gives an exactly zero column.  lse, g, ysel: the chunk's
+// rounded once to bfloat16 and written both token-major (dz: n rows, K extent ldv; the operand of the hidden-state
+// gradient) and vocabulary-major (dzt: V rows, K extent ldg, at token position col0; the operand of the weight
+// gradient), both in the contraction kernel's panel layout, in which a 64 x 64 tile is 8 KiB of contiguous memory.  A workgroup takes
+// a tile of 64 tokens x 64 vocabulary entries: 16-byte loads and 8-byte stores along the vocabulary, then through
+// LDS 16-byte stores along the tokens.  Token columns n .. (next multiple of 128) of dzt are written as zeros (they
+// pad the contraction over the tokens); a token with g = 0 gives an exactly zero row.  lse, g, ysel: the chunk's
 // tokens in compacted order.
 constexpr int kDzTile = 64;
-__global__ __launch_bounds__(256) void lmhead_dz_kernel(const float *__restrict__ zt, int64_t V, DynCount count, int64_t ldn,
+__global__ __launch_bounds__(256) void lmhead_dz_kernel(const float *__restrict__ zc, int64_t V, DynCount count, int64_t ldv,
                                                         const float *__restrict__ lse, const float *__restrict__ g,
-                                                        const int32_t *__restrict__ ysel,
-                                                        uint16_t *__restrict__ dzt, uint16_t *__restrict__ dz, int64_t ldv)
+                                                        const int32_t *__restrict__ ysel, uint16_t *__restrict__ dz,
+                                                        uint16_t *__restrict__ dzt, int64_t ldg, int64_t col0)
 {
-    __shared__ __align__(16) uint16_t tile[kDzTile][kDzTile + 8];  // [token][vocabulary row], rows 144 bytes apart
+    __shared__ __align__(16) uint16_t tile[kDzTile][kDzTile + 8];  // [vocabulary entry][token], rows 144 bytes apart
     const int tid = threadIdx.x;
     const int64_t n = dyn_extent(count, 0);
     const int64_t v0 = (int64_t)blockIdx.x * kDzTile, t0 = (int64_t)blockIdx.y * kDzTile;
     if (t0 >= (n + kPadK - 1) / kPadK * kPadK) return;  // past the padded chunk (uniform)
-    const int tq = tid & 15;            // this thread's four tokens: t0 + 4 tq ..
-    const int64_t t4 = t0 + 4 * tq;
-    float neg_g[4], tl[4];
-    int32_t ty[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const bool in = t4 + i < n;
-        neg_g[i] = in ? -g[t4 + i] : 0.0f;
-        tl[i] = in ? lse[t4 + i] : 0.0f;
-        ty[i] = in ? ysel[t4 + i] : -1;
-    }
+    const int vq = (tid & 15) * 4;  // this thread's four vocabulary entries: v0 + vq ..
+    const int64_t v = v0 + vq;      // (V and vq are multiples of 4: the four are inside or outside as a whole)
 #pragma unroll
     for (int pass = 0; pass < 4; ++pass) {
-        const int vr = (tid >> 4) + 16 * pass;
-        const int64_t v = v0 + vr;
+        const int tr = (tid >> 4) + 16 * pass;
+        const int64_t t = t0 + tr;
         float d[4] = {0.0f, 0.0f, 0.0f, 0.0f};
-        if (v < V) {
-            const float4 z = *reinterpret_cast<const float4 *>(zt + v * ldn + t4);
-            const float zz[4] = {z.x, z.y, z.z, z.w};
+        if (t < n && v < V) {
+            const float neg_g = -g[t];
+            if (neg_g != 0.0f) {
+                const float tl = lse[t];
+                const int64_t y = ysel[t];
+                const float4 z = *reinterpret_cast<const float4 *>(zc + t * ldv + v);
+                const float zz[4] = {z.x, z.y, z.z, z.w};
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                if (neg_g[i] != 0.0f) {  // (also keeps whatever lies in the padding columns of z^T out)
-                    const float p = exp2_hw((zz[i] - tl[i]) * kLog2e);
-                    d[i] = neg_g[i] * p - ((int64_t)ty[i] == v ? neg_g[i] : 0.0f);
+                for (int i = 0; i < 4; ++i) {
+                    const float p = exp2_hw((zz[i] - tl) * kLog2e);
+                    d[i] = neg_g * p - (y == v + i ? neg_g : 0.0f);
                 }
             }
-            const uint32_t lo = pack_bf16x2(d[0], d[1]), hi = pack_bf16x2(d[2], d[3]);
-            *reinterpret_cast<uint2 *>(dzt + v * ldn + t4) = make_uint2(lo, hi);
-            tile[4 * tq + 0][vr] = (uint16_t)(lo & 0xFFFFu);
-            tile[4 * tq + 1][vr] = (uint16_t)(lo >> 16);
-            tile[4 * tq + 2][vr] = (uint16_t)(hi & 0xFFFFu);
-            tile[4 * tq + 3][vr] = (uint16_t)(hi >> 16);
         }
+        const uint32_t lo = pack_bf16x2(d[0], d[1]), hi = pack_bf16x2(d[2], d[3]);
+        if (t < n && v < V) *reinterpret_cast<uint2 *>(dz + panel_offset(t, v, ldv)) = make_uint2(lo, hi);
+        tile[vq + 0][tr] = (uint16_t)(lo & 0xFFFFu);
+        tile[vq + 1][tr] = (uint16_t)(lo >> 16);
+        tile[vq + 2][tr] = (uint16_t)(hi & 0xFFFFu);
+        tile[vq + 3][tr] = (uint16_t)(hi >> 16);
     }
     __syncthreads();
-    // token-major: 64 tokens x 128 bytes; thread -> token tid / 4, 16 vocabulary rows (tid % 4) 16 ..
-    const int tr = tid >> 2, vq = (tid & 3) * 16;
-    if (t0 + tr < n) {
+    // vocabulary-major: 64 entries x 128 bytes; thread -> entry tid / 4, 16 tokens (tid % 4) 16 ..
+    const int vr = tid >> 2, tq = (tid & 3) * 16;
+    if (v0 + vr < V) {
 #pragma unroll
         for (int half = 0; half < 2; ++half) {
-            const int64_t v = v0 + vq + 8 * half;
-            if (v < V) {  // V and the tile origin are multiples of 8: a vector is inside or outside as a whole
-                const uint4 w = *reinterpret_cast<const uint4 *>(&tile[tr][vq + 8 * half]);
-                *reinterpret_cast<uint4 *>(dz + (t0 + tr) * ldv + v) = w;
-            }
+            const uint4 w = *reinterpret_cast<const uint4 *>(&tile[vr][tq + 8 * half]);
+            *reinterpret_cast<uint4 *>(dzt + panel_offset(v0 + vr, col0 + t0 + tq + 8 * half, ldg)) = w;
         }
     }
 }
@@ -379,7 +379,7 @@ extern "C" int a3po_fused_lmhead_loss_fwd_bwd(const void *hidden, const void *we
     int32_t *pos = reinterpret_cast<int32_t *>(ws + lay.pos);      // token -> compacted position or -1
     int32_t *counts = reinterpret_cast<int32_t *>(ws + lay.counts);
     float2 *partial = reinterpret_cast<float2 *>(ws + lay.partial);
-    float *zt = reinterpret_cast<float *>(ws + lay.zt);
+    float *zt = reinterpret_cast<float *>(ws + lay.zt);            // the chunk's logits [chunk, ldv], fp32
     uint16_t *dzt = reinterpret_cast<uint16_t *>(ws + lay.dzt);
     uint16_t *dz = reinterpret_cast<uint16_t *>(ws + lay.dz);
     uint16_t *wt = reinterpret_cast<uint16_t *>(ws + lay.wt);
@@ -432,9 +432,9 @@ extern "C" int a3po_fused_lmhead_loss_fwd_bwd(const void *hidden, const void *we
     if (hipGetLastError() != hipSuccess) return A3PO_E_LAUNCH;
     if (launch_transpose_pad(W, wt, V, H, lay.ldv, nullptr, s) != hipSuccess) return A3PO_E_LAUNCH;
     if (launch_transpose_pad(hc, ht, T, H, lay.ldt, n_counted, s) != hipSuccess) return A3PO_E_LAUNCH;
-    if (lay.ldv > V) {  // padding columns of the token-major gradient chunk: never written below
-        const int64_t cells = lay.chunk * (lay.ldv - V);
-        hipLaunchKernelGGL(zero_columns_kernel, dim3((unsigned)((cells + 255) / 256)), dim3(256), 0, s, dz, lay.chunk,
+    if (lay.ldv > V) {  // padding of the contracted index in the token-major gradient chunk: never written below
+        const int64_t rows = (lay.chunk + 255) / 256 * 256, cells = rows * (lay.ldv - V);
+        hipLaunchKernelGGL(zero_panel_columns_kernel, dim3((unsigned)((cells + 255) / 256)), dim3(256), 0, s, dz, rows,
                            lay.ldv, V, lay.ldv);
         if (hipGetLastError() != hipSuccess) return A3PO_E_LAUNCH;
     }
@@ -448,7 +448,8 @@ extern "C" int a3po_fused_lmhead_loss_fwd_bwd(const void *hidden, const void *we
         cnt.n = n_counted;
         cnt.offset = c0;
         cnt.cap = nmax;
-        // 1. z^T [V, n] = W h_chunk^T, folded into (max, sum) per token on the way out
+        // 1. z [n, V] = h_chunk W^T (vocabulary on the row side of the tiles, stored transposed), folded into
+        //    (max, sum) per token on the way out
         GemmArgs fw = {};
         fw.A = W;
         fw.lda = H;
@@ -458,7 +459,8 @@ extern "C" int a3po_fused_lmhead_loss_fwd_bwd(const void *hidden, const void *we
         fw.N = nmax;
         fw.K = H;
         fw.C = zt;
-        fw.ldc = lay.ldn;
+        fw.ldc = lay.ldv;
+        fw.transposed = 1;
         fw.partial = partial;
         fw.partial_stride = lay.chunk;
         fw.dyn_dim = kDynN;
@@ -473,16 +475,19 @@ extern "C" int a3po_fused_lmhead_loss_fwd_bwd(const void *hidden, const void *we
                            logp_prox_out, a.ws_obj, a.ws_iw, a.ws_flags, gtok + c0);
         if (hipGetLastError() != hipSuccess) return A3PO_E_LAUNCH;
         // 3. the gradient chunk in both layouts
+        const int64_t g0 = c0 / (kLmDwGroup * lay.chunk) * (kLmDwGroup * lay.chunk);  // first token of this chunk's group
         const dim3 dz_grid((unsigned)((V + kDzTile - 1) / kDzTile), (unsigned)(kmax / kDzTile));
-        hipLaunchKernelGGL(lmhead_dz_kernel, dz_grid, dim3(256), 0, s, zt, V, cnt, lay.ldn, lse + c0, gtok + c0,
-                           ysel + c0, dzt, dz, lay.ldv);
+        hipLaunchKernelGGL(lmhead_dz_kernel, dz_grid, dim3(256), 0, s, zt, V, cnt, lay.ldv, lse + c0, gtok + c0,
+                           ysel + c0, dz, dzt, lay.ldg, c0 - g0);
         if (hipGetLastError() != hipSuccess) return A3PO_E_LAUNCH;
         // 4. dh_chunk [n, H] = dz [n, V] (W^T [H, V])^T
         GemmArgs bh = {};
         bh.A = dz;
         bh.lda = lay.ldv;
+        bh.a_panel = 1;
         bh.B = wt;
         bh.ldb = lay.ldv;
+        bh.b_panel = 1;
         bh.M = nmax;
         bh.N = H;
         bh.K = lay.ldv;
@@ -491,21 +496,33 @@ extern "C" int a3po_fused_lmhead_loss_fwd_bwd(const void *hidden, const void *we
         bh.dyn_dim = kDynM;
         bh.dyn = cnt;
         if (launch_gemm_nt(bh, kEpiStoreBf16, s) != hipSuccess) return A3PO_E_LAUNCH;
-        // 5. dW [V, H] += dz^T [V, n] (h^T [H, n])^T     (fp32 accumulator across chunks)
-        GemmArgs bw = {};
-        bw.A = dzt;
-        bw.lda = lay.ldn;
-        bw.B = ht + c0;
-        bw.ldb = lay.ldt;
-        bw.M = V;
-        bw.N = H;
-        bw.K = kmax;
-        bw.C = dwacc;
-        bw.ldc = H;
-        bw.accumulate = c0 > 0;
-        bw.dyn_dim = kDynK;
-        bw.dyn = cnt;
-        if (launch_gemm_nt(bw, kEpiAccumF32, s) != hipSuccess) return A3PO_E_LAUNCH;
+        // 5. at the end of a group of chunks: dW [V, H] += (dz^T [V, group] (h^T [H, group])^T): h^T on the row side
+        //    of the tiles, stored transposed; fp32 accumulator across groups
+        const bool group_ends = c0 + lay.chunk >= T || (c0 + lay.chunk) % (kLmDwGroup * lay.chunk) == 0;
+        if (group_ends) {
+            const int64_t gmax = c0 + nmax - g0;  // tokens of the group, at most
+            DynCount gcnt;
+            gcnt.n = n_counted;
+            gcnt.offset = g0;
+            gcnt.cap = gmax;
+            GemmArgs bw = {};
+            bw.A = ht + panel_offset(0, g0, lay.ldt);
+            bw.lda = lay.ldt;
+            bw.a_panel = 1;
+            bw.B = dzt;
+            bw.ldb = lay.ldg;
+            bw.b_panel = 1;
+            bw.M = H;
+            bw.N = V;
+            bw.K = (gmax + kPadK - 1) / kPadK * kPadK;
+            bw.C = dwacc;
+            bw.ldc = H;
+            bw.transposed = 1;
+            bw.accumulate = g0 > 0;
+            bw.dyn_dim = kDynK;
+            bw.dyn = gcnt;
+            if (launch_gemm_nt(bw, kEpiAccumF32, s) != hipSuccess) return A3PO_E_LAUNCH;
+        }
     }
     if (launch_loss_finish(a, s) != hipSuccess) return A3PO_E_LAUNCH;
     hipLaunchKernelGGL(scatter_rows_kernel, dim3((unsigned)((T + 3) / 4)), dim3(256), 0, s, dhc,
