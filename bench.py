@@ -213,6 +213,31 @@ def secondary_kernels(a3po, torch, w, b, adv, dz, ws, log, reps=10, shards=8):
         nbytes = row * (2 * live + (T - live))
         res["shard_backward"] = {"shards": shards, "ms": ms, "gbs": nbytes / ms / 1e6,
                                  "frac": nbytes / ms / 1e6 / HBM_PEAK_GBS, "live_rows": live}
+    # fp32 logits at the full vocabulary: a row (594 KiB) no longer fits the registers; 16,384 rows of the batch
+    # (every (T / 16,384)-th) widened to fp32, every row counted; bytes as for the row kernel (read + write per
+    # live row)
+    if w.elem_bytes == 2 and T >= 16384:
+        n32 = 16384
+        pick = slice(0, T, T // n32)
+        z32 = b["z"][pick].float()
+        dz32 = torch.empty_like(z32)
+        tok32 = {k: b[k][pick].contiguous() for k in ("chosen", "lb", "versions")}
+        adv32 = adv[pick].contiguous()
+        ones32 = torch.ones(n32, dtype=b["mask"].dtype, device="cuda")
+        ws32 = torch.empty(a3po.workspace_bytes(n32, V), dtype=torch.uint8, device="cuda")
+        last32 = {}
+
+        def f32_step():
+            last32.update(a3po.loss_fwd_bwd(z32, tok32["chosen"], tok32["lb"], tok32["versions"], b["cur"], adv32,
+                                            ones32, w.clip_eps, V=V, dlogits=dz32, workspace=ws32))
+
+        ms = timed(f32_step)
+        st = a3po.stats_to_dict(last32["stats"])
+        live = int((adv32 != 0).sum().item()) - st["n_clipped"]
+        nbytes = V * 4 * (2 * live + (n32 - live))
+        res["fp32_full_vocabulary"] = {"rows": n32, "ms": ms, "gbs": nbytes / ms / 1e6,
+                                       "frac": nbytes / ms / 1e6 / HBM_PEAK_GBS, "live_rows": live}
+        del z32, dz32
     # the same batch as 4 gradient updates of micro-batches within the paper's 10,240-token budget (Section 4.1):
     # plan on the host, one token count per mini-batch kept on the device, one loss call per micro-batch
     import numpy as np

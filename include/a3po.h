@@ -16,16 +16,16 @@
  *    a3po_stats (chosen id outside [0,V) => the token is treated as masked; negative
  *    staleness => alpha = 1).
  *  - No state is kept between calls: they are re-entrant and may be issued from several host threads
- *    on different streams, as long as they do not share output buffers or a workspace.  (Two one-time
- *    set-ups exist and are thread-safe: the LM-head kernels' LDS limit, and the address of the array that
+ *    on different streams, as long as they do not share output buffers or a workspace.  (The one-time
+ *    set-ups that exist are thread-safe: the LDS limit of the kernels that use more than 64 KiB, and the address of the array that
  *    a3po_loss_fwd_bwd_noalloc uses in place of a workspace.)
  *  - Logits are row-major [T, V] with a row stride of `ld` elements (ld >= V), float32
  *    or bfloat16.  Row t pairs with chosen[t]; any next-token shift is the caller's.
  *    Base pointers of logits / dlogits must be aligned to their element size.  Rows whose base
- *    and byte stride are multiples of 16 take vectorised kernels: a single pass (each row read once
- *    and written once) when the row fits on chip (V <= 163,840 bfloat16 / 81,920 float32), three
- *    streaming passes (read, read, write) when it does not.  Everything else takes slower element-wise
- *    multi-pass kernels.  Results are identical up to rounding order.
+ *    and byte stride are multiples of 16 take the vectorised kernels: each row is read once and written
+ *    once when it fits the registers (V <= 163,840 bfloat16 / 81,920 float32); a longer row stays on chip as
+ *    far as registers and LDS hold it (448 KiB) and only its remainder is read a second time.  Everything
+ *    else takes slower element-wise multi-pass kernels.  Results are identical up to rounding order.
  */
 #ifndef A3PO_H
 #define A3PO_H

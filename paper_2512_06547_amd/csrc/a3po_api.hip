@@ -9,9 +9,9 @@
 using namespace a3po;
 
 // Workspace of the entry point that allocates nothing (a3po_loss_fwd_bwd_noalloc): the loss workspace of
-// A3PO_NOALLOC_MAX_TOKENS tokens (per-token records, objective, weights, flags, three-pass partials, per-workgroup
-// partials, each rounded up to 256 bytes).
-constexpr size_t kStaticWsBytes = A3PO_NOALLOC_MAX_TOKENS * (size_t)(16 + 4 + 4 + 1 + 4 + 16) + 8 * 256 + kLossScratchBytes;
+// A3PO_NOALLOC_MAX_TOKENS tokens (per-token records, objective, weights, flags, per-workgroup partials, each rounded up
+// to 256 bytes).
+constexpr size_t kStaticWsBytes = A3PO_NOALLOC_MAX_TOKENS * (size_t)(16 + 4 + 4 + 1) + 6 * 256 + kLossScratchBytes;
 static __device__ __align__(256) unsigned char scratch[kStaticWsBytes];
 
 namespace {

@@ -40,15 +40,12 @@ struct LossArgs {
     float *ws_obj;
     float *ws_iw;
     uint8_t *ws_flags;
-    float *ws_lse;                  // [T], three-pass path only (rows too long for the registers)
-    a3po_shard_partial *ws_partial; // [T], three-pass path only
     void *ws_scratch;               // kLossScratchBytes: per-workgroup partials of the prep and finish kernels
 };
 
-// Workspace of the loss path: header | TokenRecord[T] (16 bytes each) | obj[T] | iw[T] | flags[T] | lse[T] | partial[T] |
-// scratch
+// Workspace of the loss path: header | TokenRecord[T] (16 bytes each) | obj[T] | iw[T] | flags[T] | scratch
 struct LossWsLayout {
-    size_t records, obj, iw, flags, lse, partial, scratch, total;
+    size_t records, obj, iw, flags, scratch, total;
 };
 
 // The O(T) kernels before and after the row kernel run on up to kTokMaxBlocks workgroups of kTokBlockTokens tokens
@@ -65,9 +62,7 @@ inline LossWsLayout loss_ws_layout(int64_t T)
     l.obj = l.records + up(t * 16);
     l.iw = l.obj + up(t * sizeof(float));
     l.flags = l.iw + up(t * sizeof(float));
-    l.lse = l.flags + up(t);
-    l.partial = l.lse + up(t * sizeof(float));
-    l.scratch = l.partial + up(t * sizeof(a3po_shard_partial));
+    l.scratch = l.flags + up(t);
     l.total = l.scratch + kLossScratchBytes;
     return l;
 }
@@ -82,8 +77,6 @@ inline void carve_loss_ws(LossArgs &a, void *workspace, int64_t T)
     a.ws_obj = reinterpret_cast<float *>(ws + lay.obj);
     a.ws_iw = reinterpret_cast<float *>(ws + lay.iw);
     a.ws_flags = reinterpret_cast<uint8_t *>(ws + lay.flags);
-    a.ws_lse = reinterpret_cast<float *>(ws + lay.lse);
-    a.ws_partial = reinterpret_cast<a3po_shard_partial *>(ws + lay.partial);
     a.ws_scratch = ws + lay.scratch;
 }
 
@@ -112,7 +105,6 @@ hipError_t launch_shard_partials(const void *z, int dt, int64_t T, int64_t Vs, i
 hipError_t launch_shard_combine(const a3po_shard_partial *parts, int32_t P, int64_t T, const int32_t *chosen, int64_t V,
                                 float *logp, float *lse, float *ent, const TokenRecord *records, hipStream_t s);
 // the loss rows in three streaming passes (partials, merge, gradient bursts) for rows that do not fit on chip
-hipError_t launch_loss_rows_three_pass(const LossArgs &a, hipStream_t s);
 // The row kernel and the gradient bursts hand out work through a 32-bit counter: item index = grid size + number
 // of claims so far, and every workgroup makes one claim past the end.  Item counts above this bound are refused
 // by the entry points (rows for the register-resident kernel, bursts for the streaming one).

@@ -10,6 +10,8 @@
 // All loads of a row are issued before the first is consumed; the online (max, sum)
 // update of each vector then runs while later vectors are still in flight, and the
 // gradient of each vector is stored while the next is being computed.
+#include <mutex>
+
 #include "a3po_common.h"
 #include "a3po_launch.h"
 
@@ -301,6 +303,287 @@ __global__ __launch_bounds__(kRowThreads) void loss_rows_kernel(
 }
 
 // ---------------------------------------------------------------------------------------
+// Fused forward+backward for rows that do not fit the registers (more than kMaxVec sweeps: fp32 logits at the
+// full vocabulary, bfloat16 beyond 163,840 columns).  Same workgroup per row, same queue, same arithmetic; the
+// row is cut into three parts by sweep index:
+//   sweeps 0 .. kLongReg-1            in vector registers, as in the kernel above;
+//   the next up to kLongLds sweeps    in LDS, brought there by direct global -> LDS loads (no registers, no LDS
+//                                     write instructions; lane l of a wavefront lands at base + 16 l, so a thread
+//                                     reads back exactly the 16 bytes its own load wrote and no barrier is needed);
+//   the rest ("tail")                 streamed: read once for the forward reduction, last of all, and read again
+//                                     first thing in the backward pass, latest sweeps first, while the compute
+//                                     unit's share of the L2 and of the memory-side cache still holds most of it.
+// Registers plus LDS hold 28 sweeps = 448 KiB, three quarters of an fp32 row of 151,936 (594 KiB): the row crosses
+// HBM about 2.25 times instead of the 3 of separate forward and backward passes.  The first read of the tail
+// is an ordinary load (it is wanted again soon); everything else is non-temporal.
+constexpr int kLongReg = 19;     // sweeps in registers
+constexpr int kLongRegEnt = 15;  // the same with the entropy, whose running sum and temporaries need the room
+constexpr int kLongLds = 9;
+constexpr int kLongTailUnroll = 4;  // tail vectors in flight per thread
+constexpr int kLongStashBytes = kLongLds * (int)kSweepBytes;
+constexpr int kLongLdsBytes = kLongStashBytes + (6 * kRowWaves + 2) * (int)sizeof(float);
+
+typedef __attribute__((address_space(3))) void *rows_lds_ptr_t;
+
+__device__ __forceinline__ uint4 cached_load(const char *p) { return *reinterpret_cast<const uint4 *>(p); }
+
+template <typename DT, bool ENT>
+__global__ __launch_bounds__(kRowThreads) void loss_rows_long_kernel(
+    const void *z, void *dz, int64_t T, int64_t V, int64_t ld, const TokenRecord *__restrict__ records,
+    int32_t current_version, float clip_eps, int prox_mode, const WsHeader *__restrict__ hdr,
+    unsigned int *row_queue, RowOutputs out)
+{
+    constexpr int EPV = DT::kPerVec;
+    constexpr int NREG = ENT ? kLongRegEnt : kLongReg;
+    extern __shared__ __align__(16) char smem[];
+    float *red_m = reinterpret_cast<float *>(smem + kLongStashBytes);  // [2][kRowWaves]
+    float *red_s = red_m + 2 * kRowWaves;
+    float *ent_part = red_s + 2 * kRowWaves;                           // [2][kRowWaves]
+    unsigned int *next_row = reinterpret_cast<unsigned int *>(ent_part + 2 * kRowWaves);  // [2]
+
+    const int tid = threadIdx.x;
+    const int lane = tid & (kWave - 1), wave = tid / kWave;
+    const int wave_s = __builtin_amdgcn_readfirstlane(wave);
+    const uint32_t voff = (uint32_t)tid * 16u;
+    const int nfull = (int)(V / EPV);
+    const int rem = (int)(V % EPV);
+    const int nvec = nfull + (rem != 0);
+    const int nsweep = (nvec + kRowThreads - 1) / kRowThreads;                    // > kMaxVec
+    const int lds_sweeps = min(kLongLds, nsweep - NREG);                      // >= 2
+    const int tail0 = NREG + lds_sweeps;                                      // first streamed sweep
+    const int tail_batches = (nsweep - tail0 + kLongTailUnroll - 1) / kLongTailUnroll;
+    const float inv_n = hdr->inv_n;
+    const size_t row_bytes = (size_t)ld * DT::kBytes;
+    char *my_stash = smem + voff;  // + j * kSweepBytes: this thread's vector of LDS sweep j
+    int parity = 0;
+    // entropy of the previous counted row, finished after this row's barrier (as in the kernel above)
+    int64_t pend_row = -1;
+    float pend_lse = 0.0f;
+    int pend_par = 0;
+    auto finish_pending_entropy = [&]() {
+        if (pend_row >= 0 && tid == 0) {
+            float sum = 0.0f;
+#pragma unroll
+            for (int w = 0; w < kRowWaves; ++w) sum += ent_part[pend_par * kRowWaves + w];
+            out.ent[pend_row] = pend_lse - sum;
+        }
+        pend_row = -1;
+    };
+
+    int64_t row = blockIdx.x;
+    TokenRecord nxt = {-1, 0, 0.0f, 0.0f};
+    if (row < T) nxt = records[row];
+
+    while (row < T) {
+        const TokenRecord cur = nxt;
+        const int32_t y = cur.y;
+        const bool live = y >= 0;
+        unsigned int claimed = 0;
+        if (tid == 0) claimed = atomicAdd(row_queue, 1u);
+        __builtin_amdgcn_sched_barrier(0);
+        char *out_row = reinterpret_cast<char *>(dz) + (size_t)row * row_bytes;
+        const char *in_row = reinterpret_cast<const char *>(z) + (size_t)row * row_bytes;
+        const int row_par = parity;
+
+        uint4 v[NREG];
+        float g = 0.0f, lse = 0.0f, zy = 0.0f, row_max = 0.0f, nls2 = 0.0f;
+        int64_t next = T;
+        if (live) {
+            // a copy of the thread index the compiler cannot see through: the addresses of the direct loads are
+            // then computed where they are used (two instructions each) instead of being kept, and spilled,
+            // across the whole row loop
+            int tid_r = tid;
+            asm volatile("" : "+v"(tid_r));
+            const uint32_t zy_bits = load_raw<DT>(in_row, y);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int k = 0; k < NREG; ++k) {
+                v[k] = stream_load(in_row + (size_t)k * kSweepBytes + voff);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            // LDS sweeps; a lane past the row's end fetches the row's last vector instead (its data is never used)
+#pragma unroll
+            for (int j = 0; j < kLongLds; ++j) {
+                if (j < lds_sweeps) {
+                    const uint32_t idx = (uint32_t)min((NREG + j) * kRowThreads + tid_r, nvec - 1);
+                    __builtin_amdgcn_global_load_lds(reinterpret_cast<const u32x4_t *>(in_row + (size_t)(idx * 16u)),
+                                                     (rows_lds_ptr_t)(smem + j * (int)kSweepBytes + wave_s * 1024), 16, 0, 0);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+
+            MaxSum acc = {kNegFloor, 0.0f};
+            if (tid == 0) next_row[parity] = claimed;
+#pragma unroll
+            for (int k = 0; k < NREG; ++k) {
+                float f[EPV];
+                unpack<DT>(v[k], f);
+                fold<EPV>(acc, f);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            // the direct loads are invisible to the compiler's dependency tracking: wait for them by hand
+            __builtin_amdgcn_s_waitcnt(0x0070 | (15 << 8));  // vmcnt(0), LDS count untouched
+            __builtin_amdgcn_sched_barrier(0);
+            for (int j = 0; j < lds_sweeps; ++j) {
+                const int idx = (NREG + j) * kRowThreads + tid;
+                uint4 t = *reinterpret_cast<const uint4 *>(my_stash + j * (int)kSweepBytes);
+                if (idx >= nvec) {
+                    t = neg_inf_vec<DT>();
+                } else if (rem != 0 && idx == nfull) {  // the ragged tail vector: -inf past the row's end, once
+                    mask_tail<DT>(t, rem);
+                    *reinterpret_cast<uint4 *>(my_stash + j * (int)kSweepBytes) = t;
+                }
+                float f[EPV];
+                unpack<DT>(t, f);
+                fold<EPV>(acc, f);
+            }
+            // tail, first reading
+            for (int b = 0; b < tail_batches; ++b) {
+                uint4 t[kLongTailUnroll];
+#pragma unroll
+                for (int u = 0; u < kLongTailUnroll; ++u) {
+                    const int idx = (tail0 + b * kLongTailUnroll + u) * kRowThreads + tid;
+                    t[u] = neg_inf_vec<DT>();
+                    if (idx < nvec) t[u] = cached_load(in_row + (size_t)idx * 16);
+                }
+#pragma unroll
+                for (int u = 0; u < kLongTailUnroll; ++u) {
+                    const int idx = (tail0 + b * kLongTailUnroll + u) * kRowThreads + tid;
+                    if (rem != 0 && idx == nfull) mask_tail<DT>(t[u], rem);
+                    float f[EPV];
+                    unpack<DT>(t[u], f);
+                    fold<EPV>(acc, f);
+                }
+            }
+            zy = raw_to_float<DT>(zy_bits);
+            acc = wave_reduce(acc);
+            if (lane == 0) {
+                red_m[parity * kRowWaves + wave] = acc.m;
+                red_s[parity * kRowWaves + wave] = acc.s;
+            }
+            __syncthreads();
+            MaxSum tot = {red_m[parity * kRowWaves], red_s[parity * kRowWaves]};
+#pragma unroll
+            for (int w = 1; w < kRowWaves; ++w)
+                tot = combine(tot, MaxSum{red_m[parity * kRowWaves + w], red_s[parity * kRowWaves + w]});
+            const int64_t upcoming = (int64_t)gridDim.x + (int64_t)__builtin_amdgcn_readfirstlane(next_row[parity]);
+            parity ^= 1;
+            if (upcoming < T) nxt = records[upcoming];
+            if constexpr (ENT) finish_pending_entropy();
+
+            row_max = tot.m;
+            const float log_s = logf(tot.s);
+            nls2 = -log_s * kLog2e;
+            lse = tot.m + log_s;
+            const float lt = (zy - tot.m) - log_s;
+            const TokenTerms tt =
+                token_terms(lt, cur.lb, cur.ver, current_version, cur.A, clip_eps, inv_n, prox_mode);
+            g = tt.g;
+            if (tid == 0) {
+                out.logp[row] = lt;
+                if (out.prox) out.prox[row] = tt.lp;
+                out.obj[row] = tt.obj;
+                out.iw[row] = tt.iw;
+                out.flags[row] = (uint8_t)(kFlagCounted | (tt.clipped ? kFlagClipped : 0) |
+                                           (tt.negative_staleness ? kFlagNegStale : 0));
+            }
+            next = upcoming;
+        } else {
+            if (tid == 0) {
+                next_row[parity] = claimed;
+                out.logp[row] = 0.0f;
+                if (out.prox) out.prox[row] = 0.0f;
+                if constexpr (ENT) out.ent[row] = 0.0f;
+                out.obj[row] = 0.0f;
+                out.iw[row] = 0.0f;
+                out.flags[row] = 0;
+            }
+            __syncthreads();
+            next = (int64_t)gridDim.x + (int64_t)__builtin_amdgcn_readfirstlane(next_row[parity]);
+            parity ^= 1;
+            if (next < T) nxt = records[next];
+            if constexpr (ENT) finish_pending_entropy();
+        }
+
+        const bool want_p = ENT ? live : g != 0.0f;  // the entropy needs every p_j of a counted row
+        if (!want_p) {
+            const uint4 zero = make_uint4(0u, 0u, 0u, 0u);
+            for (int k = 0; k < nsweep; ++k) {
+                const int idx = k * kRowThreads + tid;
+                if (idx < nfull) {
+                    stream_store(out_row + (size_t)idx * 16, zero);
+                } else if (idx == nfull) {
+                    for (int e = 0; e < rem; ++e) store_elem<DT>(out_row, (int64_t)nfull * EPV + e, 0.0f);
+                }
+            }
+            row = next;
+            continue;
+        }
+
+        const float neg_g = g != 0.0f ? -g : 0.0f;  // +0 rows when there is no gradient, as the zero path stores
+        float pz = 0.0f;
+        auto emit = [&](uint4 t, int idx) {  // gradient of one vector; idx < nvec
+            float f[EPV];
+            unpack<DT>(t, f);
+            backward_vec<EPV, ENT>(f, neg_g, row_max, nls2, pz);
+            if (idx < nfull) {
+                stream_store(out_row + (size_t)idx * 16, pack<DT>(f));
+            } else {
+#pragma unroll
+                for (int e = 0; e < EPV; ++e)
+                    if (e < rem) store_elem<DT>(out_row, (int64_t)nfull * EPV + e, f[e]);
+            }
+        };
+        // tail, second reading: latest sweeps first
+        for (int b = tail_batches - 1; b >= 0; --b) {
+            uint4 t[kLongTailUnroll];
+#pragma unroll
+            for (int u = 0; u < kLongTailUnroll; ++u) {
+                const int idx = (tail0 + b * kLongTailUnroll + u) * kRowThreads + tid;
+                t[u] = neg_inf_vec<DT>();
+                if (idx < nvec) t[u] = stream_load(in_row + (size_t)idx * 16);
+            }
+#pragma unroll
+            for (int u = 0; u < kLongTailUnroll; ++u) {
+                const int idx = (tail0 + b * kLongTailUnroll + u) * kRowThreads + tid;
+                if (idx < nvec) {
+                    if (rem != 0 && idx == nfull) mask_tail<DT>(t[u], rem);
+                    emit(t[u], idx);
+                }
+            }
+        }
+#pragma unroll
+        for (int k = 0; k < NREG; ++k) {
+            float f[EPV];
+            unpack<DT>(v[k], f);
+            backward_vec<EPV, ENT>(f, neg_g, row_max, nls2, pz);
+            stream_store(out_row + (size_t)k * kSweepBytes + voff, pack<DT>(f));
+            if constexpr (ENT) __builtin_amdgcn_sched_barrier(0);  // one vector's temporaries at a time
+        }
+        for (int j = 0; j < lds_sweeps; ++j) {
+            const int idx = (NREG + j) * kRowThreads + tid;
+            if (idx < nvec) emit(*reinterpret_cast<const uint4 *>(my_stash + j * (int)kSweepBytes), idx);
+        }
+        // the chosen column gets +g from the thread that stored its vector (same thread, same address: program order)
+        if (g != 0.0f && tid == ((y / EPV) & (kRowThreads - 1)))
+            store_elem<DT>(out_row, y, neg_g * exp2_hw(fmaf(zy - row_max, kLog2e, nls2)) + g);
+        if constexpr (ENT) {
+#pragma unroll
+            for (int off = kWave / 2; off > 0; off >>= 1) pz += __shfl_xor(pz, off, kWave);
+            if (lane == 0) ent_part[row_par * kRowWaves + wave] = pz;
+            pend_row = row;
+            pend_lse = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(lse)));
+            pend_par = row_par;
+        }
+        row = next;
+    }
+    if constexpr (ENT) {
+        __syncthreads();
+        finish_pending_entropy();
+    }
+}
+
+// ---------------------------------------------------------------------------------------
 // Multi-pass fallback for rows the fused kernel cannot hold (unaligned stride, very large
 // V): element-wise accesses, three reads of the row (max, sum, gradient).  Same results up
 // to summation order.  Any blockDim.x that is a multiple of 64 up to 1024.
@@ -471,8 +754,30 @@ static hipError_t launch_loss_rows_t(const LossArgs &a, hipStream_t s)
     const int cus = device_cu_count();
     const unsigned grid = (unsigned)(a.T < (int64_t)cus ? a.T : (int64_t)cus);
     if (!rows_fit_on_chip(a.dt, a.V, a.ld, a.z, a.dz)) {
-        // aligned but too long for the registers: three vectorised streaming passes
-        if (aligned16(a.z) && aligned16(a.dz) && (a.ld * DT::kBytes) % 16 == 0) return launch_loss_rows_three_pass(a, s);
+        if (aligned16(a.z) && aligned16(a.dz) && (a.ld * DT::kBytes) % 16 == 0) {
+            // aligned but too long for the registers: registers + LDS + a streamed tail
+            const RowOutputs lout = {a.logp_out, a.prox_out, a.ws_obj, a.ws_iw, a.ent_out, a.ws_flags};
+            const WsHeader *lhdr = reinterpret_cast<const WsHeader *>(a.ws_header);
+            static std::once_flag once;
+            static hipError_t attr_err = hipSuccess;
+            std::call_once(once, [] {
+                attr_err = hipFuncSetAttribute(reinterpret_cast<const void *>(&loss_rows_long_kernel<DT, false>),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, kLongLdsBytes);
+                if (attr_err == hipSuccess)
+                    attr_err = hipFuncSetAttribute(reinterpret_cast<const void *>(&loss_rows_long_kernel<DT, true>),
+                                                   hipFuncAttributeMaxDynamicSharedMemorySize, kLongLdsBytes);
+            });
+            if (attr_err != hipSuccess) return attr_err;
+            if (a.ent_out)
+                hipLaunchKernelGGL((loss_rows_long_kernel<DT, true>), dim3(grid), dim3(kRowThreads), kLongLdsBytes, s,
+                                   a.z, a.dz, a.T, a.V, a.ld, a.ws_records, a.current_version, a.clip_eps, a.prox_mode,
+                                   lhdr, row_queue_of(a.ws_header), lout);
+            else
+                hipLaunchKernelGGL((loss_rows_long_kernel<DT, false>), dim3(grid), dim3(kRowThreads), kLongLdsBytes, s,
+                                   a.z, a.dz, a.T, a.V, a.ld, a.ws_records, a.current_version, a.clip_eps, a.prox_mode,
+                                   lhdr, row_queue_of(a.ws_header), lout);
+            return hipGetLastError();
+        }
         hipLaunchKernelGGL((loss_rows_generic_kernel<DT>), dim3(grid * 2 > a.T ? (unsigned)a.T : grid * 2),
                            dim3(kRowThreads), 0, s, a);
         return hipGetLastError();

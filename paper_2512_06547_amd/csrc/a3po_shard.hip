@@ -560,16 +560,4 @@ hipError_t launch_shard_bwd_rows(const LossArgs &a, int64_t v0, const float *log
     return hipGetLastError();
 }
 
-// Rows too long to stay in registers (but 16-byte aligned): the whole vocabulary as one shard - forward
-// partials of the counted rows, merge into log pi / lse / entropy, gradient in bursts.  Three passes over
-// a counted row (read, read, write) instead of two.
-hipError_t launch_loss_rows_three_pass(const LossArgs &a, hipStream_t s)
-{
-    hipError_t e = launch_shard_partials(a.z, a.dt, a.T, a.V, a.ld, a.chosen, 0, a.ws_partial, a.ws_records, s);
-    if (e != hipSuccess) return e;
-    e = launch_shard_combine(a.ws_partial, 1, a.T, a.chosen, a.V, a.logp_out, a.ws_lse, a.ent_out, a.ws_records, s);
-    if (e != hipSuccess) return e;
-    return launch_shard_bwd_rows(a, 0, a.logp_out, a.ws_lse, s);
-}
-
 }  // namespace a3po

@@ -188,7 +188,7 @@ def test_ragged_vocabularies_and_strides(a3po, dtype, V, pad):
     # covers: single partial sweep, exact sweep multiples, ragged tail vectors, padded strides
     # (padding columns hold a 1e30 sentinel and must be neither read nor written), strides
     # whose byte size is not a multiple of 16 (element-wise multi-pass kernel), and rows too long for the
-    # registers (100,000 float32 / 170,000 bfloat16: three vectorised passes; 100,001: element-wise).
+    # registers (100,000 float32 / 170,000 bfloat16: registers plus LDS; 100,001: element-wise).
     w = synth.WORKLOADS["tiny"].scaled(V=V, dtype=dtype, S=4, L=6, len_lo=3, len_hi=6, sigma=3.0,
                                        boost=6.0, boost_prob=0.5, noise_std=0.15, stale_max=6)
     c = make_case(w, ld=V + pad)
@@ -196,6 +196,33 @@ def test_ragged_vocabularies_and_strides(a3po, dtype, V, pad):
     check_against_oracle(a3po, c, out)
     if pad:
         assert (out["dlogits"][:, V:].float() == 7.0).all(), "padding columns were written"
+
+
+@pytest.mark.parametrize("dtype,V,pad", [
+    ("f32", 151936, 0),    # the full vocabulary in fp32: 19 sweeps in registers, 9 in LDS, 9.1 streamed twice
+    ("f32", 114688, 0),    # exactly 28 sweeps: nothing streamed, the last LDS sweep full
+    ("f32", 114690, 2),    # the ragged vector is the first one of the streamed part
+    ("f32", 130001, 3),    # ragged end inside the streamed part, two batches
+    ("f32", 86017, 3),     # 21 sweeps and one ragged vector, which lives in LDS
+    ("f32", 500000, 0),    # 122 sweeps: 24 batches of streamed vectors
+    ("bf16", 163848, 0),   # one vector more than the register-resident kernel holds
+    ("bf16", 256000, 0),   # 31.25 sweeps
+    ("bf16", 300005, 3),   # 36.6 sweeps, ragged end in the last streamed batch
+])
+def test_rows_beyond_the_registers(a3po, dtype, V, pad):
+    # 16-byte aligned rows of more than 20 sweeps of 1024 vectors: kept in registers and LDS as far as they fit, the
+    # rest read twice; every element against the oracle, padding untouched, and the in-place form bit-identical
+    w = synth.WORKLOADS["tiny"].scaled(V=V, dtype=dtype, S=4, L=6, len_lo=3, len_hi=6, sigma=3.0,
+                                       boost=6.0, boost_prob=0.5, noise_std=0.15, stale_max=6)
+    c = make_case(w, ld=V + pad)
+    out = run_gpu(a3po, c, dz_fill=7.0)
+    check_against_oracle(a3po, c, out)
+    if pad:
+        assert (out["dlogits"][:, V:].float() == 7.0).all(), "padding columns were written"
+    inp = run_gpu(a3po, c, inplace=True)
+    assert torch.equal(out["dlogits"][:, :V].contiguous().view(torch.uint8),
+                       inp["dlogits"][:, :V].contiguous().view(torch.uint8))
+    assert torch.equal(out["logp"], inp["logp"]) and torch.equal(out["loss"], inp["loss"])
 
 
 @pytest.mark.parametrize("dtype,V", [("f32", 32000), ("bf16", 151936), ("bf16", 4099), ("f32", 1001)])

@@ -1,7 +1,7 @@
 """Seeded random shapes through the whole path and its variants, against the CPU oracle with the bars of
 test_gpu_parity.py: vocabularies from 1 to 170,000 entries around every kernel boundary (register-resident,
-three-pass, element-wise), padded strides, in-place gradients, entropy, the two baseline objectives, and
-vocabulary shards cut at random columns (views of the matrix or contiguous copies).  Every case prints its
+registers plus LDS plus a streamed remainder, element-wise), padded strides, in-place gradients, entropy, the two
+baseline objectives, and vocabulary shards cut at random columns (views of the matrix or contiguous copies).  Every case prints its
 parameters first."""
 import numpy as np
 import pytest

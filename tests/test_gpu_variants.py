@@ -49,7 +49,9 @@ ENTROPY_CASES = [
     ("bf16", 131072, 0),    # exactly 16 full sweeps
     ("bf16", 4099, 5),      # stride not a multiple of 16 bytes: multi-pass kernel
     ("f32", 7, 1),
-    ("f32", 100000, 0),     # too long for the registers: three-pass path (entropy from the forward partials)
+    ("f32", 100000, 0),     # too long for the registers: registers plus LDS
+    ("f32", 151936, 0),     # registers, LDS and a remainder that is read twice
+    ("bf16", 300005, 3),    # the same in bfloat16 with a ragged end
 ]
 
 
