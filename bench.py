@@ -215,7 +215,7 @@ def secondary_kernels(a3po, torch, w, b, adv, dz, ws, log, reps=10, shards=8):
                                  "frac": nbytes / ms / 1e6 / HBM_PEAK_GBS, "live_rows": live}
     # fp32 logits at the full vocabulary: a row (594 KiB) no longer fits the registers; 16,384 rows of the batch
     # (every (T / 16,384)-th) widened to fp32, every row counted; bytes as for the row kernel (read + write per
-    # live row)
+    # counted row)
     if w.elem_bytes == 2 and T >= 16384:
         n32 = 16384
         pick = slice(0, T, T // n32)
@@ -232,11 +232,9 @@ def secondary_kernels(a3po, torch, w, b, adv, dz, ws, log, reps=10, shards=8):
                                             ones32, w.clip_eps, V=V, dlogits=dz32, workspace=ws32))
 
         ms = timed(f32_step)
-        st = a3po.stats_to_dict(last32["stats"])
-        live = int((adv32 != 0).sum().item()) - st["n_clipped"]
-        nbytes = V * 4 * (2 * live + (n32 - live))
+        nbytes = V * 4 * 2 * n32  # every row is counted: read once (its log-prob is an output) and written once
         res["fp32_full_vocabulary"] = {"rows": n32, "ms": ms, "gbs": nbytes / ms / 1e6,
-                                       "frac": nbytes / ms / 1e6 / HBM_PEAK_GBS, "live_rows": live}
+                                       "frac": nbytes / ms / 1e6 / HBM_PEAK_GBS}
         del z32, dz32
     # the same batch as 4 gradient updates of micro-batches within the paper's 10,240-token budget (Section 4.1):
     # plan on the host, one token count per mini-batch kept on the device, one loss call per micro-batch

@@ -311,11 +311,11 @@ __global__ __launch_bounds__(kRowThreads) void loss_rows_kernel(
 //                                     write instructions; lane l of a wavefront lands at base + 16 l, so a thread
 //                                     reads back exactly the 16 bytes its own load wrote and no barrier is needed);
 //   the rest ("tail")                 streamed: read once for the forward reduction, last of all, and read again
-//                                     first thing in the backward pass, latest sweeps first, while the compute
-//                                     unit's share of the L2 and of the memory-side cache still holds most of it.
-// Registers plus LDS hold 28 sweeps = 448 KiB, three quarters of an fp32 row of 151,936 (594 KiB): the row crosses
-// HBM about 2.25 times instead of the 3 of separate forward and backward passes.  The first read of the tail
-// is an ordinary load (it is wanted again soon); everything else is non-temporal.
+//                                     at the end of the backward pass, latest sweeps first.
+// Registers plus LDS hold 28 sweeps = 448 KiB, three quarters of an fp32 row of 151,936 (594 KiB): at most 2.25
+// crossings of HBM per row instead of the 3 of separate forward and backward passes.  The first read of the tail
+// is an ordinary load and most of the second reading is then served by the caches (with a non-temporal first read
+// the kernel is 10 % slower); everything else is non-temporal.
 constexpr int kLongReg = 19;     // sweeps in registers
 constexpr int kLongRegEnt = 15;  // the same with the entropy, whose running sum and temporaries need the room
 constexpr int kLongLds = 9;
@@ -534,6 +534,18 @@ __global__ __launch_bounds__(kRowThreads) void loss_rows_long_kernel(
                     if (e < rem) store_elem<DT>(out_row, (int64_t)nfull * EPV + e, f[e]);
             }
         };
+#pragma unroll
+        for (int k = 0; k < NREG; ++k) {
+            float f[EPV];
+            unpack<DT>(v[k], f);
+            backward_vec<EPV, ENT>(f, neg_g, row_max, nls2, pz);
+            stream_store(out_row + (size_t)k * kSweepBytes + voff, pack<DT>(f));
+            if constexpr (ENT) __builtin_amdgcn_sched_barrier(0);  // one vector's temporaries at a time
+        }
+        for (int j = 0; j < lds_sweeps; ++j) {
+            const int idx = (NREG + j) * kRowThreads + tid;
+            if (idx < nvec) emit(*reinterpret_cast<const uint4 *>(my_stash + j * (int)kSweepBytes), idx);
+        }
         // tail, second reading: latest sweeps first
         for (int b = tail_batches - 1; b >= 0; --b) {
             uint4 t[kLongTailUnroll];
@@ -551,18 +563,6 @@ __global__ __launch_bounds__(kRowThreads) void loss_rows_long_kernel(
                     emit(t[u], idx);
                 }
             }
-        }
-#pragma unroll
-        for (int k = 0; k < NREG; ++k) {
-            float f[EPV];
-            unpack<DT>(v[k], f);
-            backward_vec<EPV, ENT>(f, neg_g, row_max, nls2, pz);
-            stream_store(out_row + (size_t)k * kSweepBytes + voff, pack<DT>(f));
-            if constexpr (ENT) __builtin_amdgcn_sched_barrier(0);  // one vector's temporaries at a time
-        }
-        for (int j = 0; j < lds_sweeps; ++j) {
-            const int idx = (NREG + j) * kRowThreads + tid;
-            if (idx < nvec) emit(*reinterpret_cast<const uint4 *>(my_stash + j * (int)kSweepBytes), idx);
         }
         // the chosen column gets +g from the thread that stored its vector (same thread, same address: program order)
         if (g != 0.0f && tid == ((y / EPV) & (kRowThreads - 1)))

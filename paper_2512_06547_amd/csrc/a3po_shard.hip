@@ -274,18 +274,20 @@ __global__ __launch_bounds__(kShardThreads) void shard_bwd_rows_kernel(
 }
 
 // ---------------------------------------------------------------------------------------
-// The same gradient slice in bursts.  A workgroup of 1024 threads takes an item of up to 19 x 1024 (float32: 16 x 1024)
-// sixteen-byte vectors - several whole shard rows when they are short, one row, or one column chunk
+// The same gradient slice in bursts.  A workgroup of 1024 threads takes an item of up to 7 x 1024
+// sixteen-byte vectors (112 KiB) - several whole shard rows when they are short, one row, or one column chunk
 // of a long row - loads all of it into registers, then computes and stores all of it: the
 // read-a-burst / write-a-burst rhythm of the fused row kernel, which HBM rewards over fine-grained
-// interleaving of loads and stores (about 5.9 against 5.0 TB/s on the same matrix).
+// interleaving of loads and stores (about 5.9 against 5.0 TB/s on the same matrix).  Nothing here needs a whole
+// row at once (the log-sum-exp is an input), so the burst length is free: 5 to 8 vectors per thread run 4-7 %
+// faster than the 19 a row of the fused kernel takes (measured on a full-width matrix, on a 1/8 shard of its own
+// and on eight column views), shorter ones are slower again.
 // Vector path only (16-byte aligned bases and stride).  Per-row scalars of the item's rows are
 // evaluated by the first threads and handed over through LDS (double-buffered by item parity, so one
 // barrier per item suffices); the chosen column's +g is added in registers by the thread that holds
 // that element.  Items come from the workspace's queue counter.
 constexpr int kBurstThreads = 1024;  // one workgroup per compute unit: halves and quarters (more, smaller bursts) are 6-8 % slower
-template <typename DT> struct BurstVec { static constexpr int value = 19; };  // vectors per thread and item
-template <> struct BurstVec<F32> { static constexpr int value = 16; };  // (what fits in 128 registers)
+constexpr int kBurstVec = 7;         // vectors per thread and item
 
 // hides a value's origin from the optimizer, so that index arithmetic is redone where it is needed
 // instead of being kept in registers across the bursts (there are none to spare)
@@ -322,7 +324,6 @@ __global__ __launch_bounds__(kBurstThreads) void shard_bwd_burst_kernel(
     int prox_mode, const WsHeader *__restrict__ hdr, unsigned int *queue, RowOutputs out, BurstShape sh)
 {
     constexpr int EPV = DT::kPerVec;
-    constexpr int kBurstVec = BurstVec<DT>::value;
     __shared__ float s_negg[2][kBurstThreads], s_lse[2][kBurstThreads];
     __shared__ int s_ycol[2][kBurstThreads];  // chosen column inside the shard, or -1
     __shared__ unsigned int s_next[2];
@@ -492,7 +493,7 @@ hipError_t launch_shard_combine(const a3po_shard_partial *parts, int32_t P, int6
 
 static BurstShape burst_shape(int64_t T, int64_t Vs, int64_t esz)
 {
-    const int64_t cap = (int64_t)(esz == 4 ? BurstVec<F32>::value : BurstVec<Bf16>::value) * kBurstThreads;
+    const int64_t cap = (int64_t)kBurstVec * kBurstThreads;
     BurstShape sh;
     sh.nvec_row = (int)((Vs * esz + 15) / 16);
     sh.align = sh.nvec_row >= kBurstAlignMinVec;

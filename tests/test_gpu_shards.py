@@ -111,7 +111,7 @@ def test_eight_even_shards_of_the_full_vocabulary_bf16(a3po):
     print(f"8 shards: N={st['n_tokens']} clipped={st['n_clipped']} excused={excused}")
 
 
-@pytest.mark.parametrize("bounds", [[0, 50000, 110008, 151936],     # 3 / 2 / 3 rows per burst
+@pytest.mark.parametrize("bounds", [[0, 50000, 110008, 151936],     # one row / two chunks of a row / one row per burst
                                     [0, 50004, 151936]])             # a partial last vector next to a neighbour's
                                                                      # columns; the second base is only 8-byte aligned
 def test_uneven_shards_bf16(a3po, bounds):
@@ -132,8 +132,8 @@ def test_uneven_shards_bf16(a3po, bounds):
     ("f32", 4099, [0, 1001, 2002, 4099]),            # odd widths: element-wise path
     ("bf16", 5001, [0, 3, 4, 2500, 5001]),           # tiny shards, one of a single column
     ("bf16", 70000, [0, 70000]),                     # a single shard is the whole vocabulary
-    ("f32", 70000, [0, 70000]),                      # 17,500 vectors per row: two column chunks per row
-    ("bf16", 163848, [0, 163848]),                   # 20,481 vectors per row: two chunks, the last vector whole
+    ("f32", 70000, [0, 70000]),                      # 17,500 vectors per row: three column chunks per row
+    ("bf16", 163848, [0, 163848]),                   # 20,481 vectors per row: three chunks, the last vector whole
     ("bf16", 45, [0, 21, 30, 37, 45]),               # a shard of exactly one 16-byte vector per row (8 columns)
     ("f32", 20, [0, 4, 8, 20]),                      # the same in fp32 (4 columns), next to a three-vector shard
 ])
@@ -155,7 +155,7 @@ def test_contiguous_shards(a3po, dtype, V, bounds):
     # 128 bytes (the position changes from row to row), a partial last vector
     ("bf16", 9003, 5, [0, 1032, 3120, 5208, 9003]),
     ("f32", 5000, 4, [0, 516, 1100, 5000]),
-    # a row of two column chunks that starts one vector into a line, next to a shard of one vector
+    # a row of several column chunks that starts one vector into a line, next to a shard of one vector
     ("bf16", 163856, 0, [0, 8, 163856]),
     # row stride a multiple of 128 bytes: the same position in every row
     ("bf16", 8192, 0, [0, 1096, 4112, 8192]),
