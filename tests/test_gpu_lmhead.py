@@ -193,12 +193,14 @@ def _check_backward(gpu, ref, ref_abs, what):
 
 
 @pytest.mark.parametrize("T,H,V,p_mask", [(300, 64, 1000, 0.8), (1, 64, 8, 1.0), (8192 + 300, 64, 512, 0.8),
-                                          (467, 192, 1344, 0.8), (16384, 256, 4096, 1.0)])
+                                          (467, 192, 1344, 0.8), (16384, 256, 4096, 1.0),
+                                          (65536 + 700, 64, 512, 1.0)])
 def test_fused_lmhead_loss_fwd_bwd(a3po, T, H, V, p_mask):
     """Whole path from hidden states against the un-rounded fp64 oracle.  The cases span one and several token
     chunks (8,192 tokens each), ragged tiles on every side, hidden sizes that are and are not a multiple of the
-    ring depth; the last one has every token counted with a non-zero advantage over two full chunks, so the
-    weight gradient accumulates dense contributions across chunks."""
+    ring depth; the last but one has every token counted with a non-zero advantage over two full chunks, the last
+    one nine chunks, i.e. more than the 65,536 tokens one weight-gradient contraction takes, so the second
+    contraction adds onto the result of the first."""
     r = np.random.default_rng(T + 7 * V)
     cur = 50
     h = bf16_bits(r.standard_normal((T, H)))
