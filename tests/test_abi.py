@@ -287,7 +287,8 @@ def test_library_needs_only_the_hip_runtime(lib):
     import subprocess
     if shutil.which("readelf") is None:
         pytest.skip("needs readelf")
-    out = subprocess.run(["readelf", "-d", B.lib_path()], check=True, capture_output=True, text=True).stdout
+    from paper_2512_06547_amd import binding
+    out = subprocess.run(["readelf", "-d", binding.lib_path()], check=True, capture_output=True, text=True).stdout
     needed = [ln.split("[")[1].split("]")[0] for ln in out.splitlines() if "(NEEDED)" in ln]
     assert any(n.startswith("libamdhip64") for n in needed)
     allowed = ("libamdhip64", "libstdc++", "libm.", "libgcc_s", "libc.", "ld-linux", "libpthread", "libdl", "librt")
