@@ -286,9 +286,9 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_nt_kernel(const GemmArgs g)
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
             const int r = (8 * j + wave) * 16 + drow;
-            // panels: every row of the band exists (padding), rows are 128 bytes apart
-            aoff[j] = g.a_panel ? (uint32_t)r * 128u + dpiece : (uint32_t)min(r, m_last) * lda2 + dpiece;
-            boff[j] = g.b_panel ? (uint32_t)r * 128u + dpiece : (uint32_t)min(r, n_last) * ldb2 + dpiece;
+            // panels: every row of the band exists (padding), rows are 64 bytes apart
+            aoff[j] = g.a_panel ? (uint32_t)r * 64u + dpiece : (uint32_t)min(r, m_last) * lda2 + dpiece;
+            boff[j] = g.b_panel ? (uint32_t)r * 64u + dpiece : (uint32_t)min(r, n_last) * ldb2 + dpiece;
         }
     };
     set_tile(r_p);
@@ -296,7 +296,7 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_nt_kernel(const GemmArgs g)
     auto refill = [&](int sl, int q, int u, int operand) {
         const uint32_t st = (uint32_t)(r_k + u);
         const uint32_t koff = st * (uint32_t)kDmaRowBytes;                 // rows: 64 bytes further along the row
-        const uint32_t poff = (st >> 1) * 32768u + (st & 1u) * 64u;        // panels: the next half block
+        const uint32_t poff = st * 16384u;                                 // panels: the next block
         char *dst = lds + sl * kDmaStageBytes + wave_s * 1024 + q * 8192;
         if (operand == 0) dma16(r_a + (g.a_panel ? poff : koff) + aoff[q], dst);
         else dma16(r_b + (g.b_panel ? poff : koff) + boff[q], dst + kDmaOperandBytes);

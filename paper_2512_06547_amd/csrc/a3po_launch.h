@@ -156,13 +156,14 @@ struct GemmArgs {
     int nxcd, ml_count; // filled in by the launcher from the device
 };
 
-// Panel layout of a bfloat16 operand of the contraction kernel: the matrix is cut into blocks of 256 rows x 64
-// contracted elements, each stored as 256 rows x 128 bytes = 32 KiB contiguous; blocks of one 256-row band follow
-// each other along K.  A stage of the kernel (256 rows x 32 elements) then reads half of one such block: one
-// contiguous 32 KiB region instead of 256 pieces a whole row apart.  Element offset of (row, k), kext = K extent:
+// Panel layout of a bfloat16 operand of the contraction kernel: the matrix is cut into blocks of 256 rows x 32
+// contracted elements - what one stage of the kernel consumes -, each stored as 256 rows x 64 bytes = 16 KiB
+// contiguous; blocks of one 256-row band follow each other along K.  A direct load of the kernel (16 rows x 64
+// bytes) is then 1 KiB of contiguous memory, eight whole 128-byte lines, instead of 16 half lines a row apart, and
+// no power-of-two row stride maps a stage onto a few memory channels.  Element offset of (row, k), kext = K extent:
 __host__ __device__ inline int64_t panel_offset(int64_t row, int64_t k, int64_t kext)
 {
-    return ((row >> 8) * (kext >> 6) + (k >> 6)) * 16384 + (row & 255) * 64 + (k & 63);
+    return ((row >> 8) * (kext >> 5) + (k >> 5)) * 8192 + (row & 255) * 32 + (k & 31);
 }
 inline size_t panel_elements(int64_t rows, int64_t kext) { return (size_t)((rows + 255) / 256 * 256) * (size_t)kext; }
 

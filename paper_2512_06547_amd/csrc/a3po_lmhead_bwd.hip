@@ -286,7 +286,7 @@ __global__ void lmhead_token_terms_kernel(const TokenRecord *__restrict__ record
 //   dz[t, v] = g_t ([v == y_t] - exp(z[t, v] - lse_t)),
 // rounded once to bfloat16 and written both token-major (dz: n rows, K extent ldv; the operand of the hidden-state
 // gradient) and vocabulary-major (dzt: V rows, K extent ldg, at token position col0; the operand of the weight
-// gradient), both in the contraction kernel's panel layout, in which a 64 x 64 tile is 8 KiB of contiguous memory.  A workgroup takes
+// gradient), both in the contraction kernel's panel layout, in which a 64 x 64 tile is two runs of 4 KiB.  A workgroup takes
 // a tile of 64 tokens x 64 vocabulary entries: 16-byte loads and 8-byte stores along the vocabulary, then through
 // LDS 16-byte stores along the tokens.  Token columns n .. (next multiple of 128) of dzt are written as zeros (they
 // pad the contraction over the tokens); a token with g = 0 gives an exactly zero row.  lse, g, ysel: the chunk's
