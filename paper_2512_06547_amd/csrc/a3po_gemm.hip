@@ -36,6 +36,13 @@
 // ml_count-tile row round); pair p = group * rounds + round, and each XCD takes a contiguous range of pairs, i.e.
 // it sweeps down the rows of one column group before it moves to the next.  With kEpiLse* a workgroup therefore
 // keeps its running (max, sum) in registers over a whole sweep and writes one partial per column per sweep.
+//
+// Operand and result layouts.  An operand is either row-major (row stride lda / ldb) or in panels of 256 rows x 32
+// contracted elements (a3po_launch.h), in which the 16 rows x 64 bytes of a direct load are 1 KiB of contiguous
+// memory.  The fp32 epilogues can store the tile transposed (element (m, n) at C[n ldc + m]): a lane's four
+// accumulator values of one MFMA tile are four consecutive m of one n, i.e. one 16-byte store without staging.
+// One of M, N, K may be known only on the device (DynCount): the launch is sized for the host's upper bound and
+// every workgroup reads the extent first; beyond it there is nothing to do and it returns.
 #include <mutex>
 
 #include "a3po_common.h"
