@@ -331,13 +331,14 @@ __global__ __launch_bounds__(256) void lmhead_dz_kernel(const float *__restrict_
         tile[vq + 3][tr] = (uint16_t)(hi >> 16);
     }
     __syncthreads();
-    // vocabulary-major: 64 entries x 128 bytes; thread -> entry tid / 4, 16 tokens (tid % 4) 16 ..
-    const int vr = tid >> 2, tq = (tid & 3) * 16;
+    // vocabulary-major: 64 entries x 2 panel blocks of 32 tokens; thread -> entry tid / 4, 8 tokens of each block, so
+    // that the four lanes of an entry write 64 contiguous bytes and a wavefront 1 KiB per store instruction
+    const int vr = tid >> 2, tq = (tid & 3) * 8;
     if (v0 + vr < V) {
 #pragma unroll
         for (int half = 0; half < 2; ++half) {
-            const uint4 w = *reinterpret_cast<const uint4 *>(&tile[vr][tq + 8 * half]);
-            *reinterpret_cast<uint4 *>(dzt + panel_offset(v0 + vr, col0 + t0 + tq + 8 * half, ldg)) = w;
+            const uint4 w = *reinterpret_cast<const uint4 *>(&tile[vr][32 * half + tq]);
+            *reinterpret_cast<uint4 *>(dzt + panel_offset(v0 + vr, col0 + t0 + 32 * half + tq, ldg)) = w;
         }
     }
 }
