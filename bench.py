@@ -366,7 +366,10 @@ def bench_lmhead(args, torch, a3po, synth, log, name=None, steps=None, warmup=No
                    "tokens": T, "hidden": H, "vocab": V, "counted_tokens": st["n_tokens"]},
         "roofline": {"bound": "mfma", "achieved": tf, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": tf / MFMA_BF16_PEAK_TFLOPS, "traffic": None, "flops": flops,
-                     "kernel": "whole step (gemm_nt_kernel x 3 per chunk of 8,192 counted tokens + lmhead_dz_kernel)"},
+                     "kernel": "whole step (gemm_nt_kernel x 3 per chunk of 8,192 counted tokens + lmhead_dz_kernel)",
+                     # not an achieved rate: the flops of a path that projects every token (6 T V H) over this
+                     # step's time, for comparison with such paths; this one skips the tokens outside the loss
+                     "dense_equivalent_tflops": 6.0 * T * V * H / (ms * 1e-3) / 1e12},
         "all_rows_counted": {"value": T * steps / one["dt"], "unit": "tokens/s", "ms_per_step": one["ms"],
                              "roofline": {"bound": "mfma", "achieved": one["tf"], "peak": MFMA_BF16_PEAK_TFLOPS,
                                           "unit": "TFLOP/s", "frac": one["tf"] / MFMA_BF16_PEAK_TFLOPS,
