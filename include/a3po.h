@@ -16,8 +16,8 @@
  *    a3po_stats (chosen id outside [0,V) => the token is treated as masked; negative
  *    staleness => alpha = 1).
  *  - No state is kept between calls: they are re-entrant and may be issued from several host threads
- *    on different streams, as long as they do not share output buffers or a workspace.  (The one-time
- *    set-ups that exist are thread-safe: the LDS limit of the kernels that use more than 64 KiB, and the address of the array that
+ *    on different streams, as long as they do not share output buffers or a workspace.  (The set-ups
+ *    that happen once per device are thread-safe: the LDS limit of the kernels that use more than 64 KiB, and the address of the array that
  *    a3po_loss_fwd_bwd_noalloc uses in place of a workspace.)
  *  - Logits are row-major [T, V] with a row stride of `ld` elements (ld >= V), float32
  *    or bfloat16.  Row t pairs with chosen[t]; any next-token shift is the caller's.

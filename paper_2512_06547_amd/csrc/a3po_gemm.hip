@@ -43,8 +43,6 @@
 // accumulator values of one MFMA tile are four consecutive m of one n, i.e. one 16-byte store without staging.
 // One of M, N, K may be known only on the device (DynCount): the launch is sized for the host's upper bound and
 // every workgroup reads the extent first; beyond it there is nothing to do and it returns.
-#include <mutex>
-
 #include "a3po_common.h"
 #include "a3po_launch.h"
 
@@ -518,14 +516,9 @@ static hipError_t launch_gemm_t(GemmArgs g, hipStream_t s)
     g.ml_count = gg.ml_count;
     const bool quad = g.K % (kDmaK * kDmaStages) == 0;
     auto *kernel = quad ? gemm_nt_kernel<EPI, true> : gemm_nt_kernel<EPI, false>;
-    // the kernels' dynamic LDS limit is raised once per process and variant, race-free
-    static std::once_flag once[2];
-    static hipError_t attr_err[2];
-    std::call_once(once[quad], [&] {
-        attr_err[quad] = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
-                                             hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLdsBytes);
-    });
-    if (attr_err[quad] != hipSuccess) return attr_err[quad];
+    static LdsLimitState lds_limit[2];  // (one per variant of this epilogue)
+    const hipError_t attr_err = ensure_lds_limit(reinterpret_cast<const void *>(kernel), kGemmLdsBytes, lds_limit[quad]);
+    if (attr_err != hipSuccess) return attr_err;
     if (EPI == kEpiLse || EPI == kEpiLseStore) {
         const int64_t n = (int64_t)gg.nxcd * gg.ml_count * g.partial_stride;
         hipLaunchKernelGGL(gemm_partials_init_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, g.partial, n);

@@ -1,6 +1,7 @@
 // Host-side launch interface between the C ABI (a3po_api.hip) and the kernel files.
 #pragma once
 
+#include <mutex>
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -166,6 +167,28 @@ __host__ __device__ inline int64_t panel_offset(int64_t row, int64_t k, int64_t 
     return ((row >> 8) * (kext >> 5) + (k >> 5)) * 8192 + (row & 255) * 32 + (k & 31);
 }
 inline size_t panel_elements(int64_t rows, int64_t kext) { return (size_t)((rows + 255) / 256 * 256) * (size_t)kext; }
+
+// Raises a kernel's dynamic-LDS limit once per device (the attribute belongs to the device's copy of the kernel),
+// race-free: the first call on a device sets it under the lock, later calls only look at the flag.  One state
+// object per kernel variant.
+struct LdsLimitState {
+    std::mutex lock;
+    bool done[64] = {};
+};
+inline hipError_t ensure_lds_limit(const void *kernel, int bytes, LdsLimitState &st)
+{
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> guard(st.lock);
+    if (!st.done[dev]) {
+        e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+        if (e != hipSuccess) return e;
+        st.done[dev] = true;
+    }
+    return hipSuccess;
+}
 
 struct GemmGrid {
     int nxcd, ml_count, blocks;

@@ -10,8 +10,6 @@
 // All loads of a row are issued before the first is consumed; the online (max, sum)
 // update of each vector then runs while later vectors are still in flight, and the
 // gradient of each vector is stored while the next is being computed.
-#include <mutex>
-
 #include "a3po_common.h"
 #include "a3po_launch.h"
 
@@ -758,15 +756,10 @@ static hipError_t launch_loss_rows_t(const LossArgs &a, hipStream_t s)
             // aligned but too long for the registers: registers + LDS + a streamed tail
             const RowOutputs lout = {a.logp_out, a.prox_out, a.ws_obj, a.ws_iw, a.ent_out, a.ws_flags};
             const WsHeader *lhdr = reinterpret_cast<const WsHeader *>(a.ws_header);
-            static std::once_flag once;
-            static hipError_t attr_err = hipSuccess;
-            std::call_once(once, [] {
-                attr_err = hipFuncSetAttribute(reinterpret_cast<const void *>(&loss_rows_long_kernel<DT, false>),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, kLongLdsBytes);
-                if (attr_err == hipSuccess)
-                    attr_err = hipFuncSetAttribute(reinterpret_cast<const void *>(&loss_rows_long_kernel<DT, true>),
-                                                   hipFuncAttributeMaxDynamicSharedMemorySize, kLongLdsBytes);
-            });
+            static LdsLimitState lds_limit[2];
+            const void *kernel = a.ent_out ? reinterpret_cast<const void *>(&loss_rows_long_kernel<DT, true>)
+                                           : reinterpret_cast<const void *>(&loss_rows_long_kernel<DT, false>);
+            const hipError_t attr_err = ensure_lds_limit(kernel, kLongLdsBytes, lds_limit[a.ent_out ? 1 : 0]);
             if (attr_err != hipSuccess) return attr_err;
             if (a.ent_out)
                 hipLaunchKernelGGL((loss_rows_long_kernel<DT, true>), dim3(grid), dim3(kRowThreads), kLongLdsBytes, s,
