@@ -84,6 +84,13 @@ def lib() -> ctypes.CDLL:
             raise FileNotFoundError(
                 f"{_LIB_PATH} is missing: build it with `python -m paper_2512_06547_amd.build` "
                 "(there is no fallback path)")
+        # PyTorch first: it brings its own copy of the HIP runtime, and the library must bind to that same copy (a
+        # stream or pointer created by one copy of the runtime means nothing to another); once PyTorch's is in the
+        # process, the library's dependency on the runtime resolves to it
+        try:
+            import torch  # noqa: F401
+        except ImportError:
+            pass
         handle = ctypes.CDLL(_LIB_PATH)
         for name, (res, args) in _SIGNATURES.items():
             fn = getattr(handle, name)

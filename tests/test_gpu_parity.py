@@ -511,3 +511,32 @@ def test_large_logits(a3po, dtype, V, sigma, offset):
     err = np.abs(dz - full["dz"])
     bound = rel * np.abs(full["dz"]) + (1e-5 + rep[:, None]) * np.abs(full["g"])[:, None]
     assert (err[ok] <= bound[ok]).all(), f"dlogits: max err {err[ok].max():.3e}"
+
+
+_LIBRARY_LOADED_BEFORE_TORCH = r"""
+import sys
+sys.path.insert(0, sys.argv[1])
+import paper_2512_06547_amd as a3po
+a3po.lib()                      # before this script has imported torch itself
+import numpy as np, torch
+import oracle
+r = np.random.default_rng(3)
+z = r.standard_normal((40, 1031)).astype(np.float32)
+y = r.integers(0, 1031, 40).astype(np.int32)
+lp, lse, _ = a3po.token_logprobs(torch.from_numpy(z).cuda(), torch.from_numpy(y).cuda())
+ref = oracle.token_logprobs(z.astype(np.float64), y)
+assert (np.abs(lp.cpu().numpy() - ref["logp"]) <= 1e-5 * np.abs(ref["logp"]) + 1e-5).all()
+print("ok")
+"""
+
+
+def test_library_may_be_loaded_before_torch_is_imported(a3po):
+    """The library and PyTorch must share one copy of the HIP runtime, whichever the caller touches first: a fresh
+    process loads the library, only then imports torch, and launches on torch's stream."""
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    p = subprocess.run([sys.executable, "-c", _LIBRARY_LOADED_BEFORE_TORCH, root], capture_output=True, text=True,
+                       timeout=240)
+    assert p.returncode == 0 and p.stdout.strip().endswith("ok"), p.stdout[-2000:] + p.stderr[-4000:]
