@@ -407,3 +407,43 @@ def test_fused_lmhead_loss_fwd_bwd_full_size(a3po):
     assert float(dw.abs().max()) > 0
     print(f"lmhead8b (b): {live} live tokens of {N} counted, norm-wise dh (sampled) {rh:.2e}, "
           f"max |column sum| / column abs sum of dW {float((col / col_abs).max()):.2e}")
+
+
+def test_fused_lmhead_loss_graph_capture_and_replay(a3po):
+    """The whole path from hidden states allocates nothing, never synchronises and clears its buffers with fill
+    kernels, so it can be recorded into a HIP graph: every replay reproduces the eager result bit for bit (with the
+    program's own eager work and synchronisations between the replays), also after an input changed in place."""
+    r = np.random.default_rng(77)
+    T, H, V = 9000, 128, 1000                      # two chunks of counted tokens, ragged tiles
+    h = torch.from_numpy(bf16_bits(r.standard_normal((T, H)))).view(torch.bfloat16).cuda()
+    W = torch.from_numpy(bf16_bits(r.standard_normal((V, H)) * 0.2)).view(torch.bfloat16).cuda()
+    y = torch.from_numpy(r.integers(0, V, T).astype(np.int32)).cuda()
+    m = torch.from_numpy((r.random(T) < 0.95).astype(np.uint8)).cuda()
+    ver = torch.from_numpy((50 - r.integers(0, 5, T)).astype(np.int32)).cuda()
+    adv = torch.from_numpy(r.standard_normal(T).astype(np.float32)).cuda()
+    lb = (a3po.fused_lmhead_logprob(h, W, y)[0] + 0.05 * torch.randn(T, device="cuda")).clamp(max=0.0)
+    keys = ("dhidden", "dweight", "logp", "logp_prox", "loss", "stats")
+    eager = a3po.fused_lmhead_loss_fwd_bwd(h, W, y, lb, ver, 50, adv, m, 0.2)
+    torch.cuda.synchronize()
+    want = {k: eager[k].clone() for k in keys}
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        out = a3po.fused_lmhead_loss_fwd_bwd(h, W, y, lb, ver, 50, adv, m, 0.2, workspace=eager["workspace"])
+    for rep in range(3):
+        for k in keys:
+            out[k].zero_()
+        a3po.fused_lmhead_logprob(h, W, y)          # eager work between the replays
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        for k in keys:
+            assert torch.equal(out[k].view(torch.uint8), want[k].view(torch.uint8)), (rep, k)
+    adv.mul_(-0.5)
+    m[::7] = 0                                      # fewer counted tokens: the replay reads the new count on the device
+    torch.cuda.synchronize()
+    g.replay()
+    torch.cuda.synchronize()
+    fresh = a3po.fused_lmhead_loss_fwd_bwd(h, W, y, lb, ver, 50, adv, m, 0.2)
+    torch.cuda.synchronize()
+    for k in keys:
+        assert torch.equal(out[k].view(torch.uint8), fresh[k].view(torch.uint8)), k
