@@ -362,15 +362,16 @@ int a3po_fused_lmhead_logprob(const void *hidden, const void *weight, int64_t T,
  * points give the same log pi_theta up to rounding order); the same tiles are also kept in fp32 inside the
  * workspace, for that chunk only, and the gradient rows dlogits are formed from them in fp32 and rounded once
  * to bfloat16, the operand type of the matrix cores.  The three contractions are this library's own kernel
- * (bfloat16 operands, fp32 accumulation); dweight is contracted over up to 65,536 counted tokens at a time,
- * accumulated in fp32 beyond that, and rounded to bfloat16 once.
+ * (bfloat16 operands, fp32 accumulation); dweight is contracted over up to 65,536 counted tokens at a time and
+ * rounded to bfloat16 once: straight from the accumulators when T <= 65,536, else after summing the contractions
+ * in fp32.
  * hidden, dhidden [T, H]; weight, dweight [V, H]: row-major, contiguous, bfloat16, 16-byte
  * aligned; H a positive multiple of 64, at most 2^20; V a multiple of 8 below 2^21; T below 2^22
  * (A3PO_E_SIZE otherwise).  Per-token arguments and outputs as in a3po_loss_fwd_bwd.
- * workspace: a3po_workspace_bytes(A3PO_WS_FUSED_LMHEAD_LOSS, T, V, H) bytes, 256-byte aligned: the fp32
- * accumulator of dweight, W^T, the gathered hidden rows and their transpose, a chunk of logits (fp32) and of
- * its gradient, and the vocabulary-major gradient of up to 65,536 tokens - about 6 V H + 6 T H + 6 * 8192 V +
- * 2 V min(T, 65536) bytes, 33 GB at T = 65,536, H = 4,096, V = 151,936.
+ * workspace: a3po_workspace_bytes(A3PO_WS_FUSED_LMHEAD_LOSS, T, V, H) bytes, 256-byte aligned: W^T, the gathered
+ * hidden rows and their transpose, a chunk of logits (fp32) and of its gradient, the vocabulary-major gradient of
+ * up to 65,536 tokens, and beyond that many tokens an fp32 accumulator of dweight - about 2 V H + 6 T H +
+ * 6 * 8192 V + 2 V min(T, 65536) (+ 4 V H) bytes, 30 GB at T = 65,536, H = 4,096, V = 151,936.
  */
 int a3po_fused_lmhead_loss_fwd_bwd(const void *hidden, const void *weight, int64_t T, int64_t H, int64_t V,
                                    const int32_t *chosen, const float *logp_behav,

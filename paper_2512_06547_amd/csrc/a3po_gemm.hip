@@ -185,6 +185,29 @@ __device__ __forceinline__ void store_tile_transposed(const f32x4_t (&acc)[8][4]
     }
 }
 
+// The transposed store in bfloat16: the four values of a register are rounded and leave as one 8-byte store.
+template <bool EDGE>
+__device__ __forceinline__ void store_tile_transposed_bf16(const f32x4_t (&acc)[8][4], uint16_t *C, int64_t ldc, int64_t m0,
+                                                           int64_t n0, int64_t M, int64_t N, int wm, int wn, int lane)
+{
+    const int col0 = wn * 64 + (lane & 15);
+    const int row0 = wm * 128 + 4 * (lane >> 4);
+    const int rows_left = (int)(M - m0 < kGemmTile ? M - m0 : kGemmTile);
+    const int cols_left = (int)(N - n0 < kGemmTile ? N - n0 : kGemmTile);
+#pragma unroll
+    for (int b = 0; b < 4; ++b) {
+        if (EDGE && col0 + b * 16 >= cols_left) continue;
+        uint16_t *col = C + (n0 + col0 + b * 16) * ldc + m0 + row0;
+#pragma unroll
+        for (int a = 0; a < 8; ++a) {
+            if (EDGE && row0 + a * 16 >= rows_left) continue;
+            *reinterpret_cast<uint2 *>(col + a * 16) =
+                make_uint2(pack_bf16x2(acc[a][b][0], acc[a][b][1]), pack_bf16x2(acc[a][b][2], acc[a][b][3]));
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    }
+}
+
 // The same for a tile that lies inside C, with 16-byte stores: 16 rows x 32 columns at a time go through a staging
 // tile in LDS that belongs to this wavefront alone (LDS instructions of one wavefront execute in order, so no waits
 // or barriers are needed between its writes and its reads) and leave as 8 rows x 128 bytes (fp32) or 8 rows x 64
@@ -415,7 +438,11 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_nt_kernel(const GemmArgs g)
             // tiles inside C leave with 16-byte stores (the launcher checks that rows of C start on 16 bytes);
             // only sums into C go element by element, through the memory side's adders
             float *stage_tile = reinterpret_cast<float *>(lds + kDmaRingBytes + kGemmRedBytes + wave_s * kStageBytes);
-            if (EPI != kEpiStoreBf16 && g.transposed != 0) {
+            if (EPI == kEpiStoreBf16 && g.transposed != 0) {
+                uint16_t *ct = reinterpret_cast<uint16_t *>(g.C);
+                if (edge) store_tile_transposed_bf16<true>(acc, ct, g.ldc, m0, n0, M, N, wm, wn, lane);
+                else store_tile_transposed_bf16<false>(acc, ct, g.ldc, m0, n0, M, N, wm, wn, lane);
+            } else if (g.transposed != 0) {
                 float *ct = reinterpret_cast<float *>(g.C);
                 const bool add = EPI == kEpiAccumF32 && g.accumulate != 0;
                 if (edge) store_tile_transposed<true>(acc, ct, g.ldc, m0, n0, M, N, wm, wn, lane, add);
@@ -537,8 +564,7 @@ hipError_t launch_gemm_nt(const GemmArgs &g, int epilogue, hipStream_t s)
         return hipErrorInvalidValue;
     if (g.dyn_dim != kDynNone && (!g.dyn.n || (g.dyn_dim == kDynK && g.K % 128 != 0))) return hipErrorInvalidValue;
     if ((g.a_panel && g.lda % 64 != 0) || (g.b_panel && g.ldb % 64 != 0)) return hipErrorInvalidValue;
-    if (g.transposed != 0 && (g.M % 4 != 0 || g.dyn_dim == kDynM || epilogue == kEpiStoreBf16 || epilogue == kEpiLse))
-        return hipErrorInvalidValue;
+    if (g.transposed != 0 && (g.M % 4 != 0 || g.dyn_dim == kDynM || epilogue == kEpiLse)) return hipErrorInvalidValue;
     if (epilogue != kEpiLse && (g.ldc % 8 != 0 || (reinterpret_cast<uintptr_t>(g.C) & 15) != 0)) return hipErrorInvalidValue;
     switch (epilogue) {
         case kEpiLse: return launch_gemm_t<kEpiLse>(g, s);

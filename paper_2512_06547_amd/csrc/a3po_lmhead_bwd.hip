@@ -15,8 +15,9 @@
 //      bfloat16 operands), written token-major and vocabulary-major in one pass over the stored logits;
 //   4. dh_chunk = dz W            (contraction over the vocabulary: dz token-major against W^T)
 // and once per group of kLmDwGroup chunks
-//   5. dW     += dz^T h_group     (contraction over the tokens: h^T against dz vocabulary-major; fp32
-//      accumulator across groups, rounded to bfloat16 once at the end).
+//   5. dW     += dz^T h_group     (contraction over the tokens: h^T against dz vocabulary-major; written in
+//      bfloat16 straight from the accumulators when one group holds every token, else summed in an fp32
+//      accumulator across groups and rounded to bfloat16 once at the end).
 // All three contractions are the kernel of a3po_gemm.hip, which wants the contracted index contiguous in both
 // operands; W^T and h^T are therefore written once per call.  6 N V H flops per step for N counted tokens: the
 // logits of a chunk are kept (4 bytes each, 5 GB for 8,192 tokens at V = 151,936) rather than recomputed, which
@@ -75,7 +76,8 @@ static LmBwdLayout lmhead_bwd_layout(int64_t T, int64_t V, int64_t H)
     l.ht = l.hc + up(t * h * 2);
     l.dhc = l.ht + up(panel_elements(H, l.ldt) * 2);
     l.dwacc = l.dhc + up(t * h * 2);
-    l.total = l.dwacc + up(v * h * sizeof(float));
+    // (the fp32 accumulator of dW exists only when the tokens may need more than one contraction)
+    l.total = l.dwacc + (T > kLmDwGroup * kLmBwdChunk ? up(v * h * sizeof(float)) : 0);
     return l;
 }
 
@@ -92,6 +94,15 @@ __global__ void f32_to_bf16_kernel(const float *__restrict__ src, uint16_t *__re
     } else if (i < n) {
         dst[i] = any ? (uint16_t)(pack_bf16x2(src[i], 0.0f) & 0xFFFFu) : (uint16_t)0;
     }
+}
+
+// dst = zeros when no token was counted (the weight-gradient contraction was then a no-op and wrote nothing)
+__global__ void zero_bf16_if_none_kernel(uint16_t *__restrict__ dst, size_t n, const int64_t *__restrict__ n_counted)
+{
+    if (*n_counted > 0) return;
+    const size_t i = ((size_t)blockIdx.x * blockDim.x + threadIdx.x) * 2;
+    if (i + 1 < n) *reinterpret_cast<uint32_t *>(dst + i) = 0u;
+    else if (i < n) dst[i] = 0;
 }
 
 // (fill kernels rather than hipMemsetAsync, so that the call can be captured into a HIP graph)
@@ -391,6 +402,8 @@ extern "C" int a3po_fused_lmhead_loss_fwd_bwd(const void *hidden, const void *we
     const uint16_t *h = static_cast<const uint16_t *>(hidden);
     const uint16_t *W = static_cast<const uint16_t *>(weight);
     const size_t nw = (size_t)V * (size_t)H;
+    // up to kLmDwGroup chunks of tokens: a single weight-gradient contraction, which stores dW in bfloat16 itself
+    const bool single_group = T <= kLmDwGroup * kLmBwdChunk;
 
     LossArgs a;
     a.z = nullptr;
@@ -516,19 +529,23 @@ extern "C" int a3po_fused_lmhead_loss_fwd_bwd(const void *hidden, const void *we
             bw.M = H;
             bw.N = V;
             bw.K = (gmax + kPadK - 1) / kPadK * kPadK;
-            bw.C = dwacc;
+            bw.C = single_group ? dweight : static_cast<void *>(dwacc);
             bw.ldc = H;
             bw.transposed = 1;
             bw.accumulate = g0 > 0;
             bw.dyn_dim = kDynK;
             bw.dyn = gcnt;
-            if (launch_gemm_nt(bw, kEpiAccumF32, s) != hipSuccess) return A3PO_E_LAUNCH;
+            if (launch_gemm_nt(bw, single_group ? kEpiStoreBf16 : kEpiAccumF32, s) != hipSuccess) return A3PO_E_LAUNCH;
         }
     }
     if (launch_loss_finish(a, s) != hipSuccess) return A3PO_E_LAUNCH;
     hipLaunchKernelGGL(scatter_rows_kernel, dim3((unsigned)((T + 3) / 4)), dim3(256), 0, s, dhc,
                        static_cast<uint16_t *>(dhidden), pos, T, H);
-    hipLaunchKernelGGL(f32_to_bf16_kernel, dim3((unsigned)((nw / 2 + 255) / 256)), dim3(256), 0, s, dwacc,
-                       static_cast<uint16_t *>(dweight), nw, n_counted);
+    if (single_group)
+        hipLaunchKernelGGL(zero_bf16_if_none_kernel, dim3((unsigned)((nw / 2 + 255) / 256)), dim3(256), 0, s,
+                           static_cast<uint16_t *>(dweight), nw, n_counted);
+    else
+        hipLaunchKernelGGL(f32_to_bf16_kernel, dim3((unsigned)((nw / 2 + 255) / 256)), dim3(256), 0, s, dwacc,
+                           static_cast<uint16_t *>(dweight), nw, n_counted);
     return hipGetLastError() == hipSuccess ? A3PO_OK : A3PO_E_LAUNCH;
 }
