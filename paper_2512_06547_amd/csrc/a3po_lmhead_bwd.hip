@@ -97,12 +97,15 @@ __global__ void f32_to_bf16_kernel(const float *__restrict__ src, uint16_t *__re
 }
 
 // dst = zeros when no token was counted (the weight-gradient contraction was then a no-op and wrote nothing)
+// (a fixed, small grid that strides over dst: in the usual case every workgroup only looks at the count)
 __global__ void zero_bf16_if_none_kernel(uint16_t *__restrict__ dst, size_t n, const int64_t *__restrict__ n_counted)
 {
     if (*n_counted > 0) return;
-    const size_t i = ((size_t)blockIdx.x * blockDim.x + threadIdx.x) * 2;
-    if (i + 1 < n) *reinterpret_cast<uint32_t *>(dst + i) = 0u;
-    else if (i < n) dst[i] = 0;
+    const size_t step = (size_t)gridDim.x * blockDim.x * 2;
+    for (size_t i = ((size_t)blockIdx.x * blockDim.x + threadIdx.x) * 2; i < n; i += step) {
+        if (i + 1 < n) *reinterpret_cast<uint32_t *>(dst + i) = 0u;
+        else dst[i] = 0;
+    }
 }
 
 // (fill kernels rather than hipMemsetAsync, so that the call can be captured into a HIP graph)
@@ -542,7 +545,7 @@ extern "C" int a3po_fused_lmhead_loss_fwd_bwd(const void *hidden, const void *we
     hipLaunchKernelGGL(scatter_rows_kernel, dim3((unsigned)((T + 3) / 4)), dim3(256), 0, s, dhc,
                        static_cast<uint16_t *>(dhidden), pos, T, H);
     if (single_group)
-        hipLaunchKernelGGL(zero_bf16_if_none_kernel, dim3((unsigned)((nw / 2 + 255) / 256)), dim3(256), 0, s,
+        hipLaunchKernelGGL(zero_bf16_if_none_kernel, dim3((unsigned)(nw / 512 < 2048 ? nw / 512 + 1 : 2048)), dim3(256), 0, s,
                            static_cast<uint16_t *>(dweight), nw, n_counted);
     else
         hipLaunchKernelGGL(f32_to_bf16_kernel, dim3((unsigned)((nw / 2 + 255) / 256)), dim3(256), 0, s, dwacc,
