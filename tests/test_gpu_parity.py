@@ -225,6 +225,18 @@ def test_rows_beyond_the_registers(a3po, dtype, V, pad):
     assert torch.equal(out["logp"], inp["logp"]) and torch.equal(out["loss"], inp["loss"])
 
 
+@pytest.mark.parametrize("dtype,V,L", [("bf16", 8000, 2000), ("bf16", 32000, 1500), ("f32", 16000, 1500)])
+def test_many_short_rows(a3po, dtype, V, L):
+    # rows of at most four sweeps run as two workgroups per compute unit, all of them claiming rows from the one
+    # queue: far more rows than workgroups, every element against the oracle
+    w = synth.WORKLOADS["tiny"].scaled(V=V, dtype=dtype, S=8, L=L, G=8, len_lo=L // 4, len_hi=L, sigma=3.0, boost=6.0,
+                                       boost_prob=0.5, noise_std=0.15, stale_max=6)
+    c = make_case(w)
+    out = run_gpu(a3po, c)
+    ref, st, excused = check_against_oracle(a3po, c, out)
+    assert 0 < st["n_tokens"] < c["T"]
+
+
 @pytest.mark.parametrize("dtype,V", [("f32", 32000), ("bf16", 151936), ("bf16", 4099), ("f32", 1001)])
 def test_in_place_gradient(a3po, dtype, V):
     w = synth.WORKLOADS["tiny"].scaled(V=V, dtype=dtype, S=4, L=8, len_lo=4, len_hi=8, noise_std=0.1)
